@@ -1,0 +1,184 @@
+/*
+ * osp.h - C ABI of the MI355X-native OSP synchronization step.
+ *
+ * OSP (Overlapped Synchronization Parallel) splits the per-iteration gradient
+ * synchronization of parameter-server training into two stages (Sec. 3.1):
+ * the important gradients G^i are synchronized right after back-propagation
+ * (Routine Synchronization, RS, "stage 1" here); the unimportant gradients
+ * G^u are synchronized while the next iteration computes (In-Computation
+ * Synchronization, ICS, "stage 2").  This library is the arithmetic of that
+ * step for N workers whose buffers all live on ONE GPU: no transport.
+ *
+ * Memory model
+ *   Every buffer is a flat fp32 "arena" of arena_elems elements; tensor
+ *   ("layer") l occupies [offset[l], offset[l]+numel[l]).  Elements outside
+ *   every tensor are padding and are never written by any call.
+ *   All pointers in osp_buffers and every `grads` argument are DEVICE
+ *   pointers owned by the caller and only borrowed: the library never
+ *   allocates or frees device memory.  All pointers in osp_config and the
+ *   gib/out arguments of osp_set_gib / osp_get_* are HOST pointers.
+ *   `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   Kernels are enqueued on it and the call returns without waiting, except
+ *   osp_bind, osp_set_gib and the osp_get_* calls, which synchronize it.
+ *
+ * Errors
+ *   Every call returns a status and never throws or aborts.  Argument and
+ *   ordering errors are detected on the host before anything is enqueued and
+ *   leave all buffers untouched.  osp_last_error gives a message.
+ *
+ * Order of calls in one iteration (Sec. 3.1, Sec. 4.1.2 Eq. 5, Sec. 4.5)
+ *   osp_ps_aggregate_update(1) -> { osp_apply_stage(1), osp_lgp_correct } ->
+ *   osp_ps_aggregate_update(2) -> osp_apply_stage(2) -> osp_split
+ *   A GIB must exist before any staged call (osp_set_gib with all layers
+ *   important makes iteration 1 a plain BSP step, Algorithm 1: S(G^u)_1 = 0).
+ *   Violations return OSP_ERR_BAD_STATE:
+ *     - stage 2 (aggregate or apply) before stage 1 of the same iteration;
+ *     - a new stage 1, stage 0 or osp_set_gib while a stage 2 is pending
+ *       (the ICS of iteration t must finish inside iteration t+1's compute
+ *       window, Eq. 5);
+ *     - osp_lgp_correct twice, or after osp_apply_stage(2);
+ *     - osp_split before the iteration's stage 2 (or stage 0) aggregate.
+ *   osp_split closes the iteration; calling it is optional (the old GIB stays).
+ */
+#ifndef OSP_H
+#define OSP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct osp_ctx osp_ctx;            /* opaque, host memory, library-owned */
+
+typedef enum {
+    OSP_OK = 0,
+    OSP_ERR_INVALID_ARG = 1,
+    OSP_ERR_BAD_STATE = 2,
+    OSP_ERR_NOMEM = 3,
+    OSP_ERR_HIP = 4,
+    OSP_ERR_UNSUPPORTED = 5
+} osp_status;
+
+/* Granularity of the Gradient Importance Bitmap (GIB, Sec. 3.2).
+ * LAYER is the paper's choice (Eq. 4): one flag per tensor.
+ * ELEMENT uses the per-parameter importance I_k = |G_k P_k| (text after Eq. 3). */
+enum { OSP_GRAN_LAYER = 0, OSP_GRAN_ELEMENT = 1 };
+
+typedef struct {
+    int32_t n_workers;             /* N >= 1 */
+    int32_t n_tensors;             /* L >= 1 */
+    const int64_t *numel;          /* [L], each > 0; copied */
+    const int64_t *offset;         /* [L], ascending, multiples of 4, ranges disjoint; copied */
+    int64_t arena_elems;           /* multiple of 4, >= offset[L-1] + numel[L-1] */
+    float lr;                      /* learning rate (Sec. 5.1.3: 0.1) */
+    float momentum;                /* SGD momentum mu, 0 <= mu < 1 */
+    const float *worker_weight;    /* [N] data share alpha_w of each worker (Sec. 2.1.1), or
+                                      NULL for equal shares 1/N; copied */
+    int32_t element_keys;          /* nonzero: osp_ps_aggregate_update also stores every
+                                      element's importance key, which makes
+                                      osp_split(OSP_GRAN_ELEMENT) legal (costs 4 B/element of
+                                      workspace and of traffic) */
+    int32_t chunk_elems;           /* work-chunk size in elements, multiple of 1024;
+                                      0 = library default */
+} osp_config;
+
+typedef struct {
+    float *ps_param;               /* [arena_elems] global parameters P on the PS */
+    float *ps_momentum;            /* [arena_elems] momentum buffer V on the PS */
+    float *worker_param;           /* worker w's replica starts at worker_param + w*stride */
+    int64_t worker_param_stride;   /* elements, multiple of 4, >= arena_elems */
+    void *workspace;               /* 256-byte aligned scratch, >= osp_workspace_bytes() */
+    size_t workspace_bytes;
+} osp_buffers;
+
+/* Create / destroy a context (host only; no GPU needed). *out is NULL on error. */
+osp_status osp_create(const osp_config *cfg, osp_ctx **out);
+void osp_destroy(osp_ctx *ctx);                                   /* NULL is fine */
+
+/* Bytes of device workspace osp_bind needs (chunk table, per-chunk importance
+ * partials, GIB, and with element_keys the key array, bitmap and histograms). */
+size_t osp_workspace_bytes(const osp_ctx *ctx);
+
+/* Attach device buffers; uploads the chunk table into the workspace and clears
+ * the GIB state (no GIB afterwards).  All pointers must be 16-byte aligned. */
+osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream);
+
+/* Change lr / momentum between iterations (Sec. 5.1.3: lr is halved every 10 epochs). */
+osp_status osp_set_hyper(osp_ctx *ctx, float lr, float momentum);
+
+/*
+ * Gradient split (Sec. 3.2 first challenge, Sec. 4.1.1, 4.1.2): computes the GIB
+ * of the NEXT iteration from this iteration's importances, which
+ * osp_ps_aggregate_update accumulated from the aggregated gradient and the PS
+ * parameters as they were before the update.
+ *   LAYER:   layers are ranked by (I^l, l) ascending, I^l = sum_{k in l}|g_k P_k|
+ *            (Eq. 4, summed in fp64); stage 2 = the longest prefix of the ranking
+ *            whose element count stays <= budget_elems.
+ *   ELEMENT: stage 2 = the budget_elems elements that come first in the order
+ *            (I_k ascending, arena index ascending); needs cfg.element_keys.
+ * 0 <= budget_elems <= number of parameters, else OSP_ERR_INVALID_ARG.
+ * NaN importances rank above +Inf (they stay in stage 1).
+ */
+osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream);
+
+/* Read the current GIB back (synchronizes `stream`).  Any of the three outputs
+ * may be NULL.  layer_gib: [L] bytes, 1 = important (stage 1), 0 = stage 2;
+ * only written when the current GIB is layer-granular.  elem_bitmap:
+ * [ceil(arena_elems/32)] words, bit k%32 of word k/32, 1 = important, padding
+ * bits 1; only written when it is element-granular.  n_stage2: elements in
+ * stage 2.  OSP_ERR_BAD_STATE if there is no GIB. */
+osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap,
+                       int64_t *n_stage2, void *stream);
+
+/* Install a GIB from the host (first iteration, tests, resume).  gib_host is
+ * uint8[L] for LAYER or uint32[ceil(arena_elems/32)] for ELEMENT, same encoding
+ * as osp_get_gib; padding bits are ignored.  Synchronizes `stream`. */
+osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void *stream);
+
+/*
+ * Parameter-server side of one stage (Sec. 2.1.1, per stage as in Sec. 3.1).
+ * For every element k of the stage (1 = important set, 2 = unimportant set,
+ * 0 = all elements, i.e. a plain BSP step, Sec. 4.3):
+ *     gbar = sum_w alpha_w g_{w,k}      fp32, workers in ascending order;
+ *                                       with equal shares: (sum_w g_{w,k}) * fl(1/N)
+ *     I_k  = |gbar * P_k|               PGP importance, P before this update
+ *     V_k  = mu V_k + gbar ;  P_k = P_k - lr V_k
+ * Every operation is a separately rounded fp32 operation (no fused
+ * multiply-add).  grads: DEVICE, read-only; worker w's arena starts at
+ * grads + w*worker_stride (elements, multiple of 4, >= arena_elems).
+ */
+osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
+                                   int64_t worker_stride, void *stream);
+
+/* LGP (Sec. 4.2, Eq. 6): for every stage-2 element and every worker,
+ * P_{w,k} = P_{w,k} - lr g_{w,k}: the stale parameter advances by the worker's
+ * own local gradient.  Stage-1 elements are not touched. */
+osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stride,
+                           void *stream);
+
+/* Workers receive the global parameters of a stage (Sec. 2.1.1); for stage 2
+ * this is the correction of Eq. 7, which replaces the local LGP estimate by the
+ * global result (taken as an overwrite, P_{w,k} = P_k).  stage: 1, 2, or 0 = both. */
+osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream);
+
+/* Inspection (each synchronizes `stream`): the fp64 layer importances I^l of
+ * the last osp_split(LAYER) into imp_host[L]; the element keys (bit pattern of
+ * I_k, NaN canonicalised to 0x7FC00000, padding 0xFFFFFFFF) into
+ * key_host[arena_elems] (needs cfg.element_keys). */
+osp_status osp_get_importance(osp_ctx *ctx, double *imp_host, void *stream);
+osp_status osp_get_keys(osp_ctx *ctx, uint32_t *key_host, void *stream);
+
+/* Message for the last error on this context ("" if none).  With ctx == NULL,
+ * the message of the last failed osp_create on this thread. */
+const char *osp_last_error(const osp_ctx *ctx);
+
+/* Geometry, for callers that size launches or report traffic. */
+int32_t osp_chunk_elems(const osp_ctx *ctx);
+int64_t osp_n_chunks(const osp_ctx *ctx);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OSP_H */

@@ -1,0 +1,233 @@
+"""Thin ctypes binding of libosp.so: argument marshalling only.
+
+Function names and argument order follow include/osp.h.  Every step of the
+synchronization path runs in the library's HIP kernels; this module only turns
+torch tensors into device pointers and statuses into exceptions.  There is no
+fallback: if the library is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libosp.so")
+
+OSP_OK, OSP_ERR_INVALID_ARG, OSP_ERR_BAD_STATE, OSP_ERR_NOMEM, OSP_ERR_HIP, OSP_ERR_UNSUPPORTED = range(6)
+OSP_GRAN_LAYER, OSP_GRAN_ELEMENT = 0, 1
+
+STATUS_NAMES = {0: "OSP_OK", 1: "OSP_ERR_INVALID_ARG", 2: "OSP_ERR_BAD_STATE",
+                3: "OSP_ERR_NOMEM", 4: "OSP_ERR_HIP", 5: "OSP_ERR_UNSUPPORTED"}
+
+
+class OspError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+class osp_config(C.Structure):
+    _fields_ = [("n_workers", C.c_int32), ("n_tensors", C.c_int32),
+                ("numel", C.POINTER(C.c_int64)), ("offset", C.POINTER(C.c_int64)),
+                ("arena_elems", C.c_int64), ("lr", C.c_float), ("momentum", C.c_float),
+                ("worker_weight", C.POINTER(C.c_float)),
+                ("element_keys", C.c_int32), ("chunk_elems", C.c_int32)]
+
+
+class osp_buffers(C.Structure):
+    _fields_ = [("ps_param", C.c_void_p), ("ps_momentum", C.c_void_p),
+                ("worker_param", C.c_void_p), ("worker_param_stride", C.c_int64),
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
+            "(there is no CPU fallback)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64 = C.c_void_p, C.c_int64
+    lib.osp_create.argtypes = [C.POINTER(osp_config), C.POINTER(vp)]
+    lib.osp_create.restype = C.c_int
+    lib.osp_destroy.argtypes = [vp]
+    lib.osp_destroy.restype = None
+    lib.osp_workspace_bytes.argtypes = [vp]
+    lib.osp_workspace_bytes.restype = C.c_size_t
+    lib.osp_bind.argtypes = [vp, C.POINTER(osp_buffers), vp]
+    lib.osp_bind.restype = C.c_int
+    lib.osp_set_hyper.argtypes = [vp, C.c_float, C.c_float]
+    lib.osp_set_hyper.restype = C.c_int
+    lib.osp_split.argtypes = [vp, C.c_int, i64, vp]
+    lib.osp_split.restype = C.c_int
+    lib.osp_get_gib.argtypes = [vp, vp, vp, C.POINTER(i64), vp]
+    lib.osp_get_gib.restype = C.c_int
+    lib.osp_set_gib.argtypes = [vp, C.c_int, vp, vp]
+    lib.osp_set_gib.restype = C.c_int
+    lib.osp_ps_aggregate_update.argtypes = [vp, C.c_int, vp, i64, vp]
+    lib.osp_ps_aggregate_update.restype = C.c_int
+    lib.osp_lgp_correct.argtypes = [vp, vp, i64, vp]
+    lib.osp_lgp_correct.restype = C.c_int
+    lib.osp_apply_stage.argtypes = [vp, C.c_int, vp]
+    lib.osp_apply_stage.restype = C.c_int
+    lib.osp_get_importance.argtypes = [vp, vp, vp]
+    lib.osp_get_importance.restype = C.c_int
+    lib.osp_get_keys.argtypes = [vp, vp, vp]
+    lib.osp_get_keys.restype = C.c_int
+    lib.osp_last_error.argtypes = [vp]
+    lib.osp_last_error.restype = C.c_char_p
+    lib.osp_chunk_elems.argtypes = [vp]
+    lib.osp_chunk_elems.restype = C.c_int32
+    lib.osp_n_chunks.argtypes = [vp]
+    lib.osp_n_chunks.restype = C.c_int64
+    return lib
+
+
+lib = _load()
+
+EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
+           "osp_split", "osp_get_gib", "osp_set_gib", "osp_ps_aggregate_update",
+           "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
+           "osp_last_error", "osp_chunk_elems", "osp_n_chunks"]
+
+
+def _ptr(t) -> int:
+    """Device (or host) address of a torch tensor / numpy array, or a raw int."""
+    if t is None:
+        return 0
+    if isinstance(t, int):
+        return t
+    if isinstance(t, np.ndarray):
+        return t.ctypes.data
+    return t.data_ptr()
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream
+    if isinstance(stream, int):
+        return stream
+    return stream.cuda_stream
+
+
+class Context:
+    """Owns one osp_ctx.  Methods carry the C entry points' names."""
+
+    def __init__(self, numel: Sequence[int], offset: Sequence[int], arena_elems: int,
+                 n_workers: int, lr: float, momentum: float,
+                 worker_weight: Optional[Sequence[float]] = None,
+                 element_keys: bool = False, chunk_elems: int = 0):
+        self._numel = np.ascontiguousarray(numel, dtype=np.int64)
+        self._offset = np.ascontiguousarray(offset, dtype=np.int64)
+        self._ww = None if worker_weight is None else np.ascontiguousarray(worker_weight, np.float32)
+        self.n_tensors = int(self._numel.shape[0])
+        self.n_workers = int(n_workers)
+        self.arena_elems = int(arena_elems)
+        self.n_words = (self.arena_elems + 31) // 32
+        cfg = osp_config(
+            self.n_workers, self.n_tensors,
+            self._numel.ctypes.data_as(C.POINTER(C.c_int64)),
+            self._offset.ctypes.data_as(C.POINTER(C.c_int64)),
+            self.arena_elems, lr, momentum,
+            None if self._ww is None else self._ww.ctypes.data_as(C.POINTER(C.c_float)),
+            1 if element_keys else 0, int(chunk_elems))
+        h = C.c_void_p()
+        st = lib.osp_create(C.byref(cfg), C.byref(h))
+        if st != OSP_OK:
+            raise OspError(st, lib.osp_last_error(None).decode())
+        self._h = h
+        self._keep = None
+
+    def close(self) -> None:
+        if getattr(self, "_h", None):
+            lib.osp_destroy(self._h)
+            self._h = None
+
+    __del__ = close
+
+    def _check(self, st: int) -> None:
+        if st != OSP_OK:
+            raise OspError(st, lib.osp_last_error(self._h).decode())
+
+    # ---- C entry points --------------------------------------------------
+    def osp_workspace_bytes(self) -> int:
+        return int(lib.osp_workspace_bytes(self._h))
+
+    def osp_chunk_elems(self) -> int:
+        return int(lib.osp_chunk_elems(self._h))
+
+    def osp_n_chunks(self) -> int:
+        return int(lib.osp_n_chunks(self._h))
+
+    def osp_bind(self, ps_param, ps_momentum, worker_param, worker_param_stride: int,
+                 workspace, workspace_bytes: Optional[int] = None, stream=None) -> None:
+        if workspace_bytes is None:
+            workspace_bytes = workspace.numel() * workspace.element_size()
+        buf = osp_buffers(_ptr(ps_param), _ptr(ps_momentum), _ptr(worker_param),
+                          int(worker_param_stride), _ptr(workspace), int(workspace_bytes))
+        self._check(lib.osp_bind(self._h, C.byref(buf), _stream(stream)))
+        self._keep = (ps_param, ps_momentum, worker_param, workspace)   # borrowed buffers stay alive
+
+    def osp_set_hyper(self, lr: float, momentum: float) -> None:
+        self._check(lib.osp_set_hyper(self._h, lr, momentum))
+
+    def osp_split(self, granularity: int, budget_elems: int, stream=None) -> None:
+        self._check(lib.osp_split(self._h, granularity, int(budget_elems), _stream(stream)))
+
+    def osp_set_gib(self, granularity: int, gib_host: np.ndarray, stream=None) -> None:
+        dt = np.uint8 if granularity == OSP_GRAN_LAYER else np.uint32
+        want = self.n_tensors if granularity == OSP_GRAN_LAYER else self.n_words
+        g = np.ascontiguousarray(gib_host, dtype=dt)
+        if g.shape != (want,):
+            raise ValueError(f"gib must have {want} entries")
+        self._check(lib.osp_set_gib(self._h, granularity, g.ctypes.data, _stream(stream)))
+
+    def osp_get_gib(self, stream=None):
+        """Returns (layer_gib uint8[L], elem_bitmap uint32[words], n_stage2); the array
+        that does not match the current granularity is left all-ones."""
+        layer = np.ones(self.n_tensors, np.uint8)
+        bits = np.full(self.n_words, 0xFFFFFFFF, np.uint32)
+        n2 = C.c_int64(0)
+        self._check(lib.osp_get_gib(self._h, layer.ctypes.data, bits.ctypes.data, C.byref(n2),
+                                    _stream(stream)))
+        return layer, bits, int(n2.value)
+
+    def osp_ps_aggregate_update(self, stage: int, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_ps_aggregate_update(self._h, stage, _ptr(grads), int(worker_stride),
+                                                _stream(stream)))
+
+    def osp_lgp_correct(self, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_lgp_correct(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
+
+    def osp_apply_stage(self, stage: int, stream=None) -> None:
+        self._check(lib.osp_apply_stage(self._h, stage, _stream(stream)))
+
+    def osp_get_importance(self, stream=None) -> np.ndarray:
+        imp = np.zeros(self.n_tensors, np.float64)
+        self._check(lib.osp_get_importance(self._h, imp.ctypes.data, _stream(stream)))
+        return imp
+
+    def osp_get_keys(self, stream=None) -> np.ndarray:
+        key = np.zeros(self.arena_elems, np.uint32)
+        self._check(lib.osp_get_keys(self._h, key.ctypes.data, _stream(stream)))
+        return key
+
+
+# module-level aliases with the C names, taking the context first
+def osp_split(ctx: Context, granularity, budget_elems, stream=None):
+    return ctx.osp_split(granularity, budget_elems, stream)
+
+
+def osp_ps_aggregate_update(ctx: Context, stage, grads, worker_stride, stream=None):
+    return ctx.osp_ps_aggregate_update(stage, grads, worker_stride, stream)
+
+
+def osp_lgp_correct(ctx: Context, grads, worker_stride, stream=None):
+    return ctx.osp_lgp_correct(grads, worker_stride, stream)
+
+
+def osp_apply_stage(ctx: Context, stage, stream=None):
+    return ctx.osp_apply_stage(stage, stream)

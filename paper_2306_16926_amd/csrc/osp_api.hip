@@ -1,0 +1,634 @@
+// C ABI of the OSP synchronization step (declared in include/osp.h):
+// context, argument validation, the per-iteration order-of-calls state machine,
+// workspace layout, and the kernel launches.  Host logic here never touches
+// the GPU before osp_bind, so creation, validation and ordering errors can be
+// exercised on a machine without one.
+#include "../../include/osp.h"
+#include "osp_split_kernels.hpp"
+
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+using namespace osp;
+
+namespace {
+
+constexpr int kDefaultChunkElems = 4096;
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+thread_local std::string g_create_error;
+
+} // namespace
+
+struct osp_ctx {
+    // ---- configuration (copied) ----
+    int n_workers = 0, n_tensors = 0;
+    std::vector<long long> numel, offset;
+    long long arena = 0, n_params = 0;
+    float lr = 0.f, mu = 0.f;
+    bool weighted = false;
+    std::vector<float> weights;
+    bool element_keys = false;
+    int chunk_elems = kDefaultChunkElems;
+
+    // ---- derived host tables ----
+    std::vector<Chunk> chunks;
+    std::vector<int> layer_chunk_begin;        // [L+1]
+    long long n_vec = 0, n_words = 0, n_tiles = 0;
+
+    // ---- workspace layout (byte offsets) ----
+    size_t off_chunks = 0, off_lcb = 0, off_numel = 0, off_partial = 0, off_imp = 0,
+           off_order = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
+           off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
+
+    // ---- bound buffers ----
+    bool bound = false;
+    float *P = nullptr, *V = nullptr, *Pw = nullptr;
+    long long param_stride = 0;
+    char *ws = nullptr;
+
+    // ---- iteration state machine ----
+    bool have_gib = false;
+    int gib_gran = OSP_GRAN_LAYER;
+    bool agg1 = false, agg2 = false, single_pass = false, lgp_done = false, applied2 = false;
+    bool have_layer_importance = false;
+
+    std::string err;
+
+    template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
+    Chunk *d_chunks() const { return at<Chunk>(off_chunks); }
+    int *d_lcb() const { return at<int>(off_lcb); }
+    long long *d_numel() const { return at<long long>(off_numel); }
+    double *d_partial(int slot) const { return at<double>(off_partial) + (size_t)slot * chunks.size(); }
+    double *d_imp() const { return at<double>(off_imp); }
+    int *d_order() const { return at<int>(off_order); }
+    uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
+    SplitState *d_state() const { return at<SplitState>(off_state); }
+    float *d_weights() const { return at<float>(off_weights); }
+    uint32_t *d_key() const { return at<uint32_t>(off_key); }
+    uint32_t *d_bitmap() const { return at<uint32_t>(off_bitmap); }
+    unsigned long long *d_hist(int pass) const
+    {
+        return at<unsigned long long>(off_hist) + (size_t)pass * kRadixBins;
+    }
+    unsigned int *d_tile_ties() const { return at<unsigned int>(off_tile_ties); }
+    unsigned long long *d_tile_before() const { return at<unsigned long long>(off_tile_before); }
+};
+
+namespace {
+
+osp_status fail(osp_ctx *ctx, osp_status s, const char *fmt, ...)
+{
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    if (ctx)
+        ctx->err = buf;
+    else
+        g_create_error = buf;
+    return s;
+}
+
+osp_status hip_fail(osp_ctx *ctx, hipError_t e, const char *what)
+{
+    return fail(ctx, OSP_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+#define OSP_HIP(call)                                                                          \
+    do {                                                                                       \
+        hipError_t e_ = (call);                                                                \
+        if (e_ != hipSuccess)                                                                  \
+            return hip_fail(ctx, e_, #call);                                                   \
+    } while (0)
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+void layout_workspace(osp_ctx *c)
+{
+    size_t o = 0;
+    auto take = [&](size_t bytes) {
+        size_t at = o;
+        o = align_up(o + bytes);
+        return at;
+    };
+    const size_t nc = c->chunks.size();
+    c->off_chunks = take(nc * sizeof(Chunk));
+    c->off_lcb = take((size_t)(c->n_tensors + 1) * sizeof(int));
+    c->off_numel = take((size_t)c->n_tensors * sizeof(long long));
+    c->off_partial = take(2 * nc * sizeof(double));
+    c->off_imp = take((size_t)c->n_tensors * sizeof(double));
+    c->off_order = take((size_t)c->n_tensors * sizeof(int));
+    c->off_gib = take((size_t)c->n_tensors);
+    c->off_state = take(sizeof(SplitState));
+    c->off_weights = take((size_t)c->n_workers * sizeof(float));
+    if (c->element_keys) {
+        c->off_key = take((size_t)c->arena * sizeof(uint32_t));
+        c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
+        c->off_hist = take((size_t)3 * kRadixBins * sizeof(unsigned long long));
+        c->off_tile_ties = take((size_t)c->n_tiles * sizeof(unsigned int));
+        c->off_tile_before = take((size_t)c->n_tiles * sizeof(unsigned long long));
+    }
+    c->ws_bytes = o;
+}
+
+osp_status check_grads(osp_ctx *ctx, const float *grads, int64_t stride)
+{
+    if (!grads)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "grads is NULL");
+    if (!aligned16(grads))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "grads must be 16-byte aligned");
+    if (stride < ctx->arena || stride % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG,
+                    "worker_stride %lld must be a multiple of 4 and >= arena_elems %lld",
+                    (long long)stride, ctx->arena);
+    return OSP_OK;
+}
+
+bool stage2_pending(const osp_ctx *c) { return c->agg1 && !c->agg2; }
+
+osp_status launch_check(osp_ctx *ctx, const char *what)
+{
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess)
+        return hip_fail(ctx, e, what);
+    return OSP_OK;
+}
+
+} // namespace
+
+extern "C" {
+
+osp_status osp_create(const osp_config *cfg, osp_ctx **out)
+{
+    if (out)
+        *out = nullptr;
+    osp_ctx *ctx = nullptr;                    // fail() records into the thread-local slot
+    if (!cfg || !out)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "cfg and out must not be NULL");
+    if (cfg->n_workers < 1)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "n_workers must be >= 1 (got %d)", cfg->n_workers);
+    if (cfg->n_tensors < 1)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "n_tensors must be >= 1 (got %d)", cfg->n_tensors);
+    if (!cfg->numel || !cfg->offset)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "numel and offset must not be NULL");
+    if (cfg->arena_elems <= 0 || cfg->arena_elems % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "arena_elems must be a positive multiple of 4");
+    if (!(cfg->lr == cfg->lr) || !(cfg->momentum >= 0.f && cfg->momentum < 1.f))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "lr must be a number and 0 <= momentum < 1");
+    int chunk = cfg->chunk_elems == 0 ? kDefaultChunkElems : cfg->chunk_elems;
+    if (chunk < kStride || chunk % kStride != 0 || chunk > (1 << 24))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "chunk_elems must be a multiple of %d in [%d, %d]",
+                    kStride, kStride, 1 << 24);
+    long long prev_end = 0, total = 0;
+    for (int l = 0; l < cfg->n_tensors; ++l) {
+        const long long n = cfg->numel[l], o = cfg->offset[l];
+        if (n <= 0)
+            return fail(ctx, OSP_ERR_INVALID_ARG, "numel[%d] must be > 0", l);
+        if (o < prev_end || o % 4 != 0)
+            return fail(ctx, OSP_ERR_INVALID_ARG,
+                        "offset[%d]=%lld must be a multiple of 4 and not overlap tensor %d", l, o,
+                        l - 1);
+        if (n > cfg->arena_elems - o)
+            return fail(ctx, OSP_ERR_INVALID_ARG, "tensor %d ends past arena_elems", l);
+        prev_end = o + n;
+        total += n;
+    }
+    osp_ctx *c = new (std::nothrow) osp_ctx;
+    if (!c)
+        return fail(ctx, OSP_ERR_NOMEM, "out of host memory");
+    try {
+        c->n_workers = cfg->n_workers;
+        c->n_tensors = cfg->n_tensors;
+        c->numel.assign(cfg->numel, cfg->numel + cfg->n_tensors);
+        c->offset.assign(cfg->offset, cfg->offset + cfg->n_tensors);
+        c->arena = cfg->arena_elems;
+        c->n_params = total;
+        c->lr = cfg->lr;
+        c->mu = cfg->momentum;
+        c->weighted = cfg->worker_weight != nullptr;
+        if (c->weighted)
+            c->weights.assign(cfg->worker_weight, cfg->worker_weight + cfg->n_workers);
+        else
+            c->weights.assign((size_t)cfg->n_workers, 1.0f / (float)cfg->n_workers);
+        c->element_keys = cfg->element_keys != 0;
+        c->chunk_elems = chunk;
+        c->layer_chunk_begin.reserve((size_t)c->n_tensors + 1);
+        for (int l = 0; l < c->n_tensors; ++l) {
+            c->layer_chunk_begin.push_back((int)c->chunks.size());
+            for (long long b = 0; b < c->numel[l]; b += chunk) {
+                Chunk k;
+                k.start = c->offset[l] + b;
+                k.len = (int)(c->numel[l] - b < chunk ? c->numel[l] - b : chunk);
+                k.layer = l;
+                c->chunks.push_back(k);
+                if (c->chunks.size() > (size_t)0x7FFFFFF0) {
+                    delete c;
+                    return fail(ctx, OSP_ERR_UNSUPPORTED, "more than 2^31 chunks; raise chunk_elems");
+                }
+            }
+        }
+        c->layer_chunk_begin.push_back((int)c->chunks.size());
+    } catch (const std::bad_alloc &) {
+        delete c;
+        return fail(ctx, OSP_ERR_NOMEM, "out of host memory");
+    }
+    c->n_vec = c->arena / 4;
+    c->n_words = (c->arena + 31) / 32;
+    c->n_tiles = (c->arena + kSelTile - 1) / kSelTile;
+    layout_workspace(c);
+    *out = c;
+    return OSP_OK;
+}
+
+void osp_destroy(osp_ctx *ctx) { delete ctx; }
+
+size_t osp_workspace_bytes(const osp_ctx *ctx) { return ctx ? ctx->ws_bytes : 0; }
+
+int32_t osp_chunk_elems(const osp_ctx *ctx) { return ctx ? ctx->chunk_elems : 0; }
+
+int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->chunks.size() : 0; }
+
+const char *osp_last_error(const osp_ctx *ctx)
+{
+    return ctx ? ctx->err.c_str() : g_create_error.c_str();
+}
+
+osp_status osp_set_hyper(osp_ctx *ctx, float lr, float momentum)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!(lr == lr) || !(momentum >= 0.f && momentum < 1.f))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "lr must be a number and 0 <= momentum < 1");
+    if (stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "hyper-parameters cannot change between the two stages");
+    ctx->lr = lr;
+    ctx->mu = momentum;
+    return OSP_OK;
+}
+
+osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!buf)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "buffers is NULL");
+    if (!buf->ps_param || !buf->ps_momentum || !buf->worker_param || !buf->workspace)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "ps_param, ps_momentum, worker_param and workspace must not be NULL");
+    if (!aligned16(buf->ps_param) || !aligned16(buf->ps_momentum) || !aligned16(buf->worker_param))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "parameter buffers must be 16-byte aligned");
+    if (reinterpret_cast<uintptr_t>(buf->workspace) % kAlign != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "workspace must be 256-byte aligned");
+    if (buf->worker_param_stride < ctx->arena || buf->worker_param_stride % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG,
+                    "worker_param_stride must be a multiple of 4 and >= arena_elems");
+    if (buf->workspace_bytes < ctx->ws_bytes)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "workspace has %zu bytes, %zu needed",
+                    buf->workspace_bytes, ctx->ws_bytes);
+    if (stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "cannot rebind while a stage 2 is pending");
+    hipStream_t s = (hipStream_t)stream;
+    ctx->bound = false;
+    ctx->ws = (char *)buf->workspace;
+    OSP_HIP(hipMemcpyAsync(ctx->d_chunks(), ctx->chunks.data(), ctx->chunks.size() * sizeof(Chunk),
+                           hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_lcb(), ctx->layer_chunk_begin.data(),
+                           ctx->layer_chunk_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_numel(), ctx->numel.data(), ctx->numel.size() * sizeof(long long),
+                           hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_weights(), ctx->weights.data(), ctx->weights.size() * sizeof(float),
+                           hipMemcpyHostToDevice, s));
+    // partials, importances, ranking, GIB, split state start at zero
+    const size_t zero_bytes = ctx->off_weights - ctx->off_partial;
+    k_fill_u32<<<256, kBlock, 0, s>>>(ctx->at<uint32_t>(ctx->off_partial),
+                                      (long long)(zero_bytes / 4), 0u);
+    if (ctx->element_keys) {
+        // padding keys stay 0xFFFFFFFF for good: above every real key, never selected
+        k_fill_u32<<<1024, kBlock, 0, s>>>(ctx->d_key(), ctx->arena, 0xFFFFFFFFu);
+        k_fill_u32<<<256, kBlock, 0, s>>>(ctx->d_bitmap(), ctx->n_words, 0xFFFFFFFFu);
+    }
+    osp_status st = launch_check(ctx, "bind fill kernels");
+    if (st != OSP_OK)
+        return st;
+    OSP_HIP(hipStreamSynchronize(s));
+    ctx->P = buf->ps_param;
+    ctx->V = buf->ps_momentum;
+    ctx->Pw = buf->worker_param;
+    ctx->param_stride = buf->worker_param_stride;
+    ctx->bound = true;
+    ctx->have_gib = false;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    ctx->have_layer_importance = false;
+    return OSP_OK;
+}
+
+osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (granularity != OSP_GRAN_LAYER && granularity != OSP_GRAN_ELEMENT)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "unknown granularity %d", granularity);
+    if (!gib_host)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "gib_host is NULL");
+    if (granularity == OSP_GRAN_ELEMENT && !ctx->element_keys)
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "element granularity needs cfg.element_keys");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "the GIB cannot change while a stage 2 is pending");
+    hipStream_t s = (hipStream_t)stream;
+    long long n2 = 0;
+    if (granularity == OSP_GRAN_LAYER) {
+        const uint8_t *g = (const uint8_t *)gib_host;
+        std::vector<uint8_t> norm((size_t)ctx->n_tensors);
+        for (int l = 0; l < ctx->n_tensors; ++l) {
+            norm[l] = g[l] ? 1 : 0;
+            if (!g[l])
+                n2 += ctx->numel[l];
+        }
+        OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
+        OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
+        OSP_HIP(hipStreamSynchronize(s));
+    } else {
+        const uint32_t *g = (const uint32_t *)gib_host;
+        std::vector<uint32_t> bits;
+        try {
+            bits.assign((size_t)ctx->n_words, 0xFFFFFFFFu);
+        } catch (const std::bad_alloc &) {
+            return fail(ctx, OSP_ERR_NOMEM, "out of host memory");
+        }
+        for (int l = 0; l < ctx->n_tensors; ++l)       // padding bits stay 1
+            for (long long k = ctx->offset[l]; k < ctx->offset[l] + ctx->numel[l]; ++k)
+                if (!((g[k >> 5] >> (k & 31)) & 1u)) {
+                    bits[(size_t)(k >> 5)] &= ~(1u << (k & 31));
+                    ++n2;
+                }
+        OSP_HIP(hipMemcpyAsync(ctx->d_bitmap(), bits.data(), bits.size() * sizeof(uint32_t),
+                               hipMemcpyHostToDevice, s));
+        OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
+        OSP_HIP(hipStreamSynchronize(s));
+    }
+    ctx->have_gib = true;
+    ctx->gib_gran = granularity;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    return OSP_OK;
+}
+
+osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap, int64_t *n_stage2,
+                       void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!ctx->bound || !ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "no GIB yet (osp_set_gib or osp_split first)");
+    hipStream_t s = (hipStream_t)stream;
+    long long n2 = 0;
+    if (layer_gib && ctx->gib_gran == OSP_GRAN_LAYER)
+        OSP_HIP(hipMemcpyAsync(layer_gib, ctx->d_gib(), (size_t)ctx->n_tensors, hipMemcpyDeviceToHost, s));
+    if (elem_bitmap && ctx->gib_gran == OSP_GRAN_ELEMENT)
+        OSP_HIP(hipMemcpyAsync(elem_bitmap, ctx->d_bitmap(), (size_t)ctx->n_words * sizeof(uint32_t),
+                               hipMemcpyDeviceToHost, s));
+    OSP_HIP(hipMemcpyAsync(&n2, &ctx->d_state()->n_stage2, sizeof n2, hipMemcpyDeviceToHost, s));
+    OSP_HIP(hipStreamSynchronize(s));
+    if (n_stage2)
+        *n_stage2 = n2;
+    return OSP_OK;
+}
+
+osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
+                                   int64_t worker_stride, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (stage < 0 || stage > 2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 0, 1 or 2 (got %d)", stage);
+    osp_status st = check_grads(ctx, grads, worker_stride);
+    if (st != OSP_OK)
+        return st;
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (stage != 0 && !ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB (osp_set_gib or osp_split)");
+    if (stage != 2 && stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE,
+                    "stage 2 of the previous iteration is still pending (ICS must complete first)");
+    if (stage == 2 && !stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 needs this iteration's stage 1 first");
+
+    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
+    AggArgs a;
+    a.chunks = ctx->d_chunks();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.P = ctx->P;
+    a.V = ctx->V;
+    a.grads = grads;
+    a.worker_stride = worker_stride;
+    a.weights = ctx->d_weights();
+    a.partial = ctx->d_partial(stage == 2 ? 1 : 0);
+    a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+    a.n_workers = ctx->n_workers;
+    a.stage = stage;
+    a.inv_n = 1.0f / (float)ctx->n_workers;
+    a.lr = ctx->lr;
+    a.mu = ctx->mu;
+    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
+    hipStream_t s = (hipStream_t)stream;
+    const int variant = (masked ? 4 : 0) | (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    switch (variant) {
+    case 0: k_aggregate_update<false, false, false><<<grid, block, 0, s>>>(a); break;
+    case 1: k_aggregate_update<false, false, true><<<grid, block, 0, s>>>(a); break;
+    case 2: k_aggregate_update<false, true, false><<<grid, block, 0, s>>>(a); break;
+    case 3: k_aggregate_update<false, true, true><<<grid, block, 0, s>>>(a); break;
+    case 5: k_aggregate_update<true, false, true><<<grid, block, 0, s>>>(a); break;
+    case 7: k_aggregate_update<true, true, true><<<grid, block, 0, s>>>(a); break;
+    default:
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
+    }
+    st = launch_check(ctx, "k_aggregate_update");
+    if (st != OSP_OK)
+        return st;
+    if (stage == 1) {
+        ctx->agg1 = true;
+        ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    } else if (stage == 2) {
+        ctx->agg2 = true;
+    } else {
+        ctx->agg1 = ctx->agg2 = ctx->single_pass = true;
+        ctx->lgp_done = ctx->applied2 = false;
+    }
+    return OSP_OK;
+}
+
+osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    osp_status st = check_grads(ctx, grads, worker_stride);
+    if (st != OSP_OK)
+        return st;
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "LGP needs a GIB");
+    if (!ctx->agg1 || ctx->single_pass)
+        return fail(ctx, OSP_ERR_BAD_STATE, "LGP belongs after this iteration's stage 1 aggregate");
+    if (ctx->lgp_done)
+        return fail(ctx, OSP_ERR_BAD_STATE, "LGP already applied in this iteration");
+    if (ctx->applied2)
+        return fail(ctx, OSP_ERR_BAD_STATE, "LGP after the stage-2 correction would undo it");
+    LgpArgs a;
+    a.chunks = ctx->d_chunks();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.Pw = ctx->Pw;
+    a.param_stride = ctx->param_stride;
+    a.grads = grads;
+    a.worker_stride = worker_stride;
+    a.n_workers = ctx->n_workers;
+    a.lr = ctx->lr;
+    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
+    hipStream_t s = (hipStream_t)stream;
+    if (ctx->gib_gran == OSP_GRAN_ELEMENT)
+        k_lgp_correct<true><<<grid, block, 0, s>>>(a);
+    else
+        k_lgp_correct<false><<<grid, block, 0, s>>>(a);
+    st = launch_check(ctx, "k_lgp_correct");
+    if (st != OSP_OK)
+        return st;
+    ctx->lgp_done = true;
+    return OSP_OK;
+}
+
+osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (stage < 0 || stage > 2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 0, 1 or 2 (got %d)", stage);
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (stage != 0 && !ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB");
+    if (stage == 1 && !ctx->agg1)
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 1 has not been aggregated in this iteration");
+    if (stage != 1 && !(ctx->agg1 && ctx->agg2))
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
+    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
+    ApplyArgs a;
+    a.chunks = ctx->d_chunks();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.P = ctx->P;
+    a.Pw = ctx->Pw;
+    a.param_stride = ctx->param_stride;
+    a.n_workers = ctx->n_workers;
+    a.stage = stage;
+    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
+    hipStream_t s = (hipStream_t)stream;
+    if (masked)
+        k_apply_stage<true><<<grid, block, 0, s>>>(a);
+    else
+        k_apply_stage<false><<<grid, block, 0, s>>>(a);
+    osp_status st = launch_check(ctx, "k_apply_stage");
+    if (st != OSP_OK)
+        return st;
+    if (stage != 1)
+        ctx->applied2 = true;
+    return OSP_OK;
+}
+
+osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (granularity != OSP_GRAN_LAYER && granularity != OSP_GRAN_ELEMENT)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "unknown granularity %d", granularity);
+    if (budget_elems < 0 || budget_elems > ctx->n_params)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "budget %lld outside [0, %lld]",
+                    (long long)budget_elems, ctx->n_params);
+    if (granularity == OSP_GRAN_ELEMENT && !ctx->element_keys)
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "element granularity needs cfg.element_keys");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!(ctx->agg1 && ctx->agg2))
+        return fail(ctx, OSP_ERR_BAD_STATE,
+                    "split needs the importances of a complete iteration (stage 2 or stage 0 aggregate)");
+    hipStream_t s = (hipStream_t)stream;
+    if (granularity == OSP_GRAN_LAYER) {
+        const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
+        k_layer_importance<<<ctx->n_tensors, kBlock, 0, s>>>(ctx->d_lcb(), ctx->d_partial(0),
+                                                             ctx->d_partial(1), ctx->d_gib(), mode,
+                                                             ctx->d_imp());
+        k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_imp(), ctx->d_numel(),
+                                              (long long)budget_elems, ctx->d_gib(), ctx->d_order(),
+                                              ctx->d_state());
+        ctx->have_layer_importance = true;
+    } else {
+        const long long nv = ctx->n_vec;
+        long long want = (nv + kBlock - 1) / kBlock;
+        const unsigned hgrid = (unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048);
+        k_fill_u32<<<24, kBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
+                                         (long long)3 * kRadixBins * 2, 0u);
+        k_select_histogram<0><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));
+        k_select_pick<<<1, kBlock, 0, s>>>(0, (long long)budget_elems, ctx->d_hist(0), ctx->d_state());
+        k_select_histogram<1><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(1));
+        k_select_pick<<<1, kBlock, 0, s>>>(1, (long long)budget_elems, ctx->d_hist(1), ctx->d_state());
+        k_select_histogram<2><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2));
+        k_select_pick<<<1, kBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state());
+        const unsigned tiles = (unsigned)ctx->n_tiles;
+        k_select_count_ties<<<tiles, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
+        k_select_scan_tiles<<<1, kBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_tile_before());
+        k_select_write_bitmap<<<tiles, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
+                                                      ctx->d_tile_ties(), ctx->d_tile_before(),
+                                                      ctx->d_bitmap());
+    }
+    osp_status st = launch_check(ctx, "split kernels");
+    if (st != OSP_OK)
+        return st;
+    ctx->have_gib = true;
+    ctx->gib_gran = granularity;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    return OSP_OK;
+}
+
+osp_status osp_get_importance(osp_ctx *ctx, double *imp_host, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!imp_host)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "imp_host is NULL");
+    if (!ctx->bound || !ctx->have_layer_importance)
+        return fail(ctx, OSP_ERR_BAD_STATE, "no layer importances yet (osp_split with OSP_GRAN_LAYER first)");
+    hipStream_t s = (hipStream_t)stream;
+    OSP_HIP(hipMemcpyAsync(imp_host, ctx->d_imp(), (size_t)ctx->n_tensors * sizeof(double),
+                           hipMemcpyDeviceToHost, s));
+    OSP_HIP(hipStreamSynchronize(s));
+    return OSP_OK;
+}
+
+osp_status osp_get_keys(osp_ctx *ctx, uint32_t *key_host, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!key_host)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "key_host is NULL");
+    if (!ctx->element_keys)
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "keys need cfg.element_keys");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    hipStream_t s = (hipStream_t)stream;
+    OSP_HIP(hipMemcpyAsync(key_host, ctx->d_key(), (size_t)ctx->arena * sizeof(uint32_t),
+                           hipMemcpyDeviceToHost, s));
+    OSP_HIP(hipStreamSynchronize(s));
+    return OSP_OK;
+}
+
+} // extern "C"

@@ -1,0 +1,341 @@
+// Split kernels: turn this iteration's importances into the next GIB.
+//
+// Layer granularity: finish the per-layer fp64 sums from the per-chunk partials
+// (fixed order, so the result is reproducible), rank the L layers by
+// (importance, index) and take the longest prefix that fits the budget.
+//
+// Element granularity: exact selection of the `budget` smallest 32-bit keys
+// with ties broken by arena index.  Three radix passes (11 + 11 + 10 bits, most
+// significant first) with per-workgroup LDS histograms find the threshold key T
+// and the number r of elements equal to T that still belong to stage 2; a
+// per-tile count of ties plus an exclusive scan over tiles turns "the first r
+// ties in index order" into a local decision, and the last pass writes the
+// bitmap.  Integer arithmetic only.
+#pragma once
+#include "osp_stream_kernels.hpp"
+
+namespace osp {
+
+struct SplitState {                    // one per context, in the workspace
+    long long n_stage2;                // elements in stage 2 under the current GIB
+    unsigned long long k_rem;          // rank still to be found inside the current radix bucket
+    unsigned long long ties_to_take;   // r
+    unsigned int prefix;               // key bits decided so far (right-aligned)
+    unsigned int threshold;            // T
+    unsigned int done;                 // 1: budget 0, nothing is selected
+    unsigned int pad;
+};
+
+// ---------------------------------------------------------------------------
+// layer granularity
+// ---------------------------------------------------------------------------
+
+// mode 0: partials of a stage-0 (single pass) aggregate are in slot 0;
+// mode 1: layer-granular GIB, layer l was aggregated by stage gib[l] ? 1 : 2;
+// mode 2: element-granular GIB, both stages visited every chunk.
+__global__ __launch_bounds__(kBlock) void k_layer_importance(
+    const int *__restrict__ layer_chunk_begin, const double *__restrict__ partial_s1,
+    const double *__restrict__ partial_s2, const uint8_t *__restrict__ gib_layer, int mode,
+    double *__restrict__ imp)
+{
+    const int l = blockIdx.x;
+    const int b = layer_chunk_begin[l], e = layer_chunk_begin[l + 1];
+    const double *src = partial_s1;
+    if (mode == 1 && gib_layer[l] == 0)
+        src = partial_s2;
+    double s = 0.0;
+    for (int c = b + (int)threadIdx.x; c < e; c += kBlock) {
+        double x = src[c];
+        if (mode == 2)
+            x += partial_s2[c];
+        s += x;
+    }
+    s = block_sum(s);
+    if (threadIdx.x == 0)
+        imp[l] = s;
+}
+
+__device__ __forceinline__ unsigned long long importance_rank_key(double x)
+{   // x >= 0, +Inf or NaN: the bit pattern orders like the value; all NaNs
+    // collapse to one pattern above +Inf
+    return (x != x) ? 0x7FF8000000000000ull
+                    : ((unsigned long long)__double_as_longlong(x) & 0x7FFFFFFFFFFFFFFFull);
+}
+
+constexpr int kRankBlock = 1024;
+
+__global__ __launch_bounds__(kRankBlock) void k_layer_rank(
+    int L, const double *__restrict__ imp, const long long *__restrict__ numel,
+    long long budget, uint8_t *__restrict__ gib_layer, int *__restrict__ order,
+    SplitState *__restrict__ st)
+{
+    for (int l = threadIdx.x; l < L; l += kRankBlock) {
+        const unsigned long long mine = importance_rank_key(imp[l]);
+        int rank = 0;
+        for (int j = 0; j < L; ++j) {
+            const unsigned long long other = importance_rank_key(imp[j]);
+            rank += (other < mine) || (other == mine && j < l);
+        }
+        order[rank] = l;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        long long taken = 0;
+        bool open = true;
+        for (int r = 0; r < L; ++r) {
+            const int l = order[r];
+            if (open && taken + numel[l] <= budget) {
+                taken += numel[l];
+                gib_layer[l] = 0;
+            } else {
+                open = false;      // prefix rule: nothing after the first misfit
+                gib_layer[l] = 1;
+            }
+        }
+        st->n_stage2 = taken;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// element granularity
+// ---------------------------------------------------------------------------
+constexpr int kRadixBins = 2048;
+// pass 0: bits 31..21, pass 1: bits 20..10, pass 2: bits 9..0
+__device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ int radix_bits(int pass) { return pass == 2 ? 10 : 11; }
+
+constexpr int kSelTile = 8192;         // keys per tile of the tie-count / bitmap passes
+
+__global__ __launch_bounds__(kBlock) void k_fill_u32(uint32_t *p, long long n, uint32_t v)
+{
+    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n;
+         i += (long long)gridDim.x * kBlock)
+        p[i] = v;
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kBlock) void k_select_histogram(
+    const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
+    unsigned long long *__restrict__ hist)
+{
+    __shared__ unsigned int h[kRadixBins];
+    for (int b = threadIdx.x; b < kRadixBins; b += kBlock)
+        h[b] = 0;
+    __syncthreads();
+    const int shift = radix_shift(PASS);
+    const unsigned mask = (1u << radix_bits(PASS)) - 1u;
+    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
+    const int hi = shift + radix_bits(PASS);          // bits above this pass's digit
+    const u4 *kv = reinterpret_cast<const u4 *>(key);
+    for (long long v = (long long)blockIdx.x * kBlock + threadIdx.x; v < n_vec;
+         v += (long long)gridDim.x * kBlock) {
+        const u4 k = kv[v];
+#pragma unroll
+        for (int j = 0; j < kVec; ++j) {
+            const unsigned x = k[j];
+            if (PASS == 0 || (x >> hi) == prefix)
+                atomicAdd(&h[(x >> shift) & mask], 1u);
+        }
+    }
+    __syncthreads();
+    for (int b = threadIdx.x; b < kRadixBins; b += kBlock)
+        if (h[b])
+            atomicAdd(&hist[b], (unsigned long long)h[b]);
+}
+
+// Exclusive scan of one unsigned long long per thread over the 256-thread
+// workgroup, in thread order.  total (may be null) gets the sum.
+__device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long x,
+                                                                   unsigned long long *total)
+{
+    __shared__ unsigned long long wave_tot[kBlock / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    unsigned long long incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const unsigned long long up = __shfl_up(incl, off, 64);
+        if (lane >= off)
+            incl += up;
+    }
+    __syncthreads();                   // wave_tot may still be read from a previous call
+    if (lane == 63)
+        wave_tot[wave] = incl;
+    __syncthreads();
+    unsigned long long base = 0;
+    for (int w = 0; w < wave; ++w)
+        base += wave_tot[w];
+    if (total)
+        *total = wave_tot[0] + wave_tot[1] + wave_tot[2] + wave_tot[3];
+    return base + incl - x;
+}
+
+// One workgroup: find the bucket of this pass that holds the k-th smallest key.
+__global__ __launch_bounds__(kBlock) void k_select_pick(int pass, long long budget,
+                                                        const unsigned long long *__restrict__ hist,
+                                                        SplitState *__restrict__ st)
+{
+    __shared__ int found_bin;
+    __shared__ unsigned long long found_below;
+    if (pass == 0 && threadIdx.x == 0) {
+        st->done = budget == 0 ? 1u : 0u;
+        st->n_stage2 = budget;
+    }
+    const unsigned long long k = pass == 0 ? (unsigned long long)budget : st->k_rem;
+    const bool done = pass == 0 ? budget == 0 : st->done != 0;
+    if (done) {
+        if (threadIdx.x == 0) {
+            st->threshold = 0;
+            st->ties_to_take = 0;
+            st->prefix = 0;
+            st->k_rem = 0;
+        }
+        return;
+    }
+    constexpr int per = kRadixBins / kBlock;          // 8 consecutive bins per thread
+    unsigned long long c[per];
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        c[j] = hist[threadIdx.x * per + j];
+        mine += c[j];
+    }
+    if (threadIdx.x == 0)
+        found_bin = -1;
+    const unsigned long long before = block_exclusive_scan(mine, nullptr);
+    // the k-th smallest (k >= 1) lies in the unique bin with below < k <= below + count
+    if (before < k && k <= before + mine) {
+        unsigned long long below = before;
+#pragma unroll
+        for (int j = 0; j < per; ++j) {
+            if (below < k && k <= below + c[j]) {
+                found_bin = threadIdx.x * per + j;
+                found_below = below;
+            }
+            below += c[j];
+        }
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        if (found_bin < 0) {           // cannot happen for budget <= number of keys
+            st->done = 1;
+            st->threshold = 0;
+            st->ties_to_take = 0;
+        } else {
+            const unsigned prefix = pass == 0 ? 0u : st->prefix;
+            const unsigned np = (prefix << radix_bits(pass)) | (unsigned)found_bin;
+            st->prefix = np;
+            st->k_rem = k - found_below;
+            if (pass == 2) {
+                st->threshold = np;
+                st->ties_to_take = k - found_below;
+            }
+        }
+    }
+}
+
+__device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key, long long v,
+                                               long long n_vec)
+{
+    if (v < n_vec)
+        return reinterpret_cast<const u4 *>(key)[v];
+    u4 pad;
+    pad.x = pad.y = pad.z = pad.w = 0xFFFFFFFFu;
+    return pad;
+}
+
+// Per tile: how many keys equal the threshold.
+__global__ __launch_bounds__(kBlock) void k_select_count_ties(
+    const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
+    unsigned int *__restrict__ tile_ties)
+{
+    const unsigned T = st->threshold;
+    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
+    unsigned long long n = 0;
+    for (int it = 0; it < kSelTile / kStride; ++it) {
+        const u4 k = load_keys_or_pad(key, v0 + it * kBlock + threadIdx.x, n_vec);
+        n += (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+    }
+    unsigned long long total;
+    block_exclusive_scan(n, &total);
+    if (threadIdx.x == 0)
+        tile_ties[blockIdx.x] = (unsigned int)total;
+}
+
+// One workgroup: exclusive scan of the per-tile tie counts, in tile order.
+__global__ __launch_bounds__(kBlock) void k_select_scan_tiles(
+    const unsigned int *__restrict__ tile_ties, long long n_tiles,
+    unsigned long long *__restrict__ tile_before)
+{
+    const long long per = (n_tiles + kBlock - 1) / kBlock;
+    const long long b = (long long)threadIdx.x * per;
+    const long long e = b + per < n_tiles ? b + per : n_tiles;
+    unsigned long long mine = 0;
+    for (long long t = b; t < e; ++t)
+        mine += tile_ties[t];
+    unsigned long long run = block_exclusive_scan(mine, nullptr);
+    for (long long t = b; t < e; ++t) {
+        tile_before[t] = run;
+        run += tile_ties[t];
+    }
+}
+
+// Write the element bitmap: bit = 1 (important, stage 1) unless the element is
+// among the `budget` smallest in the order (key, index).
+__global__ __launch_bounds__(kBlock) void k_select_write_bitmap(
+    const uint32_t *__restrict__ key, long long n_vec, long long n_words,
+    const SplitState *__restrict__ st, const unsigned int *__restrict__ tile_ties,
+    const unsigned long long *__restrict__ tile_before, uint32_t *__restrict__ bitmap)
+{
+    const unsigned T = st->threshold;
+    const unsigned long long r = st->ties_to_take;
+    const bool none = st->done != 0;
+    const unsigned long long before = tile_before[blockIdx.x];
+    const unsigned long long ties = tile_ties[blockIdx.x];
+    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
+    int tie_mode;
+    if (none || ties == 0 || before >= r)
+        tie_mode = 0;
+    else if (before + ties <= r)
+        tie_mode = 1;
+    else
+        tie_mode = 2;
+    unsigned long long run = before;
+    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
+    for (int it = 0; it < kSelTile / kStride; ++it) {
+        const long long v = v0 + it * kBlock + threadIdx.x;
+        const u4 k = load_keys_or_pad(key, v, n_vec);
+        unsigned sel = 0;              // bit j: element j goes to stage 2
+        if (!none) {
+            unsigned long long my_before = 0;
+            if (tie_mode == 2) {
+                const unsigned long long n = (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+                unsigned long long total;
+                my_before = run + block_exclusive_scan(n, &total);
+                run += total;
+            }
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const unsigned x = k[j];
+                bool s = x < T;
+                if (x == T) {
+                    if (tie_mode == 1)
+                        s = true;
+                    else if (tie_mode == 2) {
+                        s = my_before < r;
+                        ++my_before;
+                    }
+                }
+                sel |= (s ? 1u : 0u) << j;
+            }
+        }
+        unsigned word = (~sel & 0xFu) << ((threadIdx.x & 7) * 4);
+        word |= __shfl_xor(word, 1, 64);
+        word |= __shfl_xor(word, 2, 64);
+        word |= __shfl_xor(word, 4, 64);
+        const long long w = v >> 3;    // 8 lanes x 4 keys = one 32-bit word
+        if ((threadIdx.x & 7) == 0 && w < n_words)
+            bitmap[w] = word;
+    }
+}
+
+} // namespace osp

@@ -1,0 +1,372 @@
+"""Parity of the HIP library against the CPU oracle, through the C ABI.
+
+Bar: the stage-1/stage-2 partition bit-exact; fp32 parameters within a relative
+error of 1e-5 (they are in fact bit-identical, which is asserted too, because
+both sides evaluate the same sequence of separately rounded fp32 operations);
+fp64 layer importances within 1e-12 relative (different summation order)."""
+import sys
+
+import numpy as np
+import pytest
+
+from oracle.osp_oracle import GRAN_ELEMENT, GRAN_LAYER, OracleOSP
+from paper_2306_16926_amd import workloads as W
+from tests import brute
+from tests.helpers import make_oracle, random_bits, random_layer_gib
+
+pytestmark = pytest.mark.gpu
+F = np.float32
+REL_TOL = 1e-5           # tolerance of record for fp32 parameters
+
+
+def say(*a):
+    print("[case]", *a, flush=True)
+    sys.stdout.flush()
+
+
+def device_job(wl, seed=0, align=None, weights=None, element_keys=False, chunk_elems=0,
+               lr=None, mu=None, param_stride=None, pad_fill=None, params=None):
+    from paper_2306_16926_amd.device import DeviceJob
+    p = wl.make_params(seed, align) if params is None else params
+    return DeviceJob(wl.numel, wl.offsets(align), wl.arena_elems(align), wl.n_workers,
+                     wl.lr if lr is None else lr, wl.momentum if mu is None else mu, p,
+                     worker_weight=weights, element_keys=element_keys, chunk_elems=chunk_elems,
+                     param_stride=param_stride, pad_fill=pad_fill)
+
+
+def close_enough(got, want, what):
+    """rel 1e-5 (the stated bar), then bit equality (what the design promises)."""
+    got = np.asarray(got); want = np.asarray(want)
+    assert got.shape == want.shape, what
+    both_nan = np.isnan(got) & np.isnan(want)
+    fin = ~both_nan
+    err = np.abs(got[fin].astype(np.float64) - want[fin].astype(np.float64))
+    bound = REL_TOL * np.abs(want[fin].astype(np.float64))
+    with np.errstate(invalid="ignore"):
+        bad = ~((err <= bound) | (got[fin] == want[fin]))
+    assert not bad.any(), f"{what}: {int(bad.sum())} elements outside rel {REL_TOL}"
+    assert np.array_equal(got, want, equal_nan=True), f"{what}: not bit-identical"
+
+
+def compare_state(job, o, what):
+    P, V, Pw = job.download()
+    close_enough(P, o.P, what + " P")
+    close_enough(V, o.V, what + " V")
+    close_enough(Pw[:, :o.arena], o.Pw[:, :o.arena], what + " Pw")
+
+
+def compare_gib(job, o, what):
+    layer, bits, n2 = job.ctx.osp_get_gib()
+    if o.granularity == GRAN_LAYER:
+        assert np.array_equal(layer, o.gib_layer), what + " layer GIB"
+    else:
+        assert np.array_equal(bits, o.gib_bits), what + " element bitmap"
+    assert n2 == o.n_stage2, what + " n_stage2"
+
+
+def run_steps(wl, gran, steps, seed=0, align=None, weights=None, chunk_elems=0, budget=None,
+              threads=4):
+    budget = wl.budget if budget is None else budget
+    o = make_oracle(wl, seed, align, weights)
+    job = device_job(wl, seed, align, weights, element_keys=(gran == GRAN_ELEMENT),
+                     chunk_elems=chunk_elems)
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); job.ctx.osp_set_gib(GRAN_LAYER, all1)
+    sizes = []
+    for step in range(steps):
+        g = wl.make_grads(seed, step, align, threads=threads)
+        gd = job.upload_grads(g)
+        o.sync_step(g, gran, budget)
+        job.sync_step(gd, gran, budget)
+        compare_state(job, o, f"{wl.name} step {step}")
+        compare_gib(job, o, f"{wl.name} step {step}")
+        if gran == GRAN_LAYER:
+            imp = job.ctx.osp_get_importance()
+            rel = np.abs(imp - o.importance) / np.maximum(np.abs(o.importance), 1e-300)
+            assert rel.max() <= 1e-12, f"layer importance rel err {rel.max()}"
+        else:
+            real = brute.real_mask(wl.numel, wl.offsets(align), wl.arena_elems(align))
+            keys = job.ctx.osp_get_keys()
+            assert np.array_equal(keys[real], o.keys()[real]), "element keys"
+            assert (keys[~real] == 0xFFFFFFFF).all()
+        sizes.append(o.n_stage2)
+        del gd
+    return sizes
+
+
+# --------------------------------------------------------------------------
+# whole sync steps, chained
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_tiny_three_chained_steps(gran, weighted):
+    say("tiny", gran, weighted)
+    wl = W.get("tiny")
+    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
+    sizes = run_steps(wl, gran, 3, weights=wts)
+    assert sizes[0] > 0
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_tiny_other_seeds(seed):
+    say("tiny seed", seed)
+    run_steps(W.get("tiny"), GRAN_LAYER, 2, seed=seed)
+    run_steps(W.get("tiny"), GRAN_ELEMENT, 2, seed=seed)
+
+
+@pytest.mark.parametrize("chunk", [1024, 2048, 16384])
+@pytest.mark.parametrize("align", [4, 64])
+def test_tiny_chunk_sizes_and_alignment(chunk, align):
+    say("tiny chunk", chunk, "align", align)
+    run_steps(W.get("tiny"), GRAN_LAYER, 2, align=align, chunk_elems=chunk)
+    run_steps(W.get("tiny"), GRAN_ELEMENT, 2, align=align, chunk_elems=chunk)
+
+
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 7, 8, 9, 16, 17])
+def test_worker_counts(n_workers):
+    """Crosses the kernel's blocks of 8 (aggregate) and 4 (LGP) worker streams."""
+    say("workers", n_workers)
+    wl = W.custom([5000, 3, 1029, 64, 2048], n_workers, 0.4, align=4, config_id=40 + n_workers)
+    run_steps(wl, GRAN_LAYER, 2)
+    run_steps(wl, GRAN_ELEMENT, 2)
+    wts = np.random.default_rng(n_workers).random(n_workers).astype(F)
+    wts /= wts.sum()
+    run_steps(wl, GRAN_ELEMENT, 2, weights=wts)
+
+
+@pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT),
+                                       ("resnet50", GRAN_LAYER)])
+def test_cnn_shaped_two_steps(name, gran):
+    say(name, gran)
+    sizes = run_steps(W.get(name), gran, 2, threads=8)
+    assert sizes[-1] > 0
+
+
+# --------------------------------------------------------------------------
+# each call on its own, with an injected GIB
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_calls_one_by_one_with_injected_gib(gran):
+    say("one by one", gran)
+    wl = W.custom([37, 1, 128, 5, 9000, 64, 3, 4096, 4097], 5, 0.5, align=4, config_id=21)
+    rng = np.random.default_rng(8)
+    arena = wl.arena_elems()
+    stride = arena + 12                     # worker strides that differ from the arena
+    o = make_oracle(wl, param_stride=stride)
+    job = device_job(wl, element_keys=True, param_stride=stride, pad_fill=123.0)
+    o.Pw[:, arena:] = 123.0
+    # padding inside the arena carries a sentinel that nothing may overwrite
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    gib = random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER else random_bits(rng, arena)
+    o.set_gib(gran, gib); job.ctx.osp_set_gib(gran, gib)
+    compare_gib(job, o, "set_gib")
+    g = np.zeros((5, stride), F)
+    wl.make_grads(0, 0, stride=stride, out=g)
+    g[:, ~np.pad(real, (0, 12))] = 7.0      # garbage in the gradient padding must not leak
+    gd = job.upload_grads(g)
+    o.ps_aggregate_update(1, g); job.ctx.osp_ps_aggregate_update(1, gd, stride)
+    compare_state(job, o, "agg1")
+    o.apply_stage(1); job.ctx.osp_apply_stage(1)
+    compare_state(job, o, "apply1")
+    o.lgp_correct(g); job.ctx.osp_lgp_correct(gd, stride)
+    compare_state(job, o, "lgp")
+    o.ps_aggregate_update(2, g); job.ctx.osp_ps_aggregate_update(2, gd, stride)
+    compare_state(job, o, "agg2")
+    o.apply_stage(2); job.ctx.osp_apply_stage(2)
+    compare_state(job, o, "apply2")
+    P, V, Pw = job.download()
+    assert (Pw[:, arena:] == 123.0).all()
+    for w in range(5):
+        assert np.array_equal(Pw[w, :arena][real], P[real])
+    o.split(GRAN_LAYER, wl.budget); job.ctx.osp_split(GRAN_LAYER, wl.budget)
+    compare_gib(job, o, "split layer after staged " + str(gran))
+    imp = job.ctx.osp_get_importance()
+    assert np.allclose(imp, o.importance, rtol=1e-12, atol=0)
+
+
+def test_single_pass_equals_two_stages():
+    say("stage 0")
+    wl = W.get("tiny")
+    o = make_oracle(wl); job = device_job(wl, element_keys=True)
+    g = wl.make_grads(0, 0); gd = job.upload_grads(g)
+    o.ps_aggregate_update(0, g); o.apply_stage(0)
+    job.ctx.osp_ps_aggregate_update(0, gd, g.shape[1]); job.ctx.osp_apply_stage(0)
+    compare_state(job, o, "stage0")
+    o.split(GRAN_ELEMENT, wl.budget); job.ctx.osp_split(GRAN_ELEMENT, wl.budget)
+    compare_gib(job, o, "split after stage 0")
+
+
+# --------------------------------------------------------------------------
+# edge cases of the split
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("frac", [0.0, 1.0, 0.999])
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_degenerate_budgets(gran, frac):
+    say("budget", gran, frac)
+    wl = W.get("tiny")
+    budget = int(frac * wl.n_params)
+    sizes = run_steps(wl, gran, 3, budget=budget)
+    if frac == 0.0:
+        assert sizes == [0, 0, 0]
+    if frac == 1.0:
+        assert sizes == [wl.n_params] * 3
+
+
+def _split_from_keys(keys_f32, budget, numel=None):
+    """Drive both sides to a state whose element keys are |keys_f32| (P = 1,
+    one worker, gradient = keys) and split at element granularity."""
+    n = len(keys_f32)
+    wl = W.custom(numel or [n], 1, align=4, config_id=31)
+    arena = wl.arena_elems()
+    off = wl.offsets()
+    real = brute.real_mask(wl.numel, off, arena)
+    P = np.zeros(arena, F); P[real] = 1.0
+    g = np.zeros((1, arena), F); g[0, real] = keys_f32
+    o = OracleOSP(wl.numel, off, arena, 1, 0.1, 0.0); o.load_params(P)
+    job = device_job(wl, element_keys=True, mu=0.0, params=P)
+    gd = job.upload_grads(g)
+    with np.errstate(all="ignore"):
+        o.ps_aggregate_update(0, g)
+    job.ctx.osp_ps_aggregate_update(0, gd, arena)
+    o.split(GRAN_ELEMENT, budget); job.ctx.osp_split(GRAN_ELEMENT, budget)
+    compare_gib(job, o, "adversarial split")
+    compare_state(job, o, "adversarial state")
+    keys = job.ctx.osp_get_keys()
+    assert np.array_equal(keys[real], o.keys()[real])
+    return o
+
+
+@pytest.mark.parametrize("case", ["all_equal", "all_zero", "inside_ties", "ties_across_tiles",
+                                  "nan_inf", "neg_zero", "denormal", "two_values_multi_tensor"])
+def test_split_element_adversarial(case):
+    say("adversarial", case)
+    rng = np.random.default_rng(4)
+    n = 50_000                                  # several 8192-key tiles and a ragged tail
+    numel = None
+    if case == "all_equal":
+        keys, k = np.full(n, 3.0, F), 23_456
+    elif case == "all_zero":
+        keys, k = np.zeros(n, F), 8192 * 3      # boundary exactly on a tile edge
+    elif case == "inside_ties":
+        keys, k = rng.integers(0, 4, n).astype(F), 30_001
+    elif case == "ties_across_tiles":
+        keys = np.ones(n, F); keys[:100] = 0.5; keys[40_000:] = 2.0; k = 100 + 8192 * 2 + 17
+    elif case == "nan_inf":
+        keys = rng.standard_normal(n).astype(F)
+        keys[[5, 20_000]] = np.nan; keys[100] = np.inf; keys[49_999] = -np.inf
+        k = n - 3
+    elif case == "neg_zero":
+        keys = np.zeros(n, F); keys[::2] = -0.0; keys[7] = 1.0; k = 25_000
+    elif case == "denormal":
+        keys = (rng.standard_normal(n) * 1e-41).astype(F)      # subnormal magnitudes
+        keys[::5] = 0.0
+        k = 20_000
+    else:
+        numel = [8190, 3, 20_001, 1, 21_805]
+        keys = rng.integers(1, 3, n).astype(F); k = 26_000
+    _split_from_keys(keys, k, numel)
+
+
+def test_split_layer_ties_nan_and_zero_layers():
+    say("layer ties")
+    wl = W.custom([8, 8, 8, 8, 8, 5000], 1, align=4, config_id=32)
+    arena = wl.arena_elems(); off = wl.offsets()
+    real = brute.real_mask(wl.numel, off, arena)
+    P = np.zeros(arena, F); P[real] = 1.0
+    g = np.zeros((1, arena), F)
+    g[0, 0:8] = 1.0
+    g[0, 24:32] = np.nan
+    g[0, 32:40] = 0.5
+    g[0, 40:5040] = 1e-3
+    o = OracleOSP(wl.numel, off, arena, 1, 0.1, 0.0); o.load_params(P)
+    job = device_job(wl, mu=0.0, params=P)
+    gd = job.upload_grads(g)
+    for budget in (8, 24, 5032, 5040):
+        say("  budget", budget)
+        oo = OracleOSP(wl.numel, off, arena, 1, 0.1, 0.0); oo.load_params(P)
+        jj = device_job(wl, mu=0.0, params=P)
+        with np.errstate(all="ignore"):
+            oo.ps_aggregate_update(0, g)
+        jj.ctx.osp_ps_aggregate_update(0, gd, arena)
+        oo.split(GRAN_LAYER, budget); jj.ctx.osp_split(GRAN_LAYER, budget)
+        compare_gib(jj, oo, f"budget {budget}")
+        compare_state(jj, oo, f"budget {budget}")
+        imp = jj.ctx.osp_get_importance()
+        assert np.isnan(imp[3]) and imp[1] == 0.0 and imp[2] == 0.0
+    del o, job
+
+
+def test_nonfinite_gradients_flow_through_every_call():
+    say("nonfinite")
+    wl = W.custom([3000, 7, 2049], 3, 0.5, align=4, config_id=33)
+    o = make_oracle(wl); job = device_job(wl, element_keys=True)
+    rng = np.random.default_rng(3)
+    gib = random_bits(rng, wl.arena_elems())
+    o.set_gib(GRAN_ELEMENT, gib); job.ctx.osp_set_gib(GRAN_ELEMENT, gib)
+    g = wl.make_grads(0, 0)
+    g[0, 5] = np.inf; g[1, 5] = -np.inf; g[2, 9] = np.nan; g[1, 3001] = np.inf
+    g[0, 100:110] = 1e38; g[1, 100:110] = 3e38        # overflow in the sum
+    g[:, 200:260] = 1e-44                              # subnormal sums
+    gd = job.upload_grads(g)
+    with np.errstate(all="ignore"):
+        o.sync_step(g, GRAN_ELEMENT, wl.budget)
+    job.sync_step(gd, GRAN_ELEMENT, wl.budget)
+    compare_state(job, o, "nonfinite")
+    compare_gib(job, o, "nonfinite")
+
+
+# --------------------------------------------------------------------------
+# order-of-calls errors (need real launches to advance the state)
+# --------------------------------------------------------------------------
+
+def test_state_machine():
+    say("state machine")
+    from paper_2306_16926_amd import binding as B
+    wl = W.get("tiny")
+    job = device_job(wl)
+    c = job.ctx
+    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s = g.shape[1]
+
+    def bad(fn, *a):
+        with pytest.raises(B.OspError) as e:
+            fn(*a)
+        assert e.value.status == B.OSP_ERR_BAD_STATE, e.value
+    before = job.download()
+    bad(c.osp_ps_aggregate_update, 1, gd, s)            # no GIB yet
+    bad(c.osp_get_gib)
+    c.osp_ps_aggregate_update(0, gd, s)                 # stage 0 needs none
+    bad(c.osp_lgp_correct, gd, s)                       # LGP has no place in a BSP step
+    c.osp_apply_stage(0); c.osp_split(B.OSP_GRAN_LAYER, wl.budget)
+    bad(c.osp_split, B.OSP_GRAN_LAYER, wl.budget)       # nothing aggregated since
+    bad(c.osp_ps_aggregate_update, 2, gd, s)            # stage 2 before stage 1
+    bad(c.osp_apply_stage, 1)
+    bad(c.osp_lgp_correct, gd, s)
+    c.osp_ps_aggregate_update(1, gd, s)
+    bad(c.osp_ps_aggregate_update, 1, gd, s)            # stage 2 pending
+    bad(c.osp_ps_aggregate_update, 0, gd, s)
+    bad(c.osp_set_gib, B.OSP_GRAN_LAYER, np.ones(wl.n_tensors, np.uint8))
+    bad(c.osp_apply_stage, 2)
+    bad(c.osp_split, B.OSP_GRAN_LAYER, wl.budget)
+    with pytest.raises(B.OspError) as e:
+        c.osp_split(B.OSP_GRAN_ELEMENT, wl.budget)       # element_keys off
+    assert e.value.status == B.OSP_ERR_UNSUPPORTED
+    c.osp_lgp_correct(gd, s)
+    bad(c.osp_lgp_correct, gd, s)                       # twice
+    c.osp_apply_stage(1)
+    snap = job.download()
+    bad(c.osp_ps_aggregate_update, 1, gd, s)
+    after = job.download()
+    for a, b in zip(snap, after):                       # a rejected call touches nothing
+        assert np.array_equal(a, b)
+    c.osp_ps_aggregate_update(2, gd, s)
+    c.osp_apply_stage(2)
+    bad(c.osp_lgp_correct, gd, s)                       # would undo the correction
+    c.osp_ps_aggregate_update(1, gd, s)                 # split is optional: next iteration
+    c.osp_ps_aggregate_update(2, gd, s)
+    c.osp_split(B.OSP_GRAN_LAYER, 0)
+    layer, _, n2 = c.osp_get_gib()
+    assert n2 == 0 and layer.all()
+    assert not np.array_equal(before[0], after[0])
