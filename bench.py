@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Benchmark of the OSP synchronization step on one MI355X.
+
+One "step" is the whole hot path over one batch of synthetic gradients, in the
+paper's order (Sec. 3.1; Eq. 5 ordering):
+    osp_ps_aggregate_update(1) -> osp_apply_stage(1) -> osp_lgp_correct ->
+    osp_ps_aggregate_update(2) -> osp_apply_stage(2) -> osp_split
+All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
+
+Algorithmic bytes of a step (E1 + E2 = M parameters, E2 = stage-2 elements in
+effect during the step, N workers):
+    aggregate+update  4 (N + 4) E_s     per stage  (N grads + P + V read, P + V written)
+    apply_stage       4 (N + 1) E_s     per stage  (P read once, N replicas written)
+    lgp_correct       12 N E2                      (P_w and g_w read, P_w written)
+    split (layer)     0                            (a few hundred KB of partials)
+    split (element)   4 M + M/8  (+ 4 M key writes inside aggregate+update)
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
+
+
+def step_bytes(N, M, E2, element):
+    E1 = M - E2
+    b = {
+        "agg1": 4 * (N + 4) * E1, "apply1": 4 * (N + 1) * E1, "lgp": 12 * N * E2,
+        "agg2": 4 * (N + 4) * E2, "apply2": 4 * (N + 1) * E2, "split": 0,
+    }
+    if element:
+        b["agg1"] += 4 * E1
+        b["agg2"] += 4 * E2
+        b["split"] = 4 * M + M // 8
+    return b
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="vgg16",
+                    choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16"])
+    ap.add_argument("--granularity", default="layer", choices=["layer", "element"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--chunk-elems", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gen-threads", type=int, default=16)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU: all N simulated workers' buffers are "
+              "resident on one MI355X and there is no multi-GPU path; use --gpus 1",
+              file=sys.stderr)
+        return 2
+
+    import torch
+    from paper_2306_16926_amd import workloads as W
+    from paper_2306_16926_amd.device import DeviceJob
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 3
+    torch.cuda.set_device(0)
+    wl = W.get(args.workload)
+    element = args.granularity == "element"
+    gran = 1 if element else 0
+    N, M = wl.n_workers, wl.n_params
+    arena, stride = wl.arena_elems(), wl.worker_stride()
+    K, Wm = args.steps, args.warmup
+
+    t0 = time.time()
+    params = wl.make_params(args.seed)
+    job = DeviceJob(wl.numel, wl.offsets(), arena, N, wl.lr, wl.momentum, params,
+                    element_keys=element, chunk_elems=args.chunk_elems, param_stride=stride)
+    # two gradient sets, alternated, so a step never re-reads what the last one left in cache
+    host_g0 = wl.make_grads(args.seed, 0, stride=stride, threads=args.gen_threads)
+    gsets = [job.upload_grads(host_g0)]
+    tmp = wl.make_grads(args.seed, 1, stride=stride, threads=args.gen_threads)
+    gsets.append(job.upload_grads(tmp))
+    del tmp
+    print(f"[bench] {wl.name}: N={N} L={wl.n_tensors} M={M} inputs ready in {time.time()-t0:.1f}s",
+          file=sys.stderr, flush=True)
+
+    c = job.ctx
+    c.osp_set_gib(0, np.ones(wl.n_tensors, np.uint8))     # iteration 1 is BSP (Algorithm 1)
+    n2_log = torch.zeros(K + 1, dtype=torch.int64).pin_memory()
+    n2_ptr = n2_log.data_ptr()
+    for i in range(Wm):
+        job.sync_step(gsets[i % 2], gran, wl.budget)
+    c.osp_read_n_stage2_async(n2_ptr)                      # E2 in effect during timed step 0
+    names = ["agg1", "apply1", "lgp", "agg2", "apply2", "split"]
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(K)]
+    torch.cuda.synchronize()
+
+    t_start = time.perf_counter()
+    for i in range(K):
+        g = gsets[(Wm + i) % 2]
+        e = ev[i]
+        e[0].record(); c.osp_ps_aggregate_update(1, g, stride)
+        e[1].record(); c.osp_apply_stage(1)
+        e[2].record(); c.osp_lgp_correct(g, stride)
+        e[3].record(); c.osp_ps_aggregate_update(2, g, stride)
+        e[4].record(); c.osp_apply_stage(2)
+        e[5].record(); c.osp_split(gran, wl.budget)
+        e[6].record()
+        c.osp_read_n_stage2_async(n2_ptr + 8 * (i + 1))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t_start
+
+    n2 = n2_log.numpy().astype(np.int64)
+    call_ms = {n: 0.0 for n in names}
+    call_bytes = {n: 0 for n in names}
+    total_bytes = 0
+    for i in range(K):
+        b = step_bytes(N, M, int(n2[i]), element)
+        for j, n in enumerate(names):
+            call_ms[n] += ev[i][j].elapsed_time(ev[i][j + 1])
+            call_bytes[n] += b[n]
+        total_bytes += sum(b.values())
+    ms_per_step = elapsed * 1e3 / K
+    gbps = total_bytes / elapsed / 1e9
+
+    # dominant kernel: the aggregate+update kernel, launched twice per step
+    agg_launches = 2 * K
+    agg_ms = (call_ms["agg1"] + call_ms["agg2"]) / agg_launches
+    agg_bytes = (call_bytes["agg1"] + call_bytes["agg2"]) / agg_launches
+    agg_gbps = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0
+    roofline = {"bound": "hbm", "kernel": "k_aggregate_update", "achieved": round(agg_gbps, 1),
+                "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
+                "traffic": None, "launches": agg_launches,
+                "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
+    calls = {n: {"ms": round(call_ms[n] / K, 5),
+                 "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
+             for n in names}
+
+    # reference line: a plain device-to-device copy of 2 GiB on the same box
+    src = torch.empty(1 << 29, dtype=torch.float32, device="cuda"); dst = torch.empty_like(src)
+    src.fill_(1.0); dst.copy_(src)
+    a, b2 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(); a.record()
+    for _ in range(10):
+        dst.copy_(src)
+    b2.record(); torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * src.numel() * 4 / (a.elapsed_time(b2) * 1e-3) / 1e9
+    del src, dst
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        cpu = cpu_baseline(wl, args, params, host_g0, job, gran, element, stride)
+
+    out = {
+        "metric": "osp_sync_step_GBps", "value": round(gbps, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{wl.name}-shaped", "n_workers": N, "n_tensors": wl.n_tensors,
+                   "n_params": M, "granularity": args.granularity,
+                   "stage2_fraction_nominal": wl.stage2_fraction,
+                   "stage2_elems_achieved": int(n2[K - 1]), "lr": wl.lr, "momentum": wl.momentum,
+                   "seed": args.seed, "chunk_elems": c.osp_chunk_elems()},
+        "sync_steps_per_s": round(K / elapsed, 2),
+        "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
+        "GB_per_step": round(total_bytes / K / 1e9, 4),
+        "calls": calls,
+        "copy_GBps_same_box": round(copy_gbps, 1),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+        "paper_context": "paper reports up to 50% end-to-end training throughput gain on 8xT4 "
+                         "workers + 1 PS over 10 Gbps Ethernet; it never times this arithmetic",
+    }
+    print(json.dumps(out))
+    return 0
+
+
+def cpu_baseline(wl, args, params, host_g, job, gran, element, stride):
+    """The CPU oracle, as it stands, on this machine's host cores: one sync step of
+    the same workload from the same GIB the GPU is at, single-threaded (the
+    reference of record) and the same loops under OpenMP."""
+    from oracle.osp_oracle import OracleOSP
+    N, M = wl.n_workers, wl.n_params
+    layer, bits, n2 = job.ctx.osp_get_gib()
+    res = {}
+    for omp in (False, True):
+        o = OracleOSP(wl.numel, wl.offsets(), wl.arena_elems(), N, wl.lr, wl.momentum,
+                      param_stride=stride, omp=omp)
+        o.load_params(params)
+        o.set_gib(gran, bits if element else layer)
+        t = time.perf_counter()
+        o.ps_aggregate_update(1, host_g); o.apply_stage(1); o.lgp_correct(host_g)
+        o.ps_aggregate_update(2, host_g); o.apply_stage(2)
+        if not element or M <= 30_000_000:       # the oracle's element split is a full sort
+            o.split(gran, wl.budget)
+            sample = "1 full sync step"
+        else:
+            sample = "1 sync step without the element split (a full sort of M keys)"
+        dt = time.perf_counter() - t
+        b = step_bytes(N, M, n2, element)
+        res[omp] = (dt, sum(b.values()) / dt / 1e9, sample)
+        del o
+    try:
+        cores_all = len(os.sched_getaffinity(0))
+    except AttributeError:
+        cores_all = os.cpu_count()
+    omp_threads = int(os.environ.get("OMP_NUM_THREADS", cores_all))
+    model = "unknown"
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    model = line.split(":", 1)[1].strip()
+                    break
+    except OSError:
+        pass
+    return {"value": round(res[False][1], 3), "unit": "GB/s", "cores": 1, "kind": "oracle",
+            "sample": res[False][2] + f" of {wl.name}-shaped, same GIB as the GPU run",
+            "ms_per_step": round(res[False][0] * 1e3, 1),
+            "all_cores": {"value": round(res[True][1], 3), "cores": min(omp_threads, cores_all),
+                          "ms_per_step": round(res[True][0] * 1e3, 1)},
+            "cpu": model}
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -132,6 +132,12 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
 osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap,
                        int64_t *n_stage2, void *stream);
 
+/* Enqueue a copy of the current stage-2 element count into *out_host without
+ * waiting; out_host should be pinned host memory and is valid once `stream` has
+ * passed this point.  For callers that log the split size every iteration
+ * without stalling the stream. */
+osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream);
+
 /* Install a GIB from the host (first iteration, tests, resume).  gib_host is
  * uint8[L] for LAYER or uint32[ceil(arena_elems/32)] for ELEMENT, same encoding
  * as osp_get_gib; padding bits are ignored.  Synchronizes `stream`. */

@@ -64,6 +64,8 @@ def _load() -> C.CDLL:
     lib.osp_split.restype = C.c_int
     lib.osp_get_gib.argtypes = [vp, vp, vp, C.POINTER(i64), vp]
     lib.osp_get_gib.restype = C.c_int
+    lib.osp_read_n_stage2_async.argtypes = [vp, vp, vp]
+    lib.osp_read_n_stage2_async.restype = C.c_int
     lib.osp_set_gib.argtypes = [vp, C.c_int, vp, vp]
     lib.osp_set_gib.restype = C.c_int
     lib.osp_ps_aggregate_update.argtypes = [vp, C.c_int, vp, i64, vp]
@@ -88,7 +90,7 @@ def _load() -> C.CDLL:
 lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
-           "osp_split", "osp_get_gib", "osp_set_gib", "osp_ps_aggregate_update",
+           "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks"]
 
@@ -194,6 +196,10 @@ class Context:
         self._check(lib.osp_get_gib(self._h, layer.ctypes.data, bits.ctypes.data, C.byref(n2),
                                     _stream(stream)))
         return layer, bits, int(n2.value)
+
+    def osp_read_n_stage2_async(self, out_host, stream=None) -> None:
+        """out_host: address (or pinned int64 tensor / array element) the count is copied to."""
+        self._check(lib.osp_read_n_stage2_async(self._h, _ptr(out_host), _stream(stream)))
 
     def osp_ps_aggregate_update(self, stage: int, grads, worker_stride: int, stream=None) -> None:
         self._check(lib.osp_ps_aggregate_update(self._h, stage, _ptr(grads), int(worker_stride),

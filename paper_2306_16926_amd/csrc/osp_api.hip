@@ -402,6 +402,19 @@ osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap, 
     return OSP_OK;
 }
 
+osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!out_host)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "out_host is NULL");
+    if (!ctx->bound || !ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "no GIB yet (osp_set_gib or osp_split first)");
+    OSP_HIP(hipMemcpyAsync(out_host, &ctx->d_state()->n_stage2, sizeof(int64_t),
+                           hipMemcpyDeviceToHost, (hipStream_t)stream));
+    return OSP_OK;
+}
+
 osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
                                    int64_t worker_stride, void *stream)
 {

@@ -36,9 +36,16 @@ def random_layer_gib(rng, L):
     return g
 
 
-def random_bits(rng, arena):
+def random_bits(rng, arena, real=None):
+    """Random element bitmap; with `real` (bool per arena element) the padding
+    bits are set to 1, the normal form both sides report."""
     words = (arena + 31) // 32
-    return rng.integers(0, 2**32, words, dtype=np.uint64).astype(np.uint32)
+    bits = rng.integers(0, 2**32, words, dtype=np.uint64).astype(np.uint32)
+    if real is not None:
+        pad = np.ones(words * 32, np.uint8)
+        pad[:arena] = ~real
+        bits |= np.packbits(pad, bitorder="little").view(np.uint32)
+    return bits
 
 
 def bits_to_bool(bits, arena):

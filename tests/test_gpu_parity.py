@@ -159,7 +159,7 @@ def test_calls_one_by_one_with_injected_gib(gran):
     o.Pw[:, arena:] = 123.0
     # padding inside the arena carries a sentinel that nothing may overwrite
     real = brute.real_mask(wl.numel, wl.offsets(), arena)
-    gib = random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER else random_bits(rng, arena)
+    gib = random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER else random_bits(rng, arena, real)
     o.set_gib(gran, gib); job.ctx.osp_set_gib(gran, gib)
     compare_gib(job, o, "set_gib")
     g = np.zeros((5, stride), F)
@@ -304,7 +304,8 @@ def test_nonfinite_gradients_flow_through_every_call():
     wl = W.custom([3000, 7, 2049], 3, 0.5, align=4, config_id=33)
     o = make_oracle(wl); job = device_job(wl, element_keys=True)
     rng = np.random.default_rng(3)
-    gib = random_bits(rng, wl.arena_elems())
+    gib = random_bits(rng, wl.arena_elems(),
+                      brute.real_mask(wl.numel, wl.offsets(), wl.arena_elems()))
     o.set_gib(GRAN_ELEMENT, gib); job.ctx.osp_set_gib(GRAN_ELEMENT, gib)
     g = wl.make_grads(0, 0)
     g[0, 5] = np.inf; g[1, 5] = -np.inf; g[2, 9] = np.nan; g[1, 3001] = np.inf
