@@ -19,7 +19,10 @@
  *   gib/out arguments of osp_set_gib / osp_get_* are HOST pointers.
  *   `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   Kernels are enqueued on it and the call returns without waiting, except
- *   osp_bind, osp_set_gib and the osp_get_* calls, which synchronize it.
+ *   osp_bind, osp_set_gib and the osp_get_* calls, which synchronize it, and
+ *   the first staged call after a layer-granular osp_split, which waits (on
+ *   the host) for that split to finish: it needs the sizes of the two stage
+ *   sets to shape its launch, and it is ordered behind the split anyway.
  *
  * Errors
  *   Every call returns a status and never throws or aborts.  Argument and
@@ -80,8 +83,8 @@ typedef struct {
                                       element's importance key, which makes
                                       osp_split(OSP_GRAN_ELEMENT) legal (costs 4 B/element of
                                       workspace and of traffic) */
-    int32_t chunk_elems;           /* work-chunk size in elements, multiple of 1024;
-                                      0 = library default */
+    int32_t chunk_elems;           /* work-chunk size in elements, multiple of 256;
+                                      0 = library default (256: one float4 per lane) */
 } osp_config;
 
 typedef struct {

@@ -17,7 +17,7 @@ using namespace osp;
 
 namespace {
 
-constexpr int kDefaultChunkElems = 4096;
+constexpr int kDefaultChunkElems = kStride;     // one float4 per lane
 constexpr size_t kAlign = 256;
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
@@ -43,8 +43,8 @@ struct osp_ctx {
     long long n_vec = 0, n_words = 0, n_tiles = 0;
 
     // ---- workspace layout (byte offsets) ----
-    size_t off_chunks = 0, off_lcb = 0, off_numel = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
+    size_t off_chunks = 0, off_lcb = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
+           off_order = 0, off_lbase = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -59,6 +59,15 @@ struct osp_ctx {
     bool agg1 = false, agg2 = false, single_pass = false, lgp_done = false, applied2 = false;
     bool have_layer_importance = false;
 
+    // ---- stage-list lengths (layer-granular GIB) ----
+    // The split runs on the device; the two list lengths come back through a
+    // small pinned buffer.  counts_pending: the copy has been enqueued and
+    // counts_ready (an event recorded behind it) tells when it has landed.
+    int stage_chunks[2] = {0, 0};
+    bool counts_pending = false;
+    int *pinned_counts = nullptr;              // hipHostMalloc, 2 ints
+    hipEvent_t counts_ready = nullptr;
+
     std::string err;
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
@@ -68,6 +77,8 @@ struct osp_ctx {
     double *d_partial(int slot) const { return at<double>(off_partial) + (size_t)slot * chunks.size(); }
     double *d_imp() const { return at<double>(off_imp); }
     int *d_order() const { return at<int>(off_order); }
+    int *d_lbase() const { return at<int>(off_lbase); }
+    int *d_list(int stage) const { return at<int>(off_lists) + (size_t)(stage - 1) * chunks.size(); }
     uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
     SplitState *d_state() const { return at<SplitState>(off_state); }
     float *d_weights() const { return at<float>(off_weights); }
@@ -123,9 +134,11 @@ void layout_workspace(osp_ctx *c)
     c->off_chunks = take(nc * sizeof(Chunk));
     c->off_lcb = take((size_t)(c->n_tensors + 1) * sizeof(int));
     c->off_numel = take((size_t)c->n_tensors * sizeof(long long));
+    c->off_lists = take(2 * nc * sizeof(int));
     c->off_partial = take(2 * nc * sizeof(double));
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
     c->off_order = take((size_t)c->n_tensors * sizeof(int));
+    c->off_lbase = take((size_t)c->n_tensors * sizeof(int));
     c->off_gib = take((size_t)c->n_tensors);
     c->off_state = take(sizeof(SplitState));
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
@@ -153,6 +166,39 @@ osp_status check_grads(osp_ctx *ctx, const float *grads, int64_t stride)
 }
 
 bool stage2_pending(const osp_ctx *c) { return c->agg1 && !c->agg2; }
+
+// Enqueue the fill of both stage lists (bases must already be on the device)
+// and the copy of their lengths to the pinned buffer.
+osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
+{
+    const int nc = (int)ctx->chunks.size();
+    k_stage_lists<<<(nc + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
+        nc, ctx->d_chunks(), ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(), ctx->d_list(1),
+        ctx->d_list(2));
+    OSP_HIP(hipMemcpyAsync(ctx->pinned_counts, ctx->d_state()->stage_chunks, 2 * sizeof(int),
+                           hipMemcpyDeviceToHost, s));
+    OSP_HIP(hipEventRecord(ctx->counts_ready, s));
+    ctx->counts_pending = true;
+    return OSP_OK;
+}
+
+// Lengths of the stage lists, waiting for the split that produced them if it
+// is still running (the kernel that needs them is ordered behind it anyway).
+osp_status stage_counts(osp_ctx *ctx)
+{
+    if (ctx->counts_pending) {
+        OSP_HIP(hipEventSynchronize(ctx->counts_ready));
+        ctx->stage_chunks[0] = ctx->pinned_counts[0];
+        ctx->stage_chunks[1] = ctx->pinned_counts[1];
+        ctx->counts_pending = false;
+        const long long nc = (long long)ctx->chunks.size();
+        if (ctx->stage_chunks[0] < 0 || ctx->stage_chunks[1] < 0 ||
+            (long long)ctx->stage_chunks[0] + ctx->stage_chunks[1] != nc)
+            return fail(ctx, OSP_ERR_HIP, "stage lists are inconsistent (%d + %d != %lld chunks)",
+                        ctx->stage_chunks[0], ctx->stage_chunks[1], nc);
+    }
+    return OSP_OK;
+}
 
 osp_status launch_check(osp_ctx *ctx, const char *what)
 {
@@ -248,7 +294,16 @@ osp_status osp_create(const osp_config *cfg, osp_ctx **out)
     return OSP_OK;
 }
 
-void osp_destroy(osp_ctx *ctx) { delete ctx; }
+void osp_destroy(osp_ctx *ctx)
+{
+    if (!ctx)
+        return;
+    if (ctx->pinned_counts)
+        (void)hipHostFree(ctx->pinned_counts);
+    if (ctx->counts_ready)
+        (void)hipEventDestroy(ctx->counts_ready);
+    delete ctx;
+}
 
 size_t osp_workspace_bytes(const osp_ctx *ctx) { return ctx ? ctx->ws_bytes : 0; }
 
@@ -296,6 +351,11 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         return fail(ctx, OSP_ERR_BAD_STATE, "cannot rebind while a stage 2 is pending");
     hipStream_t s = (hipStream_t)stream;
     ctx->bound = false;
+    if (!ctx->pinned_counts)
+        OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, 2 * sizeof(int), hipHostMallocDefault));
+    if (!ctx->counts_ready)
+        OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
+    ctx->counts_pending = false;
     ctx->ws = (char *)buf->workspace;
     OSP_HIP(hipMemcpyAsync(ctx->d_chunks(), ctx->chunks.data(), ctx->chunks.size() * sizeof(Chunk),
                            hipMemcpyHostToDevice, s));
@@ -307,12 +367,12 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
                            hipMemcpyHostToDevice, s));
     // partials, importances, ranking, GIB, split state start at zero
     const size_t zero_bytes = ctx->off_weights - ctx->off_partial;
-    k_fill_u32<<<256, kBlock, 0, s>>>(ctx->at<uint32_t>(ctx->off_partial),
-                                      (long long)(zero_bytes / 4), 0u);
+    k_fill_u32<<<256, kSplitBlock, 0, s>>>(ctx->at<uint32_t>(ctx->off_partial),
+                                           (long long)(zero_bytes / 4), 0u);
     if (ctx->element_keys) {
         // padding keys stay 0xFFFFFFFF for good: above every real key, never selected
-        k_fill_u32<<<1024, kBlock, 0, s>>>(ctx->d_key(), ctx->arena, 0xFFFFFFFFu);
-        k_fill_u32<<<256, kBlock, 0, s>>>(ctx->d_bitmap(), ctx->n_words, 0xFFFFFFFFu);
+        k_fill_u32<<<1024, kSplitBlock, 0, s>>>(ctx->d_key(), ctx->arena, 0xFFFFFFFFu);
+        k_fill_u32<<<256, kSplitBlock, 0, s>>>(ctx->d_bitmap(), ctx->n_words, 0xFFFFFFFFu);
     }
     osp_status st = launch_check(ctx, "bind fill kernels");
     if (st != OSP_OK)
@@ -355,6 +415,14 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         }
         OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
+        k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(),
+                                       ctx->d_state());
+        osp_status st = enqueue_stage_lists(ctx, s);
+        if (st != OSP_OK)
+            return st;
+        st = launch_check(ctx, "stage list kernels");
+        if (st != OSP_OK)
+            return st;
         OSP_HIP(hipStreamSynchronize(s));
     } else {
         const uint32_t *g = (const uint32_t *)gib_host;
@@ -436,9 +504,17 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 needs this iteration's stage 1 first");
 
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
+    unsigned n_groups = (unsigned)ctx->chunks.size();
+    if (listed) {
+        st = stage_counts(ctx);
+        if (st != OSP_OK)
+            return st;
+        n_groups = (unsigned)ctx->stage_chunks[stage - 1];
+    }
     AggArgs a;
     a.chunks = ctx->d_chunks();
-    a.gib_layer = ctx->d_gib();
+    a.stage_list = listed ? ctx->d_list(stage) : nullptr;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.V = ctx->V;
@@ -452,9 +528,10 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     a.inv_n = 1.0f / (float)ctx->n_workers;
     a.lr = ctx->lr;
     a.mu = ctx->mu;
-    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
+    const dim3 grid(n_groups), block(kBlock);
     hipStream_t s = (hipStream_t)stream;
     const int variant = (masked ? 4 : 0) | (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    if (n_groups > 0) {               // an empty stage launches nothing
     switch (variant) {
     case 0: k_aggregate_update<false, false, false><<<grid, block, 0, s>>>(a); break;
     case 1: k_aggregate_update<false, false, true><<<grid, block, 0, s>>>(a); break;
@@ -464,6 +541,7 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     case 7: k_aggregate_update<true, true, true><<<grid, block, 0, s>>>(a); break;
     default:
         return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
+    }
     }
     st = launch_check(ctx, "k_aggregate_update");
     if (st != OSP_OK)
@@ -497,22 +575,38 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
         return fail(ctx, OSP_ERR_BAD_STATE, "LGP already applied in this iteration");
     if (ctx->applied2)
         return fail(ctx, OSP_ERR_BAD_STATE, "LGP after the stage-2 correction would undo it");
+    const bool masked = ctx->gib_gran == OSP_GRAN_ELEMENT;
+    unsigned n_groups = (unsigned)ctx->chunks.size();
+    if (!masked) {
+        st = stage_counts(ctx);
+        if (st != OSP_OK)
+            return st;
+        n_groups = (unsigned)ctx->stage_chunks[1];
+    }
     LgpArgs a;
     a.chunks = ctx->d_chunks();
-    a.gib_layer = ctx->d_gib();
+    a.stage_list = masked ? nullptr : ctx->d_list(2);
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.Pw = ctx->Pw;
     a.param_stride = ctx->param_stride;
     a.grads = grads;
     a.worker_stride = worker_stride;
-    a.n_workers = ctx->n_workers;
     a.lr = ctx->lr;
-    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
     hipStream_t s = (hipStream_t)stream;
-    if (ctx->gib_gran == OSP_GRAN_ELEMENT)
-        k_lgp_correct<true><<<grid, block, 0, s>>>(a);
-    else
-        k_lgp_correct<false><<<grid, block, 0, s>>>(a);
+    if (n_groups > 0) {
+        // grid.y is limited to 65535: sweep the workers in slabs of that size
+        for (int w0 = 0; w0 < ctx->n_workers; w0 += 65535) {
+            const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
+            LgpArgs b = a;
+            b.Pw = a.Pw + (long long)w0 * a.param_stride;
+            b.grads = a.grads + (long long)w0 * a.worker_stride;
+            const dim3 grid(n_groups, (unsigned)nw), block(kBlock);
+            if (masked)
+                k_lgp_correct<true><<<grid, block, 0, s>>>(b);
+            else
+                k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+        }
+    }
     st = launch_check(ctx, "k_lgp_correct");
     if (st != OSP_OK)
         return st;
@@ -535,21 +629,31 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     if (stage != 1 && !(ctx->agg1 && ctx->agg2))
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
+    unsigned n_groups = (unsigned)ctx->chunks.size();
+    if (listed) {
+        osp_status sc = stage_counts(ctx);
+        if (sc != OSP_OK)
+            return sc;
+        n_groups = (unsigned)ctx->stage_chunks[stage - 1];
+    }
     ApplyArgs a;
     a.chunks = ctx->d_chunks();
-    a.gib_layer = ctx->d_gib();
+    a.stage_list = listed ? ctx->d_list(stage) : nullptr;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.Pw = ctx->Pw;
     a.param_stride = ctx->param_stride;
     a.n_workers = ctx->n_workers;
     a.stage = stage;
-    const dim3 grid((unsigned)ctx->chunks.size()), block(kBlock);
+    const dim3 grid(n_groups), block(kBlock);
     hipStream_t s = (hipStream_t)stream;
-    if (masked)
-        k_apply_stage<true><<<grid, block, 0, s>>>(a);
-    else
-        k_apply_stage<false><<<grid, block, 0, s>>>(a);
+    if (n_groups > 0) {
+        if (masked)
+            k_apply_stage<true><<<grid, block, 0, s>>>(a);
+        else
+            k_apply_stage<false><<<grid, block, 0, s>>>(a);
+    }
     osp_status st = launch_check(ctx, "k_apply_stage");
     if (st != OSP_OK)
         return st;
@@ -577,29 +681,32 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     hipStream_t s = (hipStream_t)stream;
     if (granularity == OSP_GRAN_LAYER) {
         const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
-        k_layer_importance<<<ctx->n_tensors, kBlock, 0, s>>>(ctx->d_lcb(), ctx->d_partial(0),
-                                                             ctx->d_partial(1), ctx->d_gib(), mode,
-                                                             ctx->d_imp());
+        k_layer_importance<<<ctx->n_tensors, kImpBlock, 0, s>>>(ctx->d_lcb(), ctx->d_partial(0),
+                                                                ctx->d_partial(1), ctx->d_gib(), mode,
+                                                                ctx->d_imp());
         k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_imp(), ctx->d_numel(),
-                                              (long long)budget_elems, ctx->d_gib(), ctx->d_order(),
-                                              ctx->d_state());
+                                              ctx->d_lcb(), (long long)budget_elems, ctx->d_gib(),
+                                              ctx->d_order(), ctx->d_lbase(), ctx->d_state());
+        osp_status ls = enqueue_stage_lists(ctx, s);
+        if (ls != OSP_OK)
+            return ls;
         ctx->have_layer_importance = true;
     } else {
         const long long nv = ctx->n_vec;
-        long long want = (nv + kBlock - 1) / kBlock;
+        long long want = (nv + kSplitBlock - 1) / kSplitBlock;
         const unsigned hgrid = (unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048);
-        k_fill_u32<<<24, kBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
+        k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
                                          (long long)3 * kRadixBins * 2, 0u);
-        k_select_histogram<0><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));
-        k_select_pick<<<1, kBlock, 0, s>>>(0, (long long)budget_elems, ctx->d_hist(0), ctx->d_state());
-        k_select_histogram<1><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(1));
-        k_select_pick<<<1, kBlock, 0, s>>>(1, (long long)budget_elems, ctx->d_hist(1), ctx->d_state());
-        k_select_histogram<2><<<hgrid, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2));
-        k_select_pick<<<1, kBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state());
+        k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));
+        k_select_pick<<<1, kSplitBlock, 0, s>>>(0, (long long)budget_elems, ctx->d_hist(0), ctx->d_state());
+        k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(1));
+        k_select_pick<<<1, kSplitBlock, 0, s>>>(1, (long long)budget_elems, ctx->d_hist(1), ctx->d_state());
+        k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2));
+        k_select_pick<<<1, kSplitBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state());
         const unsigned tiles = (unsigned)ctx->n_tiles;
-        k_select_count_ties<<<tiles, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
-        k_select_scan_tiles<<<1, kBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_tile_before());
-        k_select_write_bitmap<<<tiles, kBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
+        k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
+        k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_tile_before());
+        k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
                                                       ctx->d_tile_ties(), ctx->d_tile_before(),
                                                       ctx->d_bitmap());
     }

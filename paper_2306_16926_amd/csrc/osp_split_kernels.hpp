@@ -16,8 +16,12 @@
 
 namespace osp {
 
+constexpr int kSplitBlock = 256;       // 4 wavefronts
+constexpr int kSplitStride = kSplitBlock * kVec;
+
 struct SplitState {                    // one per context, in the workspace
     long long n_stage2;                // elements in stage 2 under the current GIB
+    int stage_chunks[2];               // chunks in the stage-1 / stage-2 list (layer GIB)
     unsigned long long k_rem;          // rank still to be found inside the current radix bucket
     unsigned long long ties_to_take;   // r
     unsigned int prefix;               // key bits decided so far (right-aligned)
@@ -30,10 +34,34 @@ struct SplitState {                    // one per context, in the workspace
 // layer granularity
 // ---------------------------------------------------------------------------
 
+// Deterministic sum of one double per thread over a workgroup of BLOCK threads:
+// fixed butterfly inside each wavefront, then the wavefront totals in order.
+// The result is valid in thread 0.
+template <int BLOCK>
+__device__ __forceinline__ double block_sum(double x)
+{
+    __shared__ double wave_part[BLOCK / 64];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1)
+        x += __shfl_down(x, off, 64);
+    if ((threadIdx.x & 63) == 0)
+        wave_part[threadIdx.x >> 6] = x;
+    __syncthreads();
+    double s = 0.0;
+#pragma unroll
+    for (int i = 0; i < BLOCK / 64; ++i)
+        s += wave_part[i];
+    return s;
+}
+
+constexpr int kImpBlock = 1024;
+
 // mode 0: partials of a stage-0 (single pass) aggregate are in slot 0;
 // mode 1: layer-granular GIB, layer l was aggregated by stage gib[l] ? 1 : 2;
 // mode 2: element-granular GIB, both stages visited every chunk.
-__global__ __launch_bounds__(kBlock) void k_layer_importance(
+// One workgroup per layer; thread t adds the partials t, t+1024, ... in order
+// (four independent running sums per thread, combined in a fixed order).
+__global__ __launch_bounds__(kImpBlock) void k_layer_importance(
     const int *__restrict__ layer_chunk_begin, const double *__restrict__ partial_s1,
     const double *__restrict__ partial_s2, const uint8_t *__restrict__ gib_layer, int mode,
     double *__restrict__ imp)
@@ -43,16 +71,27 @@ __global__ __launch_bounds__(kBlock) void k_layer_importance(
     const double *src = partial_s1;
     if (mode == 1 && gib_layer[l] == 0)
         src = partial_s2;
-    double s = 0.0;
-    for (int c = b + (int)threadIdx.x; c < e; c += kBlock) {
+    double s[4] = {0.0, 0.0, 0.0, 0.0};
+    int c = b + (int)threadIdx.x;
+    for (; c + 3 * kImpBlock < e; c += 4 * kImpBlock) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            double x = src[c + u * kImpBlock];
+            if (mode == 2)
+                x += partial_s2[c + u * kImpBlock];
+            s[u] += x;
+        }
+    }
+    for (int u = 0; c < e; c += kImpBlock, ++u) {
         double x = src[c];
         if (mode == 2)
             x += partial_s2[c];
-        s += x;
+        s[u] += x;
     }
-    s = block_sum(s);
+    const double mine = (s[0] + s[1]) + (s[2] + s[3]);
+    const double total = block_sum<kImpBlock>(mine);
     if (threadIdx.x == 0)
-        imp[l] = s;
+        imp[l] = total;
 }
 
 __device__ __forceinline__ unsigned long long importance_rank_key(double x)
@@ -64,9 +103,33 @@ __device__ __forceinline__ unsigned long long importance_rank_key(double x)
 
 constexpr int kRankBlock = 1024;
 
+// Position of every layer's first chunk inside its stage list, and the list
+// lengths.  Serial over the L layers, in layer order, so the lists come out in
+// ascending address order.
+__device__ __forceinline__ void stage_list_bases(int L, const uint8_t *__restrict__ gib_layer,
+                                                 const int *__restrict__ layer_chunk_begin,
+                                                 int *__restrict__ layer_base,
+                                                 SplitState *__restrict__ st)
+{
+    int n1 = 0, n2 = 0;
+    for (int l = 0; l < L; ++l) {
+        const int nc = layer_chunk_begin[l + 1] - layer_chunk_begin[l];
+        if (gib_layer[l]) {
+            layer_base[l] = n1;
+            n1 += nc;
+        } else {
+            layer_base[l] = n2;
+            n2 += nc;
+        }
+    }
+    st->stage_chunks[0] = n1;
+    st->stage_chunks[1] = n2;
+}
+
 __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     int L, const double *__restrict__ imp, const long long *__restrict__ numel,
-    long long budget, uint8_t *__restrict__ gib_layer, int *__restrict__ order,
+    const int *__restrict__ layer_chunk_begin, long long budget,
+    uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
     SplitState *__restrict__ st)
 {
     for (int l = threadIdx.x; l < L; l += kRankBlock) {
@@ -93,7 +156,32 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
             }
         }
         st->n_stage2 = taken;
+        stage_list_bases(L, gib_layer, layer_chunk_begin, layer_base, st);
     }
+}
+
+// After a GIB was uploaded from the host: only the list bases are needed.
+__global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
+                              const int *__restrict__ layer_chunk_begin,
+                              int *__restrict__ layer_base, SplitState *__restrict__ st)
+{
+    if (blockIdx.x == 0 && threadIdx.x == 0)
+        stage_list_bases(L, gib_layer, layer_chunk_begin, layer_base, st);
+}
+
+// Fill the two stage lists: chunk c of layer l goes to position
+// layer_base[l] + (c - first chunk of l) of the list of l's stage.
+__global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
+    int n_chunks, const Chunk *__restrict__ chunks, const uint8_t *__restrict__ gib_layer,
+    const int *__restrict__ layer_chunk_begin, const int *__restrict__ layer_base,
+    int *__restrict__ list_s1, int *__restrict__ list_s2)
+{
+    const int c = blockIdx.x * kSplitBlock + threadIdx.x;
+    if (c >= n_chunks)
+        return;
+    const int l = chunks[c].layer;
+    const int pos = layer_base[l] + (c - layer_chunk_begin[l]);
+    (gib_layer[l] ? list_s1 : list_s2)[pos] = c;
 }
 
 // ---------------------------------------------------------------------------
@@ -106,20 +194,20 @@ __device__ __forceinline__ int radix_bits(int pass) { return pass == 2 ? 10 : 11
 
 constexpr int kSelTile = 8192;         // keys per tile of the tie-count / bitmap passes
 
-__global__ __launch_bounds__(kBlock) void k_fill_u32(uint32_t *p, long long n, uint32_t v)
+__global__ __launch_bounds__(kSplitBlock) void k_fill_u32(uint32_t *p, long long n, uint32_t v)
 {
-    for (long long i = (long long)blockIdx.x * kBlock + threadIdx.x; i < n;
-         i += (long long)gridDim.x * kBlock)
+    for (long long i = (long long)blockIdx.x * kSplitBlock + threadIdx.x; i < n;
+         i += (long long)gridDim.x * kSplitBlock)
         p[i] = v;
 }
 
 template <int PASS>
-__global__ __launch_bounds__(kBlock) void k_select_histogram(
+__global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
     unsigned long long *__restrict__ hist)
 {
     __shared__ unsigned int h[kRadixBins];
-    for (int b = threadIdx.x; b < kRadixBins; b += kBlock)
+    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
         h[b] = 0;
     __syncthreads();
     const int shift = radix_shift(PASS);
@@ -127,8 +215,8 @@ __global__ __launch_bounds__(kBlock) void k_select_histogram(
     const unsigned prefix = PASS == 0 ? 0u : st->prefix;
     const int hi = shift + radix_bits(PASS);          // bits above this pass's digit
     const u4 *kv = reinterpret_cast<const u4 *>(key);
-    for (long long v = (long long)blockIdx.x * kBlock + threadIdx.x; v < n_vec;
-         v += (long long)gridDim.x * kBlock) {
+    for (long long v = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v < n_vec;
+         v += (long long)gridDim.x * kSplitBlock) {
         const u4 k = kv[v];
 #pragma unroll
         for (int j = 0; j < kVec; ++j) {
@@ -138,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void k_select_histogram(
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < kRadixBins; b += kBlock)
+    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
         if (h[b])
             atomicAdd(&hist[b], (unsigned long long)h[b]);
 }
@@ -148,7 +236,7 @@ __global__ __launch_bounds__(kBlock) void k_select_histogram(
 __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long long x,
                                                                    unsigned long long *total)
 {
-    __shared__ unsigned long long wave_tot[kBlock / 64];
+    __shared__ unsigned long long wave_tot[kSplitBlock / 64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     unsigned long long incl = x;
 #pragma unroll
@@ -170,7 +258,7 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
 }
 
 // One workgroup: find the bucket of this pass that holds the k-th smallest key.
-__global__ __launch_bounds__(kBlock) void k_select_pick(int pass, long long budget,
+__global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long budget,
                                                         const unsigned long long *__restrict__ hist,
                                                         SplitState *__restrict__ st)
 {
@@ -191,7 +279,7 @@ __global__ __launch_bounds__(kBlock) void k_select_pick(int pass, long long budg
         }
         return;
     }
-    constexpr int per = kRadixBins / kBlock;          // 8 consecutive bins per thread
+    constexpr int per = kRadixBins / kSplitBlock;          // 8 consecutive bins per thread
     unsigned long long c[per];
     unsigned long long mine = 0;
 #pragma unroll
@@ -244,15 +332,15 @@ __device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key,
 }
 
 // Per tile: how many keys equal the threshold.
-__global__ __launch_bounds__(kBlock) void k_select_count_ties(
+__global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
     unsigned int *__restrict__ tile_ties)
 {
     const unsigned T = st->threshold;
     const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
     unsigned long long n = 0;
-    for (int it = 0; it < kSelTile / kStride; ++it) {
-        const u4 k = load_keys_or_pad(key, v0 + it * kBlock + threadIdx.x, n_vec);
+    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
+        const u4 k = load_keys_or_pad(key, v0 + it * kSplitBlock + threadIdx.x, n_vec);
         n += (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
     }
     unsigned long long total;
@@ -262,11 +350,11 @@ __global__ __launch_bounds__(kBlock) void k_select_count_ties(
 }
 
 // One workgroup: exclusive scan of the per-tile tie counts, in tile order.
-__global__ __launch_bounds__(kBlock) void k_select_scan_tiles(
+__global__ __launch_bounds__(kSplitBlock) void k_select_scan_tiles(
     const unsigned int *__restrict__ tile_ties, long long n_tiles,
     unsigned long long *__restrict__ tile_before)
 {
-    const long long per = (n_tiles + kBlock - 1) / kBlock;
+    const long long per = (n_tiles + kSplitBlock - 1) / kSplitBlock;
     const long long b = (long long)threadIdx.x * per;
     const long long e = b + per < n_tiles ? b + per : n_tiles;
     unsigned long long mine = 0;
@@ -281,7 +369,7 @@ __global__ __launch_bounds__(kBlock) void k_select_scan_tiles(
 
 // Write the element bitmap: bit = 1 (important, stage 1) unless the element is
 // among the `budget` smallest in the order (key, index).
-__global__ __launch_bounds__(kBlock) void k_select_write_bitmap(
+__global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
     const uint32_t *__restrict__ key, long long n_vec, long long n_words,
     const SplitState *__restrict__ st, const unsigned int *__restrict__ tile_ties,
     const unsigned long long *__restrict__ tile_before, uint32_t *__restrict__ bitmap)
@@ -301,8 +389,8 @@ __global__ __launch_bounds__(kBlock) void k_select_write_bitmap(
         tie_mode = 2;
     unsigned long long run = before;
     const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
-    for (int it = 0; it < kSelTile / kStride; ++it) {
-        const long long v = v0 + it * kBlock + threadIdx.x;
+    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
+        const long long v = v0 + it * kSplitBlock + threadIdx.x;
         const u4 k = load_keys_or_pad(key, v, n_vec);
         unsigned sel = 0;              // bit j: element j goes to stage 2
         if (!none) {

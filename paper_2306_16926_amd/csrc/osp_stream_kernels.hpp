@@ -1,13 +1,20 @@
 // Streaming kernels of the OSP synchronization step for gfx950 (MI355X):
 // PS aggregate + SGD-momentum update with fused PGP importance, worker-side
-// stage install, and LGP.  All three are HBM-bound (< 0.5 flop per byte), so
-// they are built around 16-byte coalesced accesses, many independent loads in
-// flight per lane, and one launch over a chunk table that covers every tensor.
+// stage install, and LGP.  All three are HBM-bound (< 0.5 flop per byte).
+//
+// Shape that measured fastest on MI355X: one-wavefront workgroups (64 lanes),
+// each lane issues ALL its 16-byte loads, computes, issues its stores and the
+// wave ends.  A wave that ends does not wait for its stores, so the slot is
+// reused at once and stores cost no occupancy; small workgroups also keep the
+// set of DRAM pages that are open at any moment small.  With the default chunk
+// of 256 elements a lane handles exactly one float4 position.
 //
 // Work decomposition: a chunk is a run of at most chunk_elems consecutive
-// elements of ONE tensor; workgroup b owns chunk b.  Chunk starts are multiples
-// of 4 elements, so every 16-byte access is aligned and never straddles a
-// bitmap word; only the last float4 of a tensor can be ragged.
+// elements of ONE tensor.  Chunk starts are multiples of 4 elements, so every
+// 16-byte access is aligned and never straddles a bitmap word; only the last
+// float4 of a tensor can be ragged.  For a layer-granular GIB the chunks of
+// each stage are listed in a compact index list (ascending addresses), so a
+// launch has no idle workgroups.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -18,7 +25,7 @@
 
 namespace osp {
 
-constexpr int kBlock = 256;            // 4 wavefronts of 64
+constexpr int kBlock = 64;             // one wavefront per workgroup
 constexpr int kVec = 4;                // fp32 per 16-byte access
 constexpr int kStride = kBlock * kVec; // elements covered by one block-wide access
 
@@ -63,29 +70,26 @@ __device__ __forceinline__ unsigned lane_mask(int rem, long long e, int stage,
     return m;
 }
 
-// Layer-granular stage test, uniform over the workgroup.
-__device__ __forceinline__ bool chunk_in_stage(const uint8_t *__restrict__ gib_layer, int layer,
-                                               int stage)
+// Which chunk does workgroup `b` own?  With a stage list (layer-granular GIB,
+// stage 1 or 2) the b-th entry of the list; otherwise chunk b itself.
+__device__ __forceinline__ Chunk owned_chunk(const Chunk *__restrict__ chunks,
+                                             const int *__restrict__ stage_list, unsigned b)
 {
-    if (stage == 0)
-        return true;
-    const int s = gib_layer[layer] ? 1 : 2;
-    return s == stage;
+    return chunks[stage_list ? stage_list[b] : (int)b];
+}
+__device__ __forceinline__ int owned_chunk_index(const int *__restrict__ stage_list, unsigned b)
+{
+    return stage_list ? stage_list[b] : (int)b;
 }
 
-// Deterministic sum of one double per thread over the 256-thread workgroup:
-// fixed butterfly inside each wavefront, then a fixed tree over the 4 wavefronts.
-// The result is valid in thread 0.
-__device__ __forceinline__ double block_sum(double x)
+// Deterministic sum of one double per lane over the wavefront (fixed butterfly).
+// The result is valid in lane 0.
+__device__ __forceinline__ double wave_sum(double x)
 {
-    __shared__ double wave_part[kBlock / 64];
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1)
         x += __shfl_down(x, off, 64);
-    if ((threadIdx.x & 63) == 0)
-        wave_part[threadIdx.x >> 6] = x;
-    __syncthreads();
-    return (wave_part[0] + wave_part[1]) + (wave_part[2] + wave_part[3]);
+    return x;
 }
 
 __device__ __forceinline__ uint32_t importance_key(float q)
@@ -98,8 +102,8 @@ __device__ __forceinline__ uint32_t importance_key(float q)
 // ---------------------------------------------------------------------------
 struct AggArgs {
     const Chunk *chunks;
-    const uint8_t *gib_layer;          // [L]   (layer-granular GIB)
-    const uint32_t *bitmap;            // bit per element (element-granular GIB)
+    const int *stage_list;             // chunk indices of this stage, or null = every chunk
+    const uint32_t *bitmap;            // bit per element (element-granular GIB), when MASKED
     float *P;
     float *V;
     const float *grads;
@@ -112,14 +116,13 @@ struct AggArgs {
     float inv_n, lr, mu;
 };
 
-constexpr int kWorkerBlock = 8;        // gradient streams loaded before they are summed
+constexpr int kWorkerBlock = 16;       // gradient streams loaded before they are summed
 
 template <bool MASKED, bool WEIGHTED, bool KEYS>
 __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 {
-    const Chunk c = a.chunks[blockIdx.x];
-    if (!MASKED && !chunk_in_stage(a.gib_layer, c.layer, a.stage))
-        return;
+    const int ci = owned_chunk_index(a.stage_list, blockIdx.x);
+    const Chunk c = a.chunks[ci];
     const int N = a.n_workers;
     double imp = 0.0;
     for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
@@ -127,8 +130,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         const unsigned m = lane_mask<MASKED>(c.len - i, e, a.stage, a.bitmap);
         if (m == 0)
             continue;
-        const f4 p = ld_keep(a.P + e);
-        const f4 v = ld_keep(a.V + e);
+        const f4 p = ld_stream(a.P + e);
+        const f4 v = ld_stream(a.V + e);
         const float *gp = a.grads + e;
         f4 acc;
         for (int w0 = 0; w0 < N; w0 += kWorkerBlock) {
@@ -160,8 +163,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         const f4 pn = p - step;
         if (m == 0xFu) {
             imp += (double)q.x; imp += (double)q.y; imp += (double)q.z; imp += (double)q.w;
-            st_keep(a.V + e, vn);
-            st_keep(a.P + e, pn);
+            st_stream(a.V + e, vn);
+            st_stream(a.P + e, pn);
             if (KEYS) {
                 u4 k;
                 k.x = importance_key(q.x); k.y = importance_key(q.y);
@@ -180,9 +183,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
                 }
         }
     }
-    const double total = block_sum(imp);
+    const double total = wave_sum(imp);
     if (threadIdx.x == 0)
-        a.partial[blockIdx.x] = total;
+        a.partial[ci] = total;
 }
 
 // ---------------------------------------------------------------------------
@@ -190,7 +193,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 // ---------------------------------------------------------------------------
 struct ApplyArgs {
     const Chunk *chunks;
-    const uint8_t *gib_layer;
+    const int *stage_list;
     const uint32_t *bitmap;
     const float *P;
     float *Pw;
@@ -202,9 +205,7 @@ struct ApplyArgs {
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 {
-    const Chunk c = a.chunks[blockIdx.x];
-    if (!MASKED && !chunk_in_stage(a.gib_layer, c.layer, a.stage))
-        return;
+    const Chunk c = owned_chunk(a.chunks, a.stage_list, blockIdx.x);
     const int N = a.n_workers;
     for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
         const long long e = c.start + i;
@@ -231,53 +232,40 @@ __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 // ---------------------------------------------------------------------------
 struct LgpArgs {
     const Chunk *chunks;
-    const uint8_t *gib_layer;
+    const int *stage_list;             // stage-2 chunks, or null = every chunk (MASKED)
     const uint32_t *bitmap;
     float *Pw;
     long long param_stride;
     const float *grads;
     long long worker_stride;
-    int n_workers;
     float lr;
 };
 
-constexpr int kLgpWorkerBlock = 4;
-
+// grid = (chunks of stage 2, workers): one workgroup moves one chunk of ONE
+// replica, so the whole GPU sweeps one worker's arena at a time (three streams).
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
 {
-    const Chunk c = a.chunks[blockIdx.x];
-    if (!MASKED && !chunk_in_stage(a.gib_layer, c.layer, 2))
-        return;
-    const int N = a.n_workers;
+    const Chunk c = owned_chunk(a.chunks, a.stage_list, blockIdx.x);
+    const long long w = blockIdx.y;
+    float *pw = a.Pw + w * a.param_stride;
+    const float *gw = a.grads + w * a.worker_stride;
     for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
         const long long e = c.start + i;
         const unsigned m = lane_mask<MASKED>(c.len - i, e, 2, a.bitmap);
         if (m == 0)
             continue;
-        for (int w0 = 0; w0 < N; w0 += kLgpWorkerBlock) {
-            f4 p[kLgpWorkerBlock], g[kLgpWorkerBlock];
+        const f4 p = ld_stream(pw + e);
+        const f4 g = ld_stream(gw + e);
+        const f4 step = g * a.lr;
+        const f4 pn = p - step;
+        if (m == 0xFu) {
+            st_stream(pw + e, pn);
+        } else {
 #pragma unroll
-            for (int j = 0; j < kLgpWorkerBlock; ++j)
-                if (w0 + j < N) {
-                    p[j] = ld_stream(a.Pw + (long long)(w0 + j) * a.param_stride + e);
-                    g[j] = ld_stream(a.grads + (long long)(w0 + j) * a.worker_stride + e);
-                }
-#pragma unroll
-            for (int j = 0; j < kLgpWorkerBlock; ++j)
-                if (w0 + j < N) {
-                    const f4 step = g[j] * a.lr;
-                    const f4 pn = p[j] - step;
-                    float *dst = a.Pw + (long long)(w0 + j) * a.param_stride + e;
-                    if (m == 0xFu) {
-                        st_stream(dst, pn);
-                    } else {
-#pragma unroll
-                        for (int t = 0; t < kVec; ++t)
-                            if (m & (1u << t))
-                                dst[t] = pn[t];
-                    }
-                }
+            for (int t = 0; t < kVec; ++t)
+                if (m & (1u << t))
+                    pw[e + t] = pn[t];
         }
     }
 }

@@ -47,7 +47,7 @@ def test_create_and_geometry():
 @pytest.mark.parametrize("bad", [
     dict(n_workers=0), dict(numel=[0, 7]), dict(offset=[0, 9]), dict(offset=[0, 8]),
     dict(arena_elems=18), dict(arena_elems=16), dict(momentum=1.0), dict(momentum=-0.1),
-    dict(lr=float("nan")), dict(chunk_elems=1000), dict(chunk_elems=512),
+    dict(lr=float("nan")), dict(chunk_elems=1000), dict(chunk_elems=128),
     dict(numel=[], offset=[]),
 ])
 def test_create_rejects(bad):

@@ -115,7 +115,7 @@ def test_tiny_other_seeds(seed):
     run_steps(W.get("tiny"), GRAN_ELEMENT, 2, seed=seed)
 
 
-@pytest.mark.parametrize("chunk", [1024, 2048, 16384])
+@pytest.mark.parametrize("chunk", [256, 512, 1024, 16384])
 @pytest.mark.parametrize("align", [4, 64])
 def test_tiny_chunk_sizes_and_alignment(chunk, align):
     say("tiny chunk", chunk, "align", align)
