@@ -38,13 +38,16 @@ struct osp_ctx {
     int chunk_elems = kDefaultChunkElems;
 
     // ---- derived host tables ----
-    std::vector<Chunk> chunks;
+    std::vector<WorkItem> chunks;              // every chunk, ascending addresses
+    std::vector<int> chunk_layer;              // [n_chunks]
     std::vector<int> layer_chunk_begin;        // [L+1]
+    std::vector<Segment> segments;             // fixed-order reduction tree, level 1
+    std::vector<int> layer_seg_begin;          // [L+1]
     long long n_vec = 0, n_words = 0, n_tiles = 0;
 
     // ---- workspace layout (byte offsets) ----
-    size_t off_chunks = 0, off_lcb = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_lbase = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
+    size_t off_chunks = 0, off_clayer = 0, off_lcb = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
+           off_order = 0, off_lbase = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -71,14 +74,21 @@ struct osp_ctx {
     std::string err;
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
-    Chunk *d_chunks() const { return at<Chunk>(off_chunks); }
+    WorkItem *d_chunks() const { return at<WorkItem>(off_chunks); }
+    int *d_clayer() const { return at<int>(off_clayer); }
     int *d_lcb() const { return at<int>(off_lcb); }
     long long *d_numel() const { return at<long long>(off_numel); }
     double *d_partial(int slot) const { return at<double>(off_partial) + (size_t)slot * chunks.size(); }
     double *d_imp() const { return at<double>(off_imp); }
     int *d_order() const { return at<int>(off_order); }
     int *d_lbase() const { return at<int>(off_lbase); }
-    int *d_list(int stage) const { return at<int>(off_lists) + (size_t)(stage - 1) * chunks.size(); }
+    Segment *d_segs() const { return at<Segment>(off_segs); }
+    int *d_lsb() const { return at<int>(off_lsb); }
+    double *d_segsum() const { return at<double>(off_segsum); }
+    WorkItem *d_list(int stage) const
+    {
+        return at<WorkItem>(off_lists) + (size_t)(stage - 1) * chunks.size();
+    }
     uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
     SplitState *d_state() const { return at<SplitState>(off_state); }
     float *d_weights() const { return at<float>(off_weights); }
@@ -131,11 +141,15 @@ void layout_workspace(osp_ctx *c)
         return at;
     };
     const size_t nc = c->chunks.size();
-    c->off_chunks = take(nc * sizeof(Chunk));
+    c->off_chunks = take(nc * sizeof(WorkItem));
+    c->off_clayer = take(nc * sizeof(int));
     c->off_lcb = take((size_t)(c->n_tensors + 1) * sizeof(int));
     c->off_numel = take((size_t)c->n_tensors * sizeof(long long));
-    c->off_lists = take(2 * nc * sizeof(int));
+    c->off_segs = take(c->segments.size() * sizeof(Segment));
+    c->off_lsb = take((size_t)(c->n_tensors + 1) * sizeof(int));
+    c->off_lists = take(2 * nc * sizeof(WorkItem));
     c->off_partial = take(2 * nc * sizeof(double));
+    c->off_segsum = take(c->segments.size() * sizeof(double));
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
     c->off_order = take((size_t)c->n_tensors * sizeof(int));
     c->off_lbase = take((size_t)c->n_tensors * sizeof(int));
@@ -173,8 +187,8 @@ osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
 {
     const int nc = (int)ctx->chunks.size();
     k_stage_lists<<<(nc + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
-        nc, ctx->d_chunks(), ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(), ctx->d_list(1),
-        ctx->d_list(2));
+        nc, ctx->d_chunks(), ctx->d_clayer(), ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(),
+        ctx->d_list(1), ctx->d_list(2));
     OSP_HIP(hipMemcpyAsync(ctx->pinned_counts, ctx->d_state()->stage_chunks, 2 * sizeof(int),
                            hipMemcpyDeviceToHost, s));
     OSP_HIP(hipEventRecord(ctx->counts_ready, s));
@@ -270,11 +284,12 @@ osp_status osp_create(const osp_config *cfg, osp_ctx **out)
         for (int l = 0; l < c->n_tensors; ++l) {
             c->layer_chunk_begin.push_back((int)c->chunks.size());
             for (long long b = 0; b < c->numel[l]; b += chunk) {
-                Chunk k;
+                WorkItem k;
                 k.start = c->offset[l] + b;
                 k.len = (int)(c->numel[l] - b < chunk ? c->numel[l] - b : chunk);
-                k.layer = l;
+                k.chunk = (int)c->chunks.size();
                 c->chunks.push_back(k);
+                c->chunk_layer.push_back(l);
                 if (c->chunks.size() > (size_t)0x7FFFFFF0) {
                     delete c;
                     return fail(ctx, OSP_ERR_UNSUPPORTED, "more than 2^31 chunks; raise chunk_elems");
@@ -282,6 +297,19 @@ osp_status osp_create(const osp_config *cfg, osp_ctx **out)
             }
         }
         c->layer_chunk_begin.push_back((int)c->chunks.size());
+        for (int l = 0; l < c->n_tensors; ++l) {
+            c->layer_seg_begin.push_back((int)c->segments.size());
+            for (int b = c->layer_chunk_begin[l]; b < c->layer_chunk_begin[l + 1]; b += kSegChunks) {
+                Segment sg;
+                sg.begin = b;
+                sg.end = b + kSegChunks < c->layer_chunk_begin[l + 1] ? b + kSegChunks
+                                                                      : c->layer_chunk_begin[l + 1];
+                sg.layer = l;
+                sg.pad = 0;
+                c->segments.push_back(sg);
+            }
+        }
+        c->layer_seg_begin.push_back((int)c->segments.size());
     } catch (const std::bad_alloc &) {
         delete c;
         return fail(ctx, OSP_ERR_NOMEM, "out of host memory");
@@ -357,10 +385,16 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
     ctx->counts_pending = false;
     ctx->ws = (char *)buf->workspace;
-    OSP_HIP(hipMemcpyAsync(ctx->d_chunks(), ctx->chunks.data(), ctx->chunks.size() * sizeof(Chunk),
+    OSP_HIP(hipMemcpyAsync(ctx->d_chunks(), ctx->chunks.data(), ctx->chunks.size() * sizeof(WorkItem),
                            hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_clayer(), ctx->chunk_layer.data(),
+                           ctx->chunk_layer.size() * sizeof(int), hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_lcb(), ctx->layer_chunk_begin.data(),
                            ctx->layer_chunk_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_segs(), ctx->segments.data(), ctx->segments.size() * sizeof(Segment),
+                           hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_lsb(), ctx->layer_seg_begin.data(),
+                           ctx->layer_seg_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_numel(), ctx->numel.data(), ctx->numel.size() * sizeof(long long),
                            hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_weights(), ctx->weights.data(), ctx->weights.size() * sizeof(float),
@@ -513,8 +547,7 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         n_groups = (unsigned)ctx->stage_chunks[stage - 1];
     }
     AggArgs a;
-    a.chunks = ctx->d_chunks();
-    a.stage_list = listed ? ctx->d_list(stage) : nullptr;
+    a.items = listed ? ctx->d_list(stage) : ctx->d_chunks();
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.V = ctx->V;
@@ -584,8 +617,7 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
         n_groups = (unsigned)ctx->stage_chunks[1];
     }
     LgpArgs a;
-    a.chunks = ctx->d_chunks();
-    a.stage_list = masked ? nullptr : ctx->d_list(2);
+    a.items = masked ? ctx->d_chunks() : ctx->d_list(2);
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.Pw = ctx->Pw;
     a.param_stride = ctx->param_stride;
@@ -638,8 +670,7 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         n_groups = (unsigned)ctx->stage_chunks[stage - 1];
     }
     ApplyArgs a;
-    a.chunks = ctx->d_chunks();
-    a.stage_list = listed ? ctx->d_list(stage) : nullptr;
+    a.items = listed ? ctx->d_list(stage) : ctx->d_chunks();
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.Pw = ctx->Pw;
@@ -681,10 +712,10 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     hipStream_t s = (hipStream_t)stream;
     if (granularity == OSP_GRAN_LAYER) {
         const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
-        k_layer_importance<<<ctx->n_tensors, kImpBlock, 0, s>>>(ctx->d_lcb(), ctx->d_partial(0),
-                                                                ctx->d_partial(1), ctx->d_gib(), mode,
-                                                                ctx->d_imp());
-        k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_imp(), ctx->d_numel(),
+        k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
+            ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
+        k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
+                                              ctx->d_imp(), ctx->d_numel(),
                                               ctx->d_lcb(), (long long)budget_elems, ctx->d_gib(),
                                               ctx->d_order(), ctx->d_lbase(), ctx->d_state());
         osp_status ls = enqueue_stage_lists(ctx, s);

@@ -54,44 +54,39 @@ __device__ __forceinline__ double block_sum(double x)
     return s;
 }
 
-constexpr int kImpBlock = 1024;
+// The per-chunk partials of a layer are summed in two fixed-order levels:
+// segments of at most kSegChunks consecutive chunks of one layer, one workgroup
+// each, then the segment sums of a layer in ascending order.
+constexpr int kSegChunks = 2048;
+
+struct Segment {
+    int begin, end;                    // chunk index range [begin, end)
+    int layer;
+    int pad;
+};
 
 // mode 0: partials of a stage-0 (single pass) aggregate are in slot 0;
 // mode 1: layer-granular GIB, layer l was aggregated by stage gib[l] ? 1 : 2;
 // mode 2: element-granular GIB, both stages visited every chunk.
-// One workgroup per layer; thread t adds the partials t, t+1024, ... in order
-// (four independent running sums per thread, combined in a fixed order).
-__global__ __launch_bounds__(kImpBlock) void k_layer_importance(
-    const int *__restrict__ layer_chunk_begin, const double *__restrict__ partial_s1,
+__global__ __launch_bounds__(kSplitBlock) void k_segment_importance(
+    const Segment *__restrict__ segs, const double *__restrict__ partial_s1,
     const double *__restrict__ partial_s2, const uint8_t *__restrict__ gib_layer, int mode,
-    double *__restrict__ imp)
+    double *__restrict__ seg_sum)
 {
-    const int l = blockIdx.x;
-    const int b = layer_chunk_begin[l], e = layer_chunk_begin[l + 1];
+    const Segment sg = segs[blockIdx.x];
     const double *src = partial_s1;
-    if (mode == 1 && gib_layer[l] == 0)
+    if (mode == 1 && gib_layer[sg.layer] == 0)
         src = partial_s2;
-    double s[4] = {0.0, 0.0, 0.0, 0.0};
-    int c = b + (int)threadIdx.x;
-    for (; c + 3 * kImpBlock < e; c += 4 * kImpBlock) {
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-            double x = src[c + u * kImpBlock];
-            if (mode == 2)
-                x += partial_s2[c + u * kImpBlock];
-            s[u] += x;
-        }
-    }
-    for (int u = 0; c < e; c += kImpBlock, ++u) {
+    double s = 0.0;
+    for (int c = sg.begin + (int)threadIdx.x; c < sg.end; c += kSplitBlock) {
         double x = src[c];
         if (mode == 2)
             x += partial_s2[c];
-        s[u] += x;
+        s += x;
     }
-    const double mine = (s[0] + s[1]) + (s[2] + s[3]);
-    const double total = block_sum<kImpBlock>(mine);
+    const double total = block_sum<kSplitBlock>(s);
     if (threadIdx.x == 0)
-        imp[l] = total;
+        seg_sum[blockIdx.x] = total;
 }
 
 __device__ __forceinline__ unsigned long long importance_rank_key(double x)
@@ -127,11 +122,20 @@ __device__ __forceinline__ void stage_list_bases(int L, const uint8_t *__restric
 }
 
 __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
-    int L, const double *__restrict__ imp, const long long *__restrict__ numel,
+    int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
+    double *__restrict__ imp, const long long *__restrict__ numel,
     const int *__restrict__ layer_chunk_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
     SplitState *__restrict__ st)
 {
+    // Eq. 4: finish I^l from the layer's segment sums, in ascending order
+    for (int l = threadIdx.x; l < L; l += kRankBlock) {
+        double s = 0.0;
+        for (int g = layer_seg_begin[l]; g < layer_seg_begin[l + 1]; ++g)
+            s += seg_sum[g];
+        imp[l] = s;
+    }
+    __syncthreads();
     for (int l = threadIdx.x; l < L; l += kRankBlock) {
         const unsigned long long mine = importance_rank_key(imp[l]);
         int rank = 0;
@@ -169,19 +173,20 @@ __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
         stage_list_bases(L, gib_layer, layer_chunk_begin, layer_base, st);
 }
 
-// Fill the two stage lists: chunk c of layer l goes to position
-// layer_base[l] + (c - first chunk of l) of the list of l's stage.
+// Fill the two stage tables: chunk c of layer l goes to position
+// layer_base[l] + (c - first chunk of l) of the table of l's stage.
 __global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
-    int n_chunks, const Chunk *__restrict__ chunks, const uint8_t *__restrict__ gib_layer,
-    const int *__restrict__ layer_chunk_begin, const int *__restrict__ layer_base,
-    int *__restrict__ list_s1, int *__restrict__ list_s2)
+    int n_chunks, const WorkItem *__restrict__ items, const int *__restrict__ chunk_layer,
+    const uint8_t *__restrict__ gib_layer, const int *__restrict__ layer_chunk_begin,
+    const int *__restrict__ layer_base, WorkItem *__restrict__ list_s1,
+    WorkItem *__restrict__ list_s2)
 {
     const int c = blockIdx.x * kSplitBlock + threadIdx.x;
     if (c >= n_chunks)
         return;
-    const int l = chunks[c].layer;
+    const int l = chunk_layer[c];
     const int pos = layer_base[l] + (c - layer_chunk_begin[l]);
-    (gib_layer[l] ? list_s1 : list_s2)[pos] = c;
+    (gib_layer[l] ? list_s1 : list_s2)[pos] = items[c];
 }
 
 // ---------------------------------------------------------------------------

@@ -12,9 +12,13 @@
 // Work decomposition: a chunk is a run of at most chunk_elems consecutive
 // elements of ONE tensor.  Chunk starts are multiples of 4 elements, so every
 // 16-byte access is aligned and never straddles a bitmap word; only the last
-// float4 of a tensor can be ragged.  For a layer-granular GIB the chunks of
-// each stage are listed in a compact index list (ascending addresses), so a
-// launch has no idle workgroups.
+// float4 of a tensor can be ragged.  A launch walks a table of 16-byte work
+// items (one scalar load per workgroup): either the table of all chunks, or,
+// for a layer-granular GIB, the compact table of one stage's chunks (ascending
+// addresses), so a launch has no idle workgroups.
+//
+// Addressing: every stream is "uniform base + 32-bit lane offset", which keeps
+// the 16 gradient bases in scalar registers instead of 32 vector registers.
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -29,30 +33,30 @@ constexpr int kBlock = 64;             // one wavefront per workgroup
 constexpr int kVec = 4;                // fp32 per 16-byte access
 constexpr int kStride = kBlock * kVec; // elements covered by one block-wide access
 
-struct Chunk {
+struct WorkItem {
     long long start;                   // arena element index, multiple of 4
     int len;                           // 1 .. chunk_elems
-    int layer;
+    int chunk;                         // index of the chunk (slot of its importance partial)
 };
 
 using f4 = __attribute__((ext_vector_type(4))) float;
 using u4 = __attribute__((ext_vector_type(4))) unsigned int;
 
 __device__ __forceinline__ f4 ld_stream(const float *p)
-{   // read-once data (gradients): keep it from displacing reusable lines
+{   // read-once data: keep it from displacing reusable lines
     return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
 }
 __device__ __forceinline__ f4 ld_keep(const float *p)
 {
     return *reinterpret_cast<const f4 *>(p);
 }
-__device__ __forceinline__ void st_keep(float *p, f4 v)
-{
-    *reinterpret_cast<f4 *>(p) = v;
-}
 __device__ __forceinline__ void st_stream(float *p, f4 v)
-{
-    __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(p));
+{   // write-once data: streaming, written through at system scope.  Measured on
+    // MI355X this policy is the fastest for all three kernels (the 16-replica
+    // install gains about 7 % over a plain store, 12 % over "nt" alone).
+    // The store is the last thing a lane does to this address; nothing in the
+    // kernel reads it back, so no wait is needed after it.
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
 }
 
 // Which of the 4 elements at chunk position i does this call touch?
@@ -68,18 +72,6 @@ __device__ __forceinline__ unsigned lane_mask(int rem, long long e, int stage,
         m &= (stage == 1) ? imp : (~imp & 0xFu);
     }
     return m;
-}
-
-// Which chunk does workgroup `b` own?  With a stage list (layer-granular GIB,
-// stage 1 or 2) the b-th entry of the list; otherwise chunk b itself.
-__device__ __forceinline__ Chunk owned_chunk(const Chunk *__restrict__ chunks,
-                                             const int *__restrict__ stage_list, unsigned b)
-{
-    return chunks[stage_list ? stage_list[b] : (int)b];
-}
-__device__ __forceinline__ int owned_chunk_index(const int *__restrict__ stage_list, unsigned b)
-{
-    return stage_list ? stage_list[b] : (int)b;
 }
 
 // Deterministic sum of one double per lane over the wavefront (fixed butterfly).
@@ -101,8 +93,7 @@ __device__ __forceinline__ uint32_t importance_key(float q)
 // PS aggregate + update (+ PGP importance), one stage.
 // ---------------------------------------------------------------------------
 struct AggArgs {
-    const Chunk *chunks;
-    const int *stage_list;             // chunk indices of this stage, or null = every chunk
+    const WorkItem *items;             // one per workgroup
     const uint32_t *bitmap;            // bit per element (element-granular GIB), when MASKED
     float *P;
     float *V;
@@ -116,42 +107,61 @@ struct AggArgs {
     float inv_n, lr, mu;
 };
 
-constexpr int kWorkerBlock = 16;       // gradient streams loaded before they are summed
+// Add B consecutive workers' gradients (w0 .. w0+B-1) to the running sum, in
+// ascending worker order; with w0 == 0 worker 0 starts the sum.  All B loads
+// are issued before the first add.
+template <int B, bool WEIGHTED>
+__device__ __forceinline__ void add_workers(f4 &acc, int w0, const float *__restrict__ g0,
+                                            long long worker_stride, unsigned i,
+                                            const float *__restrict__ weights)
+{
+    f4 g[B];
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+        g[j] = ld_stream(g0 + (long long)(w0 + j) * worker_stride + i);
+    if (WEIGHTED) {
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            g[j] = g[j] * weights[w0 + j];
+    }
+    f4 s = g[0];
+    if (w0 != 0)
+        s = acc + s;
+#pragma unroll
+    for (int j = 1; j < B; ++j)
+        s = s + g[j];
+    acc = s;
+}
+
+constexpr int kWorkerBlock = 16;       // most gradient streams in flight per lane
 
 template <bool MASKED, bool WEIGHTED, bool KEYS>
 __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 {
-    const int ci = owned_chunk_index(a.stage_list, blockIdx.x);
-    const Chunk c = a.chunks[ci];
+    const WorkItem c = a.items[blockIdx.x];
     const int N = a.n_workers;
+    // uniform bases of this chunk in every stream
+    float *Pc = a.P + c.start;
+    float *Vc = a.V + c.start;
+    const float *Gc = a.grads + c.start;
     double imp = 0.0;
-    for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
-        const long long e = c.start + i;
-        const unsigned m = lane_mask<MASKED>(c.len - i, e, a.stage, a.bitmap);
+    for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, a.stage, a.bitmap);
         if (m == 0)
             continue;
-        const f4 p = ld_stream(a.P + e);
-        const f4 v = ld_stream(a.V + e);
-        const float *gp = a.grads + e;
+        const f4 p = ld_stream(Pc + i);
+        const f4 v = ld_stream(Vc + i);
+        // workers in blocks of 16, then 8, 4, 2, 1 (N in binary): ascending order,
+        // few branches, and for N = 16 all gradient loads in flight at once
         f4 acc;
-        for (int w0 = 0; w0 < N; w0 += kWorkerBlock) {
-            f4 g[kWorkerBlock];
-#pragma unroll
-            for (int j = 0; j < kWorkerBlock; ++j)
-                if (w0 + j < N)
-                    g[j] = ld_stream(gp + (long long)(w0 + j) * a.worker_stride);
-#pragma unroll
-            for (int j = 0; j < kWorkerBlock; ++j)
-                if (w0 + j < N) {
-                    f4 term = g[j];
-                    if (WEIGHTED)
-                        term = term * a.weights[w0 + j];
-                    if (w0 + j == 0)
-                        acc = term;
-                    else
-                        acc = acc + term;
-                }
-        }
+        int w = 0;
+        for (; w + kWorkerBlock <= N; w += kWorkerBlock)
+            add_workers<kWorkerBlock, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights);
+        const int rest = N - w;
+        if (rest & 8) { add_workers<8, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
+        if (rest & 4) { add_workers<4, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
+        if (rest & 2) { add_workers<2, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
+        if (rest & 1) { add_workers<1, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); }
         const f4 gbar = WEIGHTED ? acc : acc * a.inv_n;
         const f4 prod = gbar * p;
         f4 q;
@@ -163,37 +173,36 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         const f4 pn = p - step;
         if (m == 0xFu) {
             imp += (double)q.x; imp += (double)q.y; imp += (double)q.z; imp += (double)q.w;
-            st_stream(a.V + e, vn);
-            st_stream(a.P + e, pn);
+            st_stream(Vc + i, vn);
+            st_stream(Pc + i, pn);
             if (KEYS) {
                 u4 k;
                 k.x = importance_key(q.x); k.y = importance_key(q.y);
                 k.z = importance_key(q.z); k.w = importance_key(q.w);
-                *reinterpret_cast<u4 *>(a.key + e) = k;
+                st_stream(reinterpret_cast<float *>(a.key + c.start + i), __builtin_bit_cast(f4, k));
             }
         } else {
 #pragma unroll
             for (int j = 0; j < kVec; ++j)
                 if (m & (1u << j)) {
                     imp += (double)q[j];
-                    a.V[e + j] = vn[j];
-                    a.P[e + j] = pn[j];
+                    Vc[i + j] = vn[j];
+                    Pc[i + j] = pn[j];
                     if (KEYS)
-                        a.key[e + j] = importance_key(q[j]);
+                        a.key[c.start + i + j] = importance_key(q[j]);
                 }
         }
     }
     const double total = wave_sum(imp);
     if (threadIdx.x == 0)
-        a.partial[ci] = total;
+        a.partial[c.chunk] = total;
 }
 
 // ---------------------------------------------------------------------------
 // Install a stage's global parameters on every worker replica.
 // ---------------------------------------------------------------------------
 struct ApplyArgs {
-    const Chunk *chunks;
-    const int *stage_list;
+    const WorkItem *items;
     const uint32_t *bitmap;
     const float *P;
     float *Pw;
@@ -205,24 +214,24 @@ struct ApplyArgs {
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 {
-    const Chunk c = owned_chunk(a.chunks, a.stage_list, blockIdx.x);
+    const WorkItem c = a.items[blockIdx.x];
     const int N = a.n_workers;
-    for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
-        const long long e = c.start + i;
-        const unsigned m = lane_mask<MASKED>(c.len - i, e, a.stage, a.bitmap);
+    const float *Pc = a.P + c.start;
+    float *Wc = a.Pw + c.start;
+    for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, a.stage, a.bitmap);
         if (m == 0)
             continue;
-        const f4 p = ld_keep(a.P + e);
-        float *dst = a.Pw + e;
+        const f4 p = ld_keep(Pc + i);
         if (m == 0xFu) {
             for (int w = 0; w < N; ++w)
-                st_stream(dst + (long long)w * a.param_stride, p);
+                st_stream(Wc + (long long)w * a.param_stride + i, p);
         } else {
             for (int w = 0; w < N; ++w)
 #pragma unroll
                 for (int j = 0; j < kVec; ++j)
                     if (m & (1u << j))
-                        dst[(long long)w * a.param_stride + j] = p[j];
+                        Wc[(long long)w * a.param_stride + i + j] = p[j];
         }
     }
 }
@@ -231,8 +240,7 @@ __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 // LGP: stage-2 parameters of every replica advance by the local gradient.
 // ---------------------------------------------------------------------------
 struct LgpArgs {
-    const Chunk *chunks;
-    const int *stage_list;             // stage-2 chunks, or null = every chunk (MASKED)
+    const WorkItem *items;             // stage-2 chunks, or every chunk (MASKED)
     const uint32_t *bitmap;
     float *Pw;
     long long param_stride;
@@ -246,26 +254,25 @@ struct LgpArgs {
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
 {
-    const Chunk c = owned_chunk(a.chunks, a.stage_list, blockIdx.x);
+    const WorkItem c = a.items[blockIdx.x];
     const long long w = blockIdx.y;
-    float *pw = a.Pw + w * a.param_stride;
-    const float *gw = a.grads + w * a.worker_stride;
-    for (int i = threadIdx.x * kVec; i < c.len; i += kStride) {
-        const long long e = c.start + i;
-        const unsigned m = lane_mask<MASKED>(c.len - i, e, 2, a.bitmap);
+    float *pw = a.Pw + w * a.param_stride + c.start;
+    const float *gw = a.grads + w * a.worker_stride + c.start;
+    for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, 2, a.bitmap);
         if (m == 0)
             continue;
-        const f4 p = ld_stream(pw + e);
-        const f4 g = ld_stream(gw + e);
+        const f4 p = ld_stream(pw + i);
+        const f4 g = ld_stream(gw + i);
         const f4 step = g * a.lr;
         const f4 pn = p - step;
         if (m == 0xFu) {
-            st_stream(pw + e, pn);
+            st_stream(pw + i, pn);
         } else {
 #pragma unroll
             for (int t = 0; t < kVec; ++t)
                 if (m & (1u << t))
-                    pw[e + t] = pn[t];
+                    pw[i + t] = pn[t];
         }
     }
 }
