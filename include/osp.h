@@ -179,6 +179,13 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream);
 osp_status osp_get_importance(osp_ctx *ctx, double *imp_host, void *stream);
 osp_status osp_get_keys(osp_ctx *ctx, uint32_t *key_host, void *stream);
 
+/* Plain device-to-device copy of `bytes` (multiple of 16; both pointers DEVICE,
+ * 16-byte aligned, not overlapping) with the same access shape and cache policy
+ * as the step's kernels.  A reference line for bandwidth measurements and the
+ * known-size kernel that hardware traffic counters are calibrated against; not
+ * part of the synchronization step.  At most 2^31 KiB per call. */
+osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
+
 /* Message for the last error on this context ("" if none).  With ctx == NULL,
  * the message of the last failed osp_create on this thread. */
 const char *osp_last_error(const osp_ctx *ctx);

@@ -78,6 +78,8 @@ def _load() -> C.CDLL:
     lib.osp_get_importance.restype = C.c_int
     lib.osp_get_keys.argtypes = [vp, vp, vp]
     lib.osp_get_keys.restype = C.c_int
+    lib.osp_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
+    lib.osp_stream_copy.restype = C.c_int
     lib.osp_last_error.argtypes = [vp]
     lib.osp_last_error.restype = C.c_char_p
     lib.osp_chunk_elems.argtypes = [vp]
@@ -92,6 +94,7 @@ lib = _load()
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
+           "osp_stream_copy",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks"]
 
 
@@ -220,6 +223,12 @@ class Context:
         key = np.zeros(self.arena_elems, np.uint32)
         self._check(lib.osp_get_keys(self._h, key.ctypes.data, _stream(stream)))
         return key
+
+
+def osp_stream_copy(dst, src, nbytes: int, stream=None) -> None:
+    st = lib.osp_stream_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream))
+    if st != OSP_OK:
+        raise OspError(st, "osp_stream_copy")
 
 
 # module-level aliases with the C names, taking the context first

@@ -38,15 +38,17 @@ struct osp_ctx {
     int chunk_elems = kDefaultChunkElems;
 
     // ---- derived host tables ----
-    std::vector<WorkItem> chunks;              // every chunk, ascending addresses
-    std::vector<int> chunk_layer;              // [n_chunks]
-    std::vector<int> layer_chunk_begin;        // [L+1]
+    std::vector<Span> spans;                   // every span, ascending addresses
+    std::vector<int> span_layer;               // [n_spans]
+    std::vector<int> layer_span_begin;         // [L+1]
+    std::vector<int> layer_chunk_begin;        // [L+1] (host only)
+    long long n_chunks = 0;
     std::vector<Segment> segments;             // fixed-order reduction tree, level 1
     std::vector<int> layer_seg_begin;          // [L+1]
     long long n_vec = 0, n_words = 0, n_tiles = 0;
 
     // ---- workspace layout (byte offsets) ----
-    size_t off_chunks = 0, off_clayer = 0, off_lcb = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
+    size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
            off_order = 0, off_lbase = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
@@ -66,7 +68,7 @@ struct osp_ctx {
     // The split runs on the device; the two list lengths come back through a
     // small pinned buffer.  counts_pending: the copy has been enqueued and
     // counts_ready (an event recorded behind it) tells when it has landed.
-    int stage_chunks[2] = {0, 0};
+    int stage_spans[2] = {0, 0};
     bool counts_pending = false;
     int *pinned_counts = nullptr;              // hipHostMalloc, 2 ints
     hipEvent_t counts_ready = nullptr;
@@ -74,21 +76,18 @@ struct osp_ctx {
     std::string err;
 
     template <class T> T *at(size_t off) const { return reinterpret_cast<T *>(ws + off); }
-    WorkItem *d_chunks() const { return at<WorkItem>(off_chunks); }
-    int *d_clayer() const { return at<int>(off_clayer); }
-    int *d_lcb() const { return at<int>(off_lcb); }
+    Span *d_spans() const { return at<Span>(off_spans); }
+    int *d_slayer() const { return at<int>(off_slayer); }
+    int *d_lsp() const { return at<int>(off_lsp); }
     long long *d_numel() const { return at<long long>(off_numel); }
-    double *d_partial(int slot) const { return at<double>(off_partial) + (size_t)slot * chunks.size(); }
+    double *d_partial(int slot) const { return at<double>(off_partial) + (size_t)slot * (size_t)n_chunks; }
     double *d_imp() const { return at<double>(off_imp); }
     int *d_order() const { return at<int>(off_order); }
     int *d_lbase() const { return at<int>(off_lbase); }
     Segment *d_segs() const { return at<Segment>(off_segs); }
     int *d_lsb() const { return at<int>(off_lsb); }
     double *d_segsum() const { return at<double>(off_segsum); }
-    WorkItem *d_list(int stage) const
-    {
-        return at<WorkItem>(off_lists) + (size_t)(stage - 1) * chunks.size();
-    }
+    Span *d_list(int stage) const { return at<Span>(off_lists) + (size_t)(stage - 1) * spans.size(); }
     uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
     SplitState *d_state() const { return at<SplitState>(off_state); }
     float *d_weights() const { return at<float>(off_weights); }
@@ -140,14 +139,14 @@ void layout_workspace(osp_ctx *c)
         o = align_up(o + bytes);
         return at;
     };
-    const size_t nc = c->chunks.size();
-    c->off_chunks = take(nc * sizeof(WorkItem));
-    c->off_clayer = take(nc * sizeof(int));
-    c->off_lcb = take((size_t)(c->n_tensors + 1) * sizeof(int));
+    const size_t nc = (size_t)c->n_chunks, ns = c->spans.size();
+    c->off_spans = take(ns * sizeof(Span));
+    c->off_slayer = take(ns * sizeof(int));
+    c->off_lsp = take((size_t)(c->n_tensors + 1) * sizeof(int));
     c->off_numel = take((size_t)c->n_tensors * sizeof(long long));
     c->off_segs = take(c->segments.size() * sizeof(Segment));
     c->off_lsb = take((size_t)(c->n_tensors + 1) * sizeof(int));
-    c->off_lists = take(2 * nc * sizeof(WorkItem));
+    c->off_lists = take(2 * ns * sizeof(Span));
     c->off_partial = take(2 * nc * sizeof(double));
     c->off_segsum = take(c->segments.size() * sizeof(double));
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
@@ -185,11 +184,11 @@ bool stage2_pending(const osp_ctx *c) { return c->agg1 && !c->agg2; }
 // and the copy of their lengths to the pinned buffer.
 osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
 {
-    const int nc = (int)ctx->chunks.size();
-    k_stage_lists<<<(nc + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
-        nc, ctx->d_chunks(), ctx->d_clayer(), ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(),
+    const int ns = (int)ctx->spans.size();
+    k_stage_lists<<<(ns + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
+        ns, ctx->d_spans(), ctx->d_slayer(), ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
         ctx->d_list(1), ctx->d_list(2));
-    OSP_HIP(hipMemcpyAsync(ctx->pinned_counts, ctx->d_state()->stage_chunks, 2 * sizeof(int),
+    OSP_HIP(hipMemcpyAsync(ctx->pinned_counts, ctx->d_state()->stage_spans, 2 * sizeof(int),
                            hipMemcpyDeviceToHost, s));
     OSP_HIP(hipEventRecord(ctx->counts_ready, s));
     ctx->counts_pending = true;
@@ -202,14 +201,14 @@ osp_status stage_counts(osp_ctx *ctx)
 {
     if (ctx->counts_pending) {
         OSP_HIP(hipEventSynchronize(ctx->counts_ready));
-        ctx->stage_chunks[0] = ctx->pinned_counts[0];
-        ctx->stage_chunks[1] = ctx->pinned_counts[1];
+        ctx->stage_spans[0] = ctx->pinned_counts[0];
+        ctx->stage_spans[1] = ctx->pinned_counts[1];
         ctx->counts_pending = false;
-        const long long nc = (long long)ctx->chunks.size();
-        if (ctx->stage_chunks[0] < 0 || ctx->stage_chunks[1] < 0 ||
-            (long long)ctx->stage_chunks[0] + ctx->stage_chunks[1] != nc)
-            return fail(ctx, OSP_ERR_HIP, "stage lists are inconsistent (%d + %d != %lld chunks)",
-                        ctx->stage_chunks[0], ctx->stage_chunks[1], nc);
+        const long long ns = (long long)ctx->spans.size();
+        if (ctx->stage_spans[0] < 0 || ctx->stage_spans[1] < 0 ||
+            (long long)ctx->stage_spans[0] + ctx->stage_spans[1] != ns)
+            return fail(ctx, OSP_ERR_HIP, "stage tables are inconsistent (%d + %d != %lld spans)",
+                        ctx->stage_spans[0], ctx->stage_spans[1], ns);
     }
     return OSP_OK;
 }
@@ -280,23 +279,26 @@ osp_status osp_create(const osp_config *cfg, osp_ctx **out)
             c->weights.assign((size_t)cfg->n_workers, 1.0f / (float)cfg->n_workers);
         c->element_keys = cfg->element_keys != 0;
         c->chunk_elems = chunk;
-        c->layer_chunk_begin.reserve((size_t)c->n_tensors + 1);
         for (int l = 0; l < c->n_tensors; ++l) {
-            c->layer_chunk_begin.push_back((int)c->chunks.size());
-            for (long long b = 0; b < c->numel[l]; b += chunk) {
-                WorkItem k;
-                k.start = c->offset[l] + b;
-                k.len = (int)(c->numel[l] - b < chunk ? c->numel[l] - b : chunk);
-                k.chunk = (int)c->chunks.size();
-                c->chunks.push_back(k);
-                c->chunk_layer.push_back(l);
-                if (c->chunks.size() > (size_t)0x7FFFFFF0) {
+            c->layer_chunk_begin.push_back((int)c->n_chunks);
+            c->layer_span_begin.push_back((int)c->spans.size());
+            const long long per_span = (long long)chunk * kSpanChunks;
+            for (long long b = 0; b < c->numel[l]; b += per_span) {
+                Span sp;
+                sp.start = c->offset[l] + b;
+                sp.n_elems = (int)(c->numel[l] - b < per_span ? c->numel[l] - b : per_span);
+                sp.chunk_base = (int)c->n_chunks;
+                c->spans.push_back(sp);
+                c->span_layer.push_back(l);
+                c->n_chunks += (sp.n_elems + chunk - 1) / chunk;
+                if (c->n_chunks > 0x7FFFFF00LL || c->spans.size() > (size_t)(0x7FFFFF00 / kSpanChunks)) {
                     delete c;
                     return fail(ctx, OSP_ERR_UNSUPPORTED, "more than 2^31 chunks; raise chunk_elems");
                 }
             }
         }
-        c->layer_chunk_begin.push_back((int)c->chunks.size());
+        c->layer_chunk_begin.push_back((int)c->n_chunks);
+        c->layer_span_begin.push_back((int)c->spans.size());
         for (int l = 0; l < c->n_tensors; ++l) {
             c->layer_seg_begin.push_back((int)c->segments.size());
             for (int b = c->layer_chunk_begin[l]; b < c->layer_chunk_begin[l + 1]; b += kSegChunks) {
@@ -337,7 +339,7 @@ size_t osp_workspace_bytes(const osp_ctx *ctx) { return ctx ? ctx->ws_bytes : 0;
 
 int32_t osp_chunk_elems(const osp_ctx *ctx) { return ctx ? ctx->chunk_elems : 0; }
 
-int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->chunks.size() : 0; }
+int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->n_chunks : 0; }
 
 const char *osp_last_error(const osp_ctx *ctx)
 {
@@ -385,12 +387,12 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
     ctx->counts_pending = false;
     ctx->ws = (char *)buf->workspace;
-    OSP_HIP(hipMemcpyAsync(ctx->d_chunks(), ctx->chunks.data(), ctx->chunks.size() * sizeof(WorkItem),
+    OSP_HIP(hipMemcpyAsync(ctx->d_spans(), ctx->spans.data(), ctx->spans.size() * sizeof(Span),
                            hipMemcpyHostToDevice, s));
-    OSP_HIP(hipMemcpyAsync(ctx->d_clayer(), ctx->chunk_layer.data(),
-                           ctx->chunk_layer.size() * sizeof(int), hipMemcpyHostToDevice, s));
-    OSP_HIP(hipMemcpyAsync(ctx->d_lcb(), ctx->layer_chunk_begin.data(),
-                           ctx->layer_chunk_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_slayer(), ctx->span_layer.data(),
+                           ctx->span_layer.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    OSP_HIP(hipMemcpyAsync(ctx->d_lsp(), ctx->layer_span_begin.data(),
+                           ctx->layer_span_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_segs(), ctx->segments.data(), ctx->segments.size() * sizeof(Segment),
                            hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_lsb(), ctx->layer_seg_begin.data(),
@@ -449,7 +451,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         }
         OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
-        k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lcb(), ctx->d_lbase(),
+        k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
                                        ctx->d_state());
         osp_status st = enqueue_stage_lists(ctx, s);
         if (st != OSP_OK)
@@ -539,15 +541,16 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
 
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
-    unsigned n_groups = (unsigned)ctx->chunks.size();
+    unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
     if (listed) {
         st = stage_counts(ctx);
         if (st != OSP_OK)
             return st;
-        n_groups = (unsigned)ctx->stage_chunks[stage - 1];
+        n_groups = (unsigned)ctx->stage_spans[stage - 1] * kSpanChunks;
     }
     AggArgs a;
-    a.items = listed ? ctx->d_list(stage) : ctx->d_chunks();
+    a.spans = listed ? ctx->d_list(stage) : ctx->d_spans();
+    a.chunk_elems = ctx->chunk_elems;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.V = ctx->V;
@@ -609,15 +612,16 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
     if (ctx->applied2)
         return fail(ctx, OSP_ERR_BAD_STATE, "LGP after the stage-2 correction would undo it");
     const bool masked = ctx->gib_gran == OSP_GRAN_ELEMENT;
-    unsigned n_groups = (unsigned)ctx->chunks.size();
+    unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
     if (!masked) {
         st = stage_counts(ctx);
         if (st != OSP_OK)
             return st;
-        n_groups = (unsigned)ctx->stage_chunks[1];
+        n_groups = (unsigned)ctx->stage_spans[1] * kSpanChunks;
     }
     LgpArgs a;
-    a.items = masked ? ctx->d_chunks() : ctx->d_list(2);
+    a.spans = masked ? ctx->d_spans() : ctx->d_list(2);
+    a.chunk_elems = ctx->chunk_elems;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.Pw = ctx->Pw;
     a.param_stride = ctx->param_stride;
@@ -662,15 +666,16 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
-    unsigned n_groups = (unsigned)ctx->chunks.size();
+    unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
     if (listed) {
         osp_status sc = stage_counts(ctx);
         if (sc != OSP_OK)
             return sc;
-        n_groups = (unsigned)ctx->stage_chunks[stage - 1];
+        n_groups = (unsigned)ctx->stage_spans[stage - 1] * kSpanChunks;
     }
     ApplyArgs a;
-    a.items = listed ? ctx->d_list(stage) : ctx->d_chunks();
+    a.spans = listed ? ctx->d_list(stage) : ctx->d_spans();
+    a.chunk_elems = ctx->chunk_elems;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
     a.Pw = ctx->Pw;
@@ -716,7 +721,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
             ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
         k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
                                               ctx->d_imp(), ctx->d_numel(),
-                                              ctx->d_lcb(), (long long)budget_elems, ctx->d_gib(),
+                                              ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                                               ctx->d_order(), ctx->d_lbase(), ctx->d_state());
         osp_status ls = enqueue_stage_lists(ctx, s);
         if (ls != OSP_OK)
@@ -748,6 +753,20 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     ctx->gib_gran = granularity;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
     return OSP_OK;
+}
+
+osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *stream)
+{
+    if (!dst || !src || !aligned16(dst) || !aligned16(src) || bytes % 16 != 0)
+        return OSP_ERR_INVALID_ARG;
+    const long long n_vec = (long long)(bytes / 16);
+    const long long groups = (n_vec + kBlock - 1) / kBlock;
+    if (groups > 0x7FFFFFFFLL)
+        return OSP_ERR_INVALID_ARG;
+    if (groups > 0)
+        k_stream_copy<<<(unsigned)groups, kBlock, 0, (hipStream_t)stream>>>((float *)dst,
+                                                                           (const float *)src, n_vec);
+    return hipGetLastError() == hipSuccess ? OSP_OK : OSP_ERR_HIP;
 }
 
 osp_status osp_get_importance(osp_ctx *ctx, double *imp_host, void *stream)

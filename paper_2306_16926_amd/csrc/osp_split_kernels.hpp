@@ -21,7 +21,7 @@ constexpr int kSplitStride = kSplitBlock * kVec;
 
 struct SplitState {                    // one per context, in the workspace
     long long n_stage2;                // elements in stage 2 under the current GIB
-    int stage_chunks[2];               // chunks in the stage-1 / stage-2 list (layer GIB)
+    int stage_spans[2];                // spans in the stage-1 / stage-2 table (layer GIB)
     unsigned long long k_rem;          // rank still to be found inside the current radix bucket
     unsigned long long ties_to_take;   // r
     unsigned int prefix;               // key bits decided so far (right-aligned)
@@ -98,33 +98,33 @@ __device__ __forceinline__ unsigned long long importance_rank_key(double x)
 
 constexpr int kRankBlock = 1024;
 
-// Position of every layer's first chunk inside its stage list, and the list
-// lengths.  Serial over the L layers, in layer order, so the lists come out in
+// Position of every layer's first span inside its stage table, and the table
+// lengths.  Serial over the L layers, in layer order, so the tables come out in
 // ascending address order.
 __device__ __forceinline__ void stage_list_bases(int L, const uint8_t *__restrict__ gib_layer,
-                                                 const int *__restrict__ layer_chunk_begin,
+                                                 const int *__restrict__ layer_span_begin,
                                                  int *__restrict__ layer_base,
                                                  SplitState *__restrict__ st)
 {
     int n1 = 0, n2 = 0;
     for (int l = 0; l < L; ++l) {
-        const int nc = layer_chunk_begin[l + 1] - layer_chunk_begin[l];
+        const int ns = layer_span_begin[l + 1] - layer_span_begin[l];
         if (gib_layer[l]) {
             layer_base[l] = n1;
-            n1 += nc;
+            n1 += ns;
         } else {
             layer_base[l] = n2;
-            n2 += nc;
+            n2 += ns;
         }
     }
-    st->stage_chunks[0] = n1;
-    st->stage_chunks[1] = n2;
+    st->stage_spans[0] = n1;
+    st->stage_spans[1] = n2;
 }
 
 __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
     double *__restrict__ imp, const long long *__restrict__ numel,
-    const int *__restrict__ layer_chunk_begin, long long budget,
+    const int *__restrict__ layer_span_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
     SplitState *__restrict__ st)
 {
@@ -160,33 +160,32 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
             }
         }
         st->n_stage2 = taken;
-        stage_list_bases(L, gib_layer, layer_chunk_begin, layer_base, st);
+        stage_list_bases(L, gib_layer, layer_span_begin, layer_base, st);
     }
 }
 
-// After a GIB was uploaded from the host: only the list bases are needed.
+// After a GIB was uploaded from the host: only the table bases are needed.
 __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
-                              const int *__restrict__ layer_chunk_begin,
+                              const int *__restrict__ layer_span_begin,
                               int *__restrict__ layer_base, SplitState *__restrict__ st)
 {
     if (blockIdx.x == 0 && threadIdx.x == 0)
-        stage_list_bases(L, gib_layer, layer_chunk_begin, layer_base, st);
+        stage_list_bases(L, gib_layer, layer_span_begin, layer_base, st);
 }
 
-// Fill the two stage tables: chunk c of layer l goes to position
-// layer_base[l] + (c - first chunk of l) of the table of l's stage.
+// Fill the two stage tables: span k of layer l goes to position
+// layer_base[l] + (k - first span of l) of the table of l's stage.
 __global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
-    int n_chunks, const WorkItem *__restrict__ items, const int *__restrict__ chunk_layer,
-    const uint8_t *__restrict__ gib_layer, const int *__restrict__ layer_chunk_begin,
-    const int *__restrict__ layer_base, WorkItem *__restrict__ list_s1,
-    WorkItem *__restrict__ list_s2)
+    int n_spans, const Span *__restrict__ spans, const int *__restrict__ span_layer,
+    const uint8_t *__restrict__ gib_layer, const int *__restrict__ layer_span_begin,
+    const int *__restrict__ layer_base, Span *__restrict__ list_s1, Span *__restrict__ list_s2)
 {
-    const int c = blockIdx.x * kSplitBlock + threadIdx.x;
-    if (c >= n_chunks)
+    const int k = blockIdx.x * kSplitBlock + threadIdx.x;
+    if (k >= n_spans)
         return;
-    const int l = chunk_layer[c];
-    const int pos = layer_base[l] + (c - layer_chunk_begin[l]);
-    (gib_layer[l] ? list_s1 : list_s2)[pos] = items[c];
+    const int l = span_layer[k];
+    const int pos = layer_base[l] + (k - layer_span_begin[l]);
+    (gib_layer[l] ? list_s1 : list_s2)[pos] = spans[k];
 }
 
 // ---------------------------------------------------------------------------

@@ -12,10 +12,13 @@
 // Work decomposition: a chunk is a run of at most chunk_elems consecutive
 // elements of ONE tensor.  Chunk starts are multiples of 4 elements, so every
 // 16-byte access is aligned and never straddles a bitmap word; only the last
-// float4 of a tensor can be ragged.  A launch walks a table of 16-byte work
-// items (one scalar load per workgroup): either the table of all chunks, or,
-// for a layer-granular GIB, the compact table of one stage's chunks (ascending
-// addresses), so a launch has no idle workgroups.
+// float4 of a tensor can be ragged.  A launch walks a table of 16-byte spans,
+// each covering up to 64 consecutive chunks of one tensor: 64 consecutive
+// workgroups share one span (one scalar load, an L2 hit for all but the first
+// workgroup on each XCD) and keep the address order of the chunks, which the
+// DRAM likes.  The table is either that of all chunks or, for a layer-granular
+// GIB, the compact table of one stage's spans, so a launch has next to no idle
+// workgroups (at most 63 per tensor).
 //
 // Addressing: every stream is "uniform base + 32-bit lane offset", which keeps
 // the 16 gradient bases in scalar registers instead of 32 vector registers.
@@ -33,11 +36,34 @@ constexpr int kBlock = 64;             // one wavefront per workgroup
 constexpr int kVec = 4;                // fp32 per 16-byte access
 constexpr int kStride = kBlock * kVec; // elements covered by one block-wide access
 
-struct WorkItem {
-    long long start;                   // arena element index, multiple of 4
-    int len;                           // 1 .. chunk_elems
-    int chunk;                         // index of the chunk (slot of its importance partial)
+constexpr int kSpanChunks = 64;        // workgroups that share one table entry
+
+struct Span {
+    long long start;                   // arena element index of the first chunk, multiple of 4
+    int n_elems;                       // elements covered: 1 .. 64 * chunk_elems
+    int chunk_base;                    // index of the first chunk (slot of its importance partial)
 };
+
+struct Piece {                         // the chunk one workgroup owns
+    long long start;
+    int len;
+    int chunk;
+};
+
+// Workgroup b owns chunk (b % 64) of span (b / 64); false if the span is shorter.
+__device__ __forceinline__ bool owned_piece(const Span *__restrict__ spans, int chunk_elems,
+                                            Piece &p)
+{
+    const Span s = spans[blockIdx.x / kSpanChunks];
+    const int j = blockIdx.x % kSpanChunks;
+    const int off = j * chunk_elems;
+    if (off >= s.n_elems)
+        return false;
+    p.start = s.start + off;
+    p.len = s.n_elems - off < chunk_elems ? s.n_elems - off : chunk_elems;
+    p.chunk = s.chunk_base + j;
+    return true;
+}
 
 using f4 = __attribute__((ext_vector_type(4))) float;
 using u4 = __attribute__((ext_vector_type(4))) unsigned int;
@@ -93,7 +119,8 @@ __device__ __forceinline__ uint32_t importance_key(float q)
 // PS aggregate + update (+ PGP importance), one stage.
 // ---------------------------------------------------------------------------
 struct AggArgs {
-    const WorkItem *items;             // one per workgroup
+    const Span *spans;                 // one per 64 workgroups
+    int chunk_elems;
     const uint32_t *bitmap;            // bit per element (element-granular GIB), when MASKED
     float *P;
     float *V;
@@ -138,7 +165,9 @@ constexpr int kWorkerBlock = 16;       // most gradient streams in flight per la
 template <bool MASKED, bool WEIGHTED, bool KEYS>
 __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 {
-    const WorkItem c = a.items[blockIdx.x];
+    Piece c;
+    if (!owned_piece(a.spans, a.chunk_elems, c))
+        return;
     const int N = a.n_workers;
     // uniform bases of this chunk in every stream
     float *Pc = a.P + c.start;
@@ -202,7 +231,8 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 // Install a stage's global parameters on every worker replica.
 // ---------------------------------------------------------------------------
 struct ApplyArgs {
-    const WorkItem *items;
+    const Span *spans;
+    int chunk_elems;
     const uint32_t *bitmap;
     const float *P;
     float *Pw;
@@ -214,7 +244,9 @@ struct ApplyArgs {
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 {
-    const WorkItem c = a.items[blockIdx.x];
+    Piece c;
+    if (!owned_piece(a.spans, a.chunk_elems, c))
+        return;
     const int N = a.n_workers;
     const float *Pc = a.P + c.start;
     float *Wc = a.Pw + c.start;
@@ -240,7 +272,8 @@ __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
 // LGP: stage-2 parameters of every replica advance by the local gradient.
 // ---------------------------------------------------------------------------
 struct LgpArgs {
-    const WorkItem *items;             // stage-2 chunks, or every chunk (MASKED)
+    const Span *spans;                 // stage-2 spans, or all spans (MASKED)
+    int chunk_elems;
     const uint32_t *bitmap;
     float *Pw;
     long long param_stride;
@@ -254,7 +287,9 @@ struct LgpArgs {
 template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
 {
-    const WorkItem c = a.items[blockIdx.x];
+    Piece c;
+    if (!owned_piece(a.spans, a.chunk_elems, c))
+        return;
     const long long w = blockIdx.y;
     float *pw = a.Pw + w * a.param_stride + c.start;
     const float *gw = a.grads + w * a.worker_stride + c.start;
@@ -275,6 +310,20 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
                     pw[i + t] = pn[t];
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// Plain copy with the same access shape as the kernels above (one wavefront per
+// 1 KiB, one streaming 16-byte load and one written-through 16-byte store per
+// lane).  Reference line for bandwidth and calibration of traffic counters.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kBlock) void k_stream_copy(float *__restrict__ dst,
+                                                        const float *__restrict__ src,
+                                                        long long n_vec)
+{
+    const long long v = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (v < n_vec)
+        st_stream(dst + v * kVec, ld_stream(src + v * kVec));
 }
 
 } // namespace osp
