@@ -31,6 +31,13 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 
+# HBM bytes per launch of k_aggregate_update on the default workload (VGG-16-shaped, layer
+# granularity, chunk 256), average over the stage-1 and stage-2 launch of a step, from the two
+# rocprofv3 --pmc runs summarised in profiles/sync_step_traffic_vgg16_layer.txt:
+# ((7226989 + 815437) + (2503511 + 282450)) / 2 KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
+# 1.0 (what each reads for the 2 GiB k_stream_copy).  Algorithmic: 5534301760.
+AGG_TRAFFIC_VGG16_LAYER = 5544134144
+
 
 def step_bytes(N, M, E2, element):
     E1 = M - E2
@@ -138,7 +145,9 @@ def main() -> int:
     agg_gbps = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": "k_aggregate_update", "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
-                "traffic": None, "launches": agg_launches,
+                "traffic": (AGG_TRAFFIC_VGG16_LAYER if (wl.name == "vgg16" and not element
+                                                        and c.osp_chunk_elems() == 256) else None),
+                "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
     calls = {n: {"ms": round(call_ms[n] / K, 5),
                  "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
