@@ -136,11 +136,118 @@ def test_worker_counts(n_workers):
 
 
 @pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT),
-                                       ("resnet50", GRAN_LAYER)])
+                                       ("resnet50", GRAN_LAYER), ("resnet50", GRAN_ELEMENT)])
 def test_cnn_shaped_two_steps(name, gran):
     say(name, gran)
     sizes = run_steps(W.get(name), gran, 2, threads=8)
     assert sizes[-1] > 0
+
+
+# --------------------------------------------------------------------------
+# full sizes, in the launch configuration the benchmark times (same worker
+# stride, default chunk): every output element against the oracle (its loops
+# run under OpenMP here, which a CPU test shows to be bit-identical)
+# --------------------------------------------------------------------------
+
+def full_size_steps(name, steps):
+    from paper_2306_16926_amd.device import DeviceJob
+    wl = W.get(name)
+    stride = wl.worker_stride()
+    arena = wl.arena_elems()
+    o = make_oracle(wl, omp=True, param_stride=stride)
+    job = DeviceJob(wl.numel, wl.offsets(), arena, wl.n_workers, wl.lr, wl.momentum,
+                    wl.make_params(0), param_stride=stride)
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); job.ctx.osp_set_gib(GRAN_LAYER, all1)
+    sizes = []
+    g = None
+    for step in range(steps):
+        say(" ", name, "step", step, "generate")
+        g = wl.make_grads(0, step, stride=stride, threads=16, out=g)
+        gd = job.upload_grads(g)
+        say(" ", name, "step", step, "oracle")
+        o.sync_step(g, GRAN_LAYER, wl.budget)
+        say(" ", name, "step", step, "gpu")
+        job.sync_step(gd, GRAN_LAYER, wl.budget)
+        compare_gib(job, o, f"{name} step {step}")
+        imp = job.ctx.osp_get_importance()
+        rel = np.abs(imp - o.importance) / np.maximum(np.abs(o.importance), 1e-300)
+        assert rel.max() <= 1e-12
+        # smallest relative gap between neighbours in the ranking: far above the 1e-12 the
+        # two summation orders can differ by, so the ranking cannot flip
+        ranked = np.sort(o.importance)
+        gap = np.min(np.diff(ranked) / ranked[1:])
+        assert gap > 1e-9, gap
+        sizes.append(o.n_stage2)
+        del gd
+    say(" ", name, "compare state")
+    P, V, Pw = job.download()
+    close_enough(P, o.P, name + " P")
+    close_enough(V, o.V, name + " V")
+    for w in range(wl.n_workers):                  # row by row: bounded temporaries
+        close_enough(Pw[w, :arena], o.Pw[w, :arena], f"{name} Pw[{w}]")
+    return sizes
+
+
+def test_full_size_resnet152_layer():
+    say("full size resnet152")
+    sizes = full_size_steps("resnet152", 3)
+    assert sizes[-1] > 0
+
+
+def test_full_size_vgg16_layer():
+    say("full size vgg16")
+    sizes = full_size_steps("vgg16", 2)
+    assert sizes[-1] == 35_597_096                 # everything but the 102.76 M-element fc tensor
+
+
+def test_full_size_resnet152_element_properties():
+    """Element granularity at full size: keys bit-exact against the oracle, and
+    the partition checked through the three properties that determine it
+    uniquely (size, threshold, ties taken in index order); the oracle's own
+    split is a full sort and is compared directly only at smaller sizes."""
+    say("full size resnet152 element")
+    from paper_2306_16926_amd.device import DeviceJob
+    wl = W.get("resnet152")
+    stride, arena = wl.worker_stride(), wl.arena_elems()
+    o = make_oracle(wl, omp=True, param_stride=stride)
+    job = DeviceJob(wl.numel, wl.offsets(), arena, wl.n_workers, wl.lr, wl.momentum,
+                    wl.make_params(0), element_keys=True, param_stride=stride)
+    g = wl.make_grads(0, 0, stride=stride, threads=16)
+    gd = job.upload_grads(g)
+    o.ps_aggregate_update(0, g)
+    job.ctx.osp_ps_aggregate_update(0, gd, stride)
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    keys = job.ctx.osp_get_keys()
+    okeys = o.keys()
+    assert np.array_equal(keys[real], okeys[real])
+    k = wl.budget
+    job.ctx.osp_split(GRAN_ELEMENT, k)
+    _, bits, n2 = job.ctx.osp_get_gib()
+    imp = np.unpackbits(bits.view(np.uint8), bitorder="little")[:arena] == 1
+    assert imp[~real].all()                        # padding is never selected
+    s2 = ~imp & real
+    assert n2 == k == int(s2.sum())
+    T = okeys[s2].max()
+    assert T <= okeys[imp & real].min()
+    tie = real & (okeys == T)
+    tie_idx = np.nonzero(tie)[0]
+    taken = s2[tie_idx]
+    assert (np.diff(taken.astype(np.int8)) <= 0).all()      # taken ties come first in index order
+    assert (okeys[s2] <= T).all() and s2[real & (okeys < T)].all()
+    # then run the staged calls on that bitmap against the oracle (masked kernels at full size)
+    o.set_gib(GRAN_ELEMENT, bits)
+    g = wl.make_grads(0, 1, stride=stride, threads=16, out=g)
+    gd = job.upload_grads(g)
+    o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+    o.ps_aggregate_update(2, g); o.apply_stage(2)
+    c = job.ctx
+    c.osp_ps_aggregate_update(1, gd, stride); c.osp_apply_stage(1); c.osp_lgp_correct(gd, stride)
+    c.osp_ps_aggregate_update(2, gd, stride); c.osp_apply_stage(2)
+    P, V, Pw = job.download()
+    close_enough(P, o.P, "P"); close_enough(V, o.V, "V")
+    for w in range(wl.n_workers):
+        close_enough(Pw[w, :arena], o.Pw[w, :arena], f"Pw[{w}]")
 
 
 # --------------------------------------------------------------------------
