@@ -24,6 +24,14 @@
  *   the host) for that split to finish: it needs the sizes of the two stage
  *   sets to shape its launch, and it is ordered behind the split anyway.
  *
+ * Concurrency
+ *   The calls of one context update shared buffers and must not overlap in
+ *   time with each other: enqueue them on one stream, or order the streams
+ *   with events.  What OSP overlaps is the stage-2 calls of iteration t with
+ *   the COMPUTE of iteration t+1 (Sec. 3.1), which runs on the caller's other
+ *   streams and does not touch these buffers' stage-2 elements.  Different
+ *   contexts are independent.
+ *
  * Errors
  *   Every call returns a status and never throws or aborts.  Argument and
  *   ordering errors are detected on the host before anything is enqueued and

@@ -49,7 +49,7 @@ struct osp_ctx {
 
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_lbase = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
+           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -61,7 +61,8 @@ struct osp_ctx {
     // ---- iteration state machine ----
     bool have_gib = false;
     int gib_gran = OSP_GRAN_LAYER;
-    bool agg1 = false, agg2 = false, single_pass = false, lgp_done = false, applied2 = false;
+    bool agg1 = false, agg2 = false, single_pass = false, lgp_done = false, applied1 = false,
+         applied2 = false;
     bool have_layer_importance = false;
 
     // ---- stage-list lengths (layer-granular GIB) ----
@@ -71,6 +72,7 @@ struct osp_ctx {
     int stage_spans[2] = {0, 0};
     bool counts_pending = false;
     int *pinned_counts = nullptr;              // hipHostMalloc, 2 ints
+    int *pinned_counts_dev = nullptr;          // the same memory as the device sees it
     hipEvent_t counts_ready = nullptr;
 
     std::string err;
@@ -84,6 +86,7 @@ struct osp_ctx {
     double *d_imp() const { return at<double>(off_imp); }
     int *d_order() const { return at<int>(off_order); }
     int *d_lbase() const { return at<int>(off_lbase); }
+    long long *d_rscratch() const { return at<long long>(off_rscratch); }
     Segment *d_segs() const { return at<Segment>(off_segs); }
     int *d_lsb() const { return at<int>(off_lsb); }
     double *d_segsum() const { return at<double>(off_segsum); }
@@ -152,6 +155,7 @@ void layout_workspace(osp_ctx *c)
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
     c->off_order = take((size_t)c->n_tensors * sizeof(int));
     c->off_lbase = take((size_t)c->n_tensors * sizeof(int));
+    c->off_rscratch = take((size_t)c->n_tensors * sizeof(long long));
     c->off_gib = take((size_t)c->n_tensors);
     c->off_state = take(sizeof(SplitState));
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
@@ -188,8 +192,7 @@ osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
     k_stage_lists<<<(ns + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
         ns, ctx->d_spans(), ctx->d_slayer(), ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
         ctx->d_list(1), ctx->d_list(2));
-    OSP_HIP(hipMemcpyAsync(ctx->pinned_counts, ctx->d_state()->stage_spans, 2 * sizeof(int),
-                           hipMemcpyDeviceToHost, s));
+    // the table lengths were written straight into pinned host memory by the kernel before
     OSP_HIP(hipEventRecord(ctx->counts_ready, s));
     ctx->counts_pending = true;
     return OSP_OK;
@@ -381,8 +384,10 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         return fail(ctx, OSP_ERR_BAD_STATE, "cannot rebind while a stage 2 is pending");
     hipStream_t s = (hipStream_t)stream;
     ctx->bound = false;
-    if (!ctx->pinned_counts)
-        OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, 2 * sizeof(int), hipHostMallocDefault));
+    if (!ctx->pinned_counts) {
+        OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, 2 * sizeof(int), hipHostMallocMapped));
+        OSP_HIP(hipHostGetDevicePointer((void **)&ctx->pinned_counts_dev, ctx->pinned_counts, 0));
+    }
     if (!ctx->counts_ready)
         OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
     ctx->counts_pending = false;
@@ -420,7 +425,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     ctx->param_stride = buf->worker_param_stride;
     ctx->bound = true;
     ctx->have_gib = false;
-    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     ctx->have_layer_importance = false;
     return OSP_OK;
 }
@@ -452,7 +457,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
         k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
-                                       ctx->d_state());
+                                       ctx->d_state(), ctx->pinned_counts_dev);
         osp_status st = enqueue_stage_lists(ctx, s);
         if (st != OSP_OK)
             return st;
@@ -481,7 +486,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
     }
     ctx->have_gib = true;
     ctx->gib_gran = granularity;
-    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     return OSP_OK;
 }
 
@@ -584,12 +589,12 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         return st;
     if (stage == 1) {
         ctx->agg1 = true;
-        ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+        ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     } else if (stage == 2) {
         ctx->agg2 = true;
     } else {
         ctx->agg1 = ctx->agg2 = ctx->single_pass = true;
-        ctx->lgp_done = ctx->applied2 = false;
+        ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     }
     return OSP_OK;
 }
@@ -664,7 +669,11 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 1 has not been aggregated in this iteration");
     if (stage != 1 && !(ctx->agg1 && ctx->agg2))
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
-    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
+    // Element-granular stage 2 after this iteration's stage 1 was installed: the stage-1
+    // elements of every replica already equal the PS and have not changed since, so writing
+    // ALL elements gives the same result as writing the stage-2 ones, with full-width stores.
+    const bool overwrite_all = stage == 2 && ctx->gib_gran == OSP_GRAN_ELEMENT && ctx->applied1;
+    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
     unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
     if (listed) {
@@ -695,6 +704,8 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         return st;
     if (stage != 1)
         ctx->applied2 = true;
+    if (stage != 2)
+        ctx->applied1 = true;
     return OSP_OK;
 }
 
@@ -722,7 +733,8 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
                                               ctx->d_imp(), ctx->d_numel(),
                                               ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
-                                              ctx->d_order(), ctx->d_lbase(), ctx->d_state());
+                                              ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
+                                              ctx->d_state(), ctx->pinned_counts_dev);
         osp_status ls = enqueue_stage_lists(ctx, s);
         if (ls != OSP_OK)
             return ls;
@@ -751,7 +763,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         return st;
     ctx->have_gib = true;
     ctx->gib_gran = granularity;
-    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied2 = false;
+    ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     return OSP_OK;
 }
 

@@ -98,14 +98,160 @@ __device__ __forceinline__ unsigned long long importance_rank_key(double x)
 
 constexpr int kRankBlock = 1024;
 
-// Position of every layer's first span inside its stage table, and the table
-// lengths.  Serial over the L layers, in layer order, so the tables come out in
-// ascending address order.
-__device__ __forceinline__ void stage_list_bases(int L, const uint8_t *__restrict__ gib_layer,
-                                                 const int *__restrict__ layer_span_begin,
-                                                 int *__restrict__ layer_base,
-                                                 SplitState *__restrict__ st)
+// Exclusive scan of one value per thread over a workgroup of BLOCK threads, in
+// thread order (shuffles inside a wavefront, wavefront totals through LDS).
+// total (may be null) gets the sum.  All threads of the workgroup must call it.
+template <int BLOCK, class T>
+__device__ __forceinline__ T block_scan_exclusive(T x, T *total)
 {
+    __shared__ T wave_tot[BLOCK / 64];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    T incl = x;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const T up = __shfl_up(incl, off, 64);
+        if (lane >= off)
+            incl += up;
+    }
+    __syncthreads();                   // wave_tot may still be read from a previous call
+    if (lane == 63)
+        wave_tot[wave] = incl;
+    __syncthreads();
+    T base = 0, sum = 0;
+#pragma unroll
+    for (int w = 0; w < BLOCK / 64; ++w) {
+        if (w < wave)
+            base += wave_tot[w];
+        sum += wave_tot[w];
+    }
+    if (total)
+        *total = sum;
+    return base + incl - x;
+}
+
+constexpr int kRankTile = 2048;        // importance keys staged in LDS per pass of the ranking
+
+// One workgroup: finish the layer importances (Eq. 4), rank the layers by
+// (importance, index), cut the ranking where the running size first exceeds
+// the budget, write the layer GIB and the bases of the two stage tables.
+// scratch: [L] long long.
+__global__ __launch_bounds__(kRankBlock) void k_layer_rank(
+    int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
+    double *__restrict__ imp, const long long *__restrict__ numel,
+    const int *__restrict__ layer_span_begin, long long budget,
+    uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
+    long long *__restrict__ scratch, SplitState *__restrict__ st, int *__restrict__ counts_out)
+{
+    __shared__ unsigned long long tile[kRankTile];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+
+    // I^l = sum of the layer's segment sums (fixed order per layer).  Layers with
+    // few segments: one thread each, ascending.  Layers with many: one wavefront
+    // each, lanes take segments lane, lane+64, ... in order, then a fixed butterfly.
+    constexpr int kFewSegments = 16;
+    for (int l = threadIdx.x; l < L; l += kRankBlock) {
+        const int g0 = layer_seg_begin[l], g1 = layer_seg_begin[l + 1];
+        if (g1 - g0 <= kFewSegments) {
+            double s = 0.0;
+            for (int g = g0; g < g1; ++g)
+                s += seg_sum[g];
+            imp[l] = s;
+        }
+    }
+    for (int l = wave; l < L; l += kRankBlock / 64) {
+        const int g0 = layer_seg_begin[l], g1 = layer_seg_begin[l + 1];
+        if (g1 - g0 <= kFewSegments)
+            continue;
+        double s = 0.0;
+        for (int g = g0 + lane; g < g1; g += 64)
+            s += seg_sum[g];
+        s = wave_sum(s);
+        if (lane == 0)
+            imp[l] = s;
+    }
+    __syncthreads();
+
+    // rank[l] = number of layers that come before l in the order (importance, index);
+    // a thread owns layers t, t+1024, ...; all keys pass through LDS in tiles
+    const int per = (L + kRankBlock - 1) / kRankBlock;
+    for (int rep = 0; rep < per; ++rep) {
+        const int l = rep * kRankBlock + (int)threadIdx.x;
+        const unsigned long long mine = l < L ? importance_rank_key(imp[l]) : 0ull;
+        int rank = 0;
+        for (int t0 = 0; t0 < L; t0 += kRankTile) {
+            const int tn = L - t0 < kRankTile ? L - t0 : kRankTile;
+            __syncthreads();
+            for (int j = threadIdx.x; j < tn; j += kRankBlock)
+                tile[j] = importance_rank_key(imp[t0 + j]);
+            __syncthreads();
+            if (l < L)
+                for (int j = 0; j < tn; ++j) {
+                    const unsigned long long other = tile[j];
+                    rank += (other < mine) || (other == mine && t0 + j < l);
+                }
+        }
+        if (l < L) {
+            order[rank] = l;
+            scratch[rank] = numel[l];
+        }
+    }
+    if (threadIdx.x == 0)
+        st->n_stage2 = 0;
+    __syncthreads();
+
+    // running size along the ranking; sizes are positive, so "cumulative size <= budget"
+    // holds exactly on a prefix: the prefix rule needs no further test
+    long long carry = 0;
+    for (int rep = 0; rep < per; ++rep) {
+        const int r = rep * kRankBlock + (int)threadIdx.x;
+        const long long mine = r < L ? scratch[r] : 0;
+        long long total;
+        const long long incl = carry + block_scan_exclusive<kRankBlock, long long>(mine, &total) + mine;
+        if (r < L) {
+            const bool fits = incl <= budget;
+            gib_layer[order[r]] = fits ? 0 : 1;
+            const bool last = r == L - 1 || incl + scratch[r + 1] > budget;
+            if (fits && last)
+                st->n_stage2 = incl;
+        }
+        carry += total;
+    }
+    __syncthreads();
+
+    // bases of the two stage tables: exclusive scans over the layers, in layer order
+    int carry1 = 0, carry2 = 0;
+    for (int rep = 0; rep < per; ++rep) {
+        const int l = rep * kRankBlock + (int)threadIdx.x;
+        int ns = 0;
+        bool important = true;
+        if (l < L) {
+            ns = layer_span_begin[l + 1] - layer_span_begin[l];
+            important = gib_layer[l] != 0;
+        }
+        int tot1, tot2;
+        const int b1 = block_scan_exclusive<kRankBlock, int>(important ? ns : 0, &tot1);
+        const int b2 = block_scan_exclusive<kRankBlock, int>(important ? 0 : ns, &tot2);
+        if (l < L)
+            layer_base[l] = important ? carry1 + b1 : carry2 + b2;
+        carry1 += tot1;
+        carry2 += tot2;
+    }
+    if (threadIdx.x == 0) {
+        st->stage_spans[0] = carry1;
+        st->stage_spans[1] = carry2;
+        counts_out[0] = carry1;        // pinned host memory: the host shapes the next launches
+        counts_out[1] = carry2;
+    }
+}
+
+// After a GIB was uploaded from the host: only the table bases are needed.
+__global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
+                              const int *__restrict__ layer_span_begin,
+                              int *__restrict__ layer_base, SplitState *__restrict__ st,
+                              int *__restrict__ counts_out)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0)
+        return;
     int n1 = 0, n2 = 0;
     for (int l = 0; l < L; ++l) {
         const int ns = layer_span_begin[l + 1] - layer_span_begin[l];
@@ -119,58 +265,8 @@ __device__ __forceinline__ void stage_list_bases(int L, const uint8_t *__restric
     }
     st->stage_spans[0] = n1;
     st->stage_spans[1] = n2;
-}
-
-__global__ __launch_bounds__(kRankBlock) void k_layer_rank(
-    int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
-    double *__restrict__ imp, const long long *__restrict__ numel,
-    const int *__restrict__ layer_span_begin, long long budget,
-    uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
-    SplitState *__restrict__ st)
-{
-    // Eq. 4: finish I^l from the layer's segment sums, in ascending order
-    for (int l = threadIdx.x; l < L; l += kRankBlock) {
-        double s = 0.0;
-        for (int g = layer_seg_begin[l]; g < layer_seg_begin[l + 1]; ++g)
-            s += seg_sum[g];
-        imp[l] = s;
-    }
-    __syncthreads();
-    for (int l = threadIdx.x; l < L; l += kRankBlock) {
-        const unsigned long long mine = importance_rank_key(imp[l]);
-        int rank = 0;
-        for (int j = 0; j < L; ++j) {
-            const unsigned long long other = importance_rank_key(imp[j]);
-            rank += (other < mine) || (other == mine && j < l);
-        }
-        order[rank] = l;
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        long long taken = 0;
-        bool open = true;
-        for (int r = 0; r < L; ++r) {
-            const int l = order[r];
-            if (open && taken + numel[l] <= budget) {
-                taken += numel[l];
-                gib_layer[l] = 0;
-            } else {
-                open = false;      // prefix rule: nothing after the first misfit
-                gib_layer[l] = 1;
-            }
-        }
-        st->n_stage2 = taken;
-        stage_list_bases(L, gib_layer, layer_span_begin, layer_base, st);
-    }
-}
-
-// After a GIB was uploaded from the host: only the table bases are needed.
-__global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
-                              const int *__restrict__ layer_span_begin,
-                              int *__restrict__ layer_base, SplitState *__restrict__ st)
-{
-    if (blockIdx.x == 0 && threadIdx.x == 0)
-        stage_list_bases(L, gib_layer, layer_span_begin, layer_base, st);
+    counts_out[0] = n1;
+    counts_out[1] = n2;
 }
 
 // Fill the two stage tables: span k of layer l goes to position

@@ -80,13 +80,35 @@ __device__ __forceinline__ void st_stream(float *p, f4 v)
 {   // write-once data: streaming, written through at system scope.  Measured on
     // MI355X this policy is the fastest for all three kernels (the 16-replica
     // install gains about 7 % over a plain store, 12 % over "nt" alone).
-    // The store is the last thing a lane does to this address; nothing in the
-    // kernel reads it back, so no wait is needed after it.
-    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt" : : "v"(p), "v"(v) : "memory");
+    // The compiler has no way to ask for this policy on a 16-byte store, hence
+    // the inline instruction.  Two things the compiler would otherwise do for a
+    // store of its own:
+    //  * a store of more than 8 bytes reads its data registers for up to two
+    //    cycles after issue, and the compiler does not look inside an asm block
+    //    when it reuses registers, so the two wait states (s_nop 1) are part of
+    //    the block;
+    //  * no wait on the memory counter is needed: nothing in the kernels reads
+    //    back what they store, and a count the compiler does not know of only
+    //    makes its own waits conservative (the counter retires in order).
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 1"
+                 :
+                 : "v"(p), "v"(v)
+                 : "memory");
 }
 
 // Which of the 4 elements at chunk position i does this call touch?
 // Bit j set = element i+j is inside the chunk and (if MASKED) in the stage.
+//
+// Element-granular stages select scattered elements, but every 16-byte group
+// that holds a selected element is read whole anyway.  When all four elements
+// of a group are real (rem >= 4) the kernels therefore write the group back
+// whole, unselected components with the value they already had: full-width
+// streaming stores instead of up to four 4-byte ones.  This relies on the calls
+// of one context never running concurrently with each other (they share the
+// buffers they update); padding is still never written, because a ragged
+// last group (rem < 4) takes the per-element path.  All lanes of a wave take
+// the same store instruction whatever their masks are, so a wave still writes
+// its 1 KiB as whole lines.
 template <bool MASKED>
 __device__ __forceinline__ unsigned lane_mask(int rem, long long e, int stage,
                                               const uint32_t *__restrict__ bitmap)
@@ -98,6 +120,17 @@ __device__ __forceinline__ unsigned lane_mask(int rem, long long e, int stage,
         m &= (stage == 1) ? imp : (~imp & 0xFu);
     }
     return m;
+}
+
+// Per component: bit j of m set -> a[j], else b[j].
+__device__ __forceinline__ f4 blend(unsigned m, f4 a, f4 b)
+{
+    f4 r;
+    r.x = (m & 1u) ? a.x : b.x;
+    r.y = (m & 2u) ? a.y : b.y;
+    r.z = (m & 4u) ? a.z : b.z;
+    r.w = (m & 8u) ? a.w : b.w;
+    return r;
 }
 
 // Deterministic sum of one double per lane over the wavefront (fixed butterfly).
@@ -175,9 +208,9 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
     const float *Gc = a.grads + c.start;
     double imp = 0.0;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        // (masked: the data loads do not wait for the bitmap word; a group with no
+        // selected element is written back unchanged)
         const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, a.stage, a.bitmap);
-        if (m == 0)
-            continue;
         const f4 p = ld_stream(Pc + i);
         const f4 v = ld_stream(Vc + i);
         // workers in blocks of 16, then 8, 4, 2, 1 (N in binary): ascending order,
@@ -200,15 +233,23 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         const f4 vn = mv + gbar;
         const f4 step = vn * a.lr;
         const f4 pn = p - step;
-        if (m == 0xFu) {
-            imp += (double)q.x; imp += (double)q.y; imp += (double)q.z; imp += (double)q.w;
-            st_stream(Vc + i, vn);
-            st_stream(Pc + i, pn);
+        const bool whole = MASKED ? (int)c.len - (int)i >= kVec : m == 0xFu;
+        if (whole) {
+            if (m & 1u) imp += (double)q.x;
+            if (m & 2u) imp += (double)q.y;
+            if (m & 4u) imp += (double)q.z;
+            if (m & 8u) imp += (double)q.w;
+            st_stream(Vc + i, MASKED ? blend(m, vn, v) : vn);
+            st_stream(Pc + i, MASKED ? blend(m, pn, p) : pn);
             if (KEYS) {
                 u4 k;
                 k.x = importance_key(q.x); k.y = importance_key(q.y);
                 k.z = importance_key(q.z); k.w = importance_key(q.w);
-                st_stream(reinterpret_cast<float *>(a.key + c.start + i), __builtin_bit_cast(f4, k));
+                f4 kf = __builtin_bit_cast(f4, k);
+                float *kp = reinterpret_cast<float *>(a.key + c.start + i);
+                if (MASKED)
+                    kf = blend(m, kf, ld_stream(kp));
+                st_stream(kp, kf);
             }
         } else {
 #pragma unroll
@@ -252,12 +293,23 @@ __global__ __launch_bounds__(kBlock) void k_apply_stage(const ApplyArgs a)
     float *Wc = a.Pw + c.start;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, a.stage, a.bitmap);
-        if (m == 0)
-            continue;
         const f4 p = ld_keep(Pc + i);
-        if (m == 0xFu) {
+        if (!MASKED && m == 0xFu) {
             for (int w = 0; w < N; ++w)
                 st_stream(Wc + (long long)w * a.param_stride + i, p);
+        } else if (MASKED && (int)c.len - (int)i >= kVec) {
+            // all old values first (they do not wait for the bitmap word), then all stores
+            for (int w0 = 0; w0 < N; w0 += 16) {
+                f4 old[16];
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (w0 + j < N)
+                        old[j] = ld_stream(Wc + (long long)(w0 + j) * a.param_stride + i);
+#pragma unroll
+                for (int j = 0; j < 16; ++j)
+                    if (w0 + j < N)
+                        st_stream(Wc + (long long)(w0 + j) * a.param_stride + i, blend(m, p, old[j]));
+            }
         } else {
             for (int w = 0; w < N; ++w)
 #pragma unroll
@@ -295,14 +347,14 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
     const float *gw = a.grads + w * a.worker_stride + c.start;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, 2, a.bitmap);
-        if (m == 0)
-            continue;
         const f4 p = ld_stream(pw + i);
         const f4 g = ld_stream(gw + i);
         const f4 step = g * a.lr;
         const f4 pn = p - step;
-        if (m == 0xFu) {
+        if (!MASKED && m == 0xFu) {
             st_stream(pw + i, pn);
+        } else if (MASKED && (int)c.len - (int)i >= kVec) {
+            st_stream(pw + i, blend(m, pn, p));
         } else {
 #pragma unroll
             for (int t = 0; t < kVec; ++t)
