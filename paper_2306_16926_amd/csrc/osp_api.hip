@@ -8,6 +8,7 @@
 
 #include <cstdarg>
 #include <cstdio>
+#include <chrono>
 #include <cstring>
 #include <new>
 #include <string>
@@ -65,14 +66,16 @@ struct osp_ctx {
          applied2 = false;
     bool have_layer_importance = false;
 
-    // ---- stage-list lengths (layer-granular GIB) ----
-    // The split runs on the device; the two list lengths come back through a
-    // small pinned buffer.  counts_pending: the copy has been enqueued and
-    // counts_ready (an event recorded behind it) tells when it has landed.
+    // ---- stage-table lengths (layer-granular GIB) ----
+    // The split runs on the device; the ranking kernel publishes the two table
+    // lengths and a sequence number in pinned host memory.  counts_pending: a split
+    // with sequence number split_seq has been enqueued and its lengths have not been
+    // read yet.  counts_ready is an event recorded behind the split (fallback wait).
     int stage_spans[2] = {0, 0};
     bool counts_pending = false;
-    int *pinned_counts = nullptr;              // hipHostMalloc, 2 ints
-    int *pinned_counts_dev = nullptr;          // the same memory as the device sees it
+    unsigned split_seq = 0;
+    StageCounts *pinned_counts = nullptr;      // hipHostMalloc (mapped)
+    StageCounts *pinned_counts_dev = nullptr;  // the same memory as the device sees it
     hipEvent_t counts_ready = nullptr;
 
     std::string err;
@@ -203,9 +206,25 @@ osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
 osp_status stage_counts(osp_ctx *ctx)
 {
     if (ctx->counts_pending) {
-        OSP_HIP(hipEventSynchronize(ctx->counts_ready));
-        ctx->stage_spans[0] = ctx->pinned_counts[0];
-        ctx->stage_spans[1] = ctx->pinned_counts[1];
+        // Poll the sequence number instead of waiting for the whole split to retire: the
+        // lengths are published by the ranking kernel, so the next launch can be enqueued
+        // while the table-filling kernel behind it still runs.  Bounded: after 2 s fall back
+        // to the event (which also surfaces a device error instead of spinning on it).
+        const volatile unsigned *seq = &ctx->pinned_counts->seq;
+        const auto t0 = std::chrono::steady_clock::now();
+        unsigned spins = 0;
+        while (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq) {
+            if ((++spins & 1023u) == 0 &&
+                std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+                OSP_HIP(hipEventSynchronize(ctx->counts_ready));
+                if (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq)
+                    return fail(ctx, OSP_ERR_HIP, "the split did not publish its stage-table lengths");
+                break;
+            }
+            __builtin_ia32_pause();
+        }
+        ctx->stage_spans[0] = ctx->pinned_counts->n[0];
+        ctx->stage_spans[1] = ctx->pinned_counts->n[1];
         ctx->counts_pending = false;
         const long long ns = (long long)ctx->spans.size();
         if (ctx->stage_spans[0] < 0 || ctx->stage_spans[1] < 0 ||
@@ -385,8 +404,11 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     hipStream_t s = (hipStream_t)stream;
     ctx->bound = false;
     if (!ctx->pinned_counts) {
-        OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, 2 * sizeof(int), hipHostMallocMapped));
+        OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, sizeof(StageCounts), hipHostMallocMapped));
         OSP_HIP(hipHostGetDevicePointer((void **)&ctx->pinned_counts_dev, ctx->pinned_counts, 0));
+        ctx->pinned_counts->n[0] = ctx->pinned_counts->n[1] = 0;
+        ctx->pinned_counts->seq = 0;
+        ctx->split_seq = 0;
     }
     if (!ctx->counts_ready)
         OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
@@ -457,7 +479,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
         k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
-                                       ctx->d_state(), ctx->pinned_counts_dev);
+                                       ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
         osp_status st = enqueue_stage_lists(ctx, s);
         if (st != OSP_OK)
             return st;
@@ -734,7 +756,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
                                               ctx->d_imp(), ctx->d_numel(),
                                               ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                                               ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
-                                              ctx->d_state(), ctx->pinned_counts_dev);
+                                              ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
         osp_status ls = enqueue_stage_lists(ctx, s);
         if (ls != OSP_OK)
             return ls;

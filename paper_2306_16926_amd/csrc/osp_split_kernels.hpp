@@ -19,6 +19,22 @@ namespace osp {
 constexpr int kSplitBlock = 256;       // 4 wavefronts
 constexpr int kSplitStride = kSplitBlock * kVec;
 
+// Written by the device into pinned host memory: the lengths of the two stage
+// tables, then a sequence number (released at system scope) that tells the
+// host which split they belong to.
+struct StageCounts {
+    int n[2];
+    unsigned int seq;
+    unsigned int pad;
+};
+
+__device__ __forceinline__ void publish_counts(StageCounts *out, int n1, int n2, unsigned seq)
+{
+    out->n[0] = n1;
+    out->n[1] = n2;
+    __hip_atomic_store(&out->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 struct SplitState {                    // one per context, in the workspace
     long long n_stage2;                // elements in stage 2 under the current GIB
     int stage_spans[2];                // spans in the stage-1 / stage-2 table (layer GIB)
@@ -140,7 +156,8 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     double *__restrict__ imp, const long long *__restrict__ numel,
     const int *__restrict__ layer_span_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
-    long long *__restrict__ scratch, SplitState *__restrict__ st, int *__restrict__ counts_out)
+    long long *__restrict__ scratch, SplitState *__restrict__ st,
+    StageCounts *__restrict__ counts_out, unsigned seq)
 {
     __shared__ unsigned long long tile[kRankTile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -239,8 +256,7 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     if (threadIdx.x == 0) {
         st->stage_spans[0] = carry1;
         st->stage_spans[1] = carry2;
-        counts_out[0] = carry1;        // pinned host memory: the host shapes the next launches
-        counts_out[1] = carry2;
+        publish_counts(counts_out, carry1, carry2, seq);   // the host shapes the next launches
     }
 }
 
@@ -248,7 +264,7 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
 __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
                               const int *__restrict__ layer_span_begin,
                               int *__restrict__ layer_base, SplitState *__restrict__ st,
-                              int *__restrict__ counts_out)
+                              StageCounts *__restrict__ counts_out, unsigned seq)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0)
         return;
@@ -265,8 +281,7 @@ __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
     }
     st->stage_spans[0] = n1;
     st->stage_spans[1] = n2;
-    counts_out[0] = n1;
-    counts_out[1] = n2;
+    publish_counts(counts_out, n1, n2, seq);
 }
 
 // Fill the two stage tables: span k of layer l goes to position
