@@ -20,6 +20,7 @@ namespace {
 
 constexpr int kDefaultChunkElems = kStride;     // one float4 per lane
 constexpr size_t kAlign = 256;
+constexpr int kFanoutMaxWorkers = 8;           // install: fan-out kernel up to here, sweep above
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -697,29 +698,59 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     const bool overwrite_all = stage == 2 && ctx->gib_gran == OSP_GRAN_ELEMENT && ctx->applied1;
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
-    unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
+    unsigned n_spans = (unsigned)ctx->spans.size();
     if (listed) {
         osp_status sc = stage_counts(ctx);
         if (sc != OSP_OK)
             return sc;
-        n_groups = (unsigned)ctx->stage_spans[stage - 1] * kSpanChunks;
+        n_spans = (unsigned)ctx->stage_spans[stage - 1];
     }
-    ApplyArgs a;
-    a.spans = listed ? ctx->d_list(stage) : ctx->d_spans();
-    a.chunk_elems = ctx->chunk_elems;
-    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
-    a.P = ctx->P;
-    a.Pw = ctx->Pw;
-    a.param_stride = ctx->param_stride;
-    a.n_workers = ctx->n_workers;
-    a.stage = stage;
-    const dim3 grid(n_groups), block(kBlock);
     hipStream_t s = (hipStream_t)stream;
-    if (n_groups > 0) {
-        if (masked)
-            k_apply_stage<true><<<grid, block, 0, s>>>(a);
-        else
-            k_apply_stage<false><<<grid, block, 0, s>>>(a);
+    const Span *table = listed ? ctx->d_list(stage) : ctx->d_spans();
+    const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    if (ctx->n_workers > kFanoutMaxWorkers) {
+        ApplyArgs a;
+        a.spans = table;
+        a.bitmap = bitmap;
+        a.P = ctx->P;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.n_spans = n_spans;
+        a.pieces_per_span = (unsigned)(kSpanChunks * ctx->chunk_elems / kPiece);
+        // blocks of about 8 MB of parameters (at least one span)
+        const long long span_bytes = (long long)kSpanChunks * ctx->chunk_elems * 4;
+        a.spans_per_block = (unsigned)((8LL << 20) / span_bytes > 0 ? (8LL << 20) / span_bytes : 1);
+        a.n_workers = (unsigned)ctx->n_workers;
+        a.stage = stage;
+        const long long n_blocks = (n_spans + a.spans_per_block - 1) / a.spans_per_block;
+        const long long n_groups = n_blocks * a.spans_per_block * a.pieces_per_span * a.n_workers;
+        if (n_groups > 0x7FFFFFFFLL)
+            return fail(ctx, OSP_ERR_UNSUPPORTED,
+                        "install launch of %lld workgroups exceeds the grid limit", n_groups);
+        const dim3 grid((unsigned)n_groups), block(kApplyBlock);
+        if (n_groups > 0) {
+            if (masked)
+                k_apply_stage_sweep<true><<<grid, block, 0, s>>>(a);
+            else
+                k_apply_stage_sweep<false><<<grid, block, 0, s>>>(a);
+        }
+    } else {
+        FanoutArgs a;
+        a.spans = table;
+        a.chunk_elems = ctx->chunk_elems;
+        a.bitmap = bitmap;
+        a.P = ctx->P;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.n_workers = ctx->n_workers;
+        a.stage = stage;
+        const dim3 grid(n_spans * kSpanChunks), block(kBlock);
+        if (n_spans > 0) {
+            if (masked)
+                k_apply_stage_fanout<true><<<grid, block, 0, s>>>(a);
+            else
+                k_apply_stage_fanout<false><<<grid, block, 0, s>>>(a);
+        }
     }
     osp_status st = launch_check(ctx, "k_apply_stage");
     if (st != OSP_OK)
