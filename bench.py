@@ -7,8 +7,11 @@ paper's order (Sec. 3.1; Eq. 5 ordering):
     osp_ps_aggregate_update(2) -> osp_apply_stage(2) -> osp_split
 All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 
-Algorithmic bytes of a step (E1 + E2 = M parameters, E2 = stage-2 elements in
-effect during the step, N workers):
+`value` is computed on the ALGORITHMIC bytes of a step as the metric defines them
+(E1 + E2 = M parameters, E2 = stage-2 elements in effect during the step, N workers);
+`GBps_on_bytes_moved` uses the smaller byte count the step really needs when LGP
+reads the stale stage-2 values once from the PS instead of once per replica
+(4 (N-1) E2 bytes less):
     aggregate+update  4 (N + 4) E_s     per stage  (N grads + P + V read, P + V written)
     apply_stage       4 (N + 1) E_s     per stage  (P read once, N replicas written)
     lgp_correct       12 N E2                      (P_w and g_w read, P_w written)
@@ -139,6 +142,11 @@ def main() -> int:
         total_bytes += sum(b.values())
     ms_per_step = elapsed * 1e3 / K
     gbps = total_bytes / elapsed / 1e9
+    lgp_shared = c.osp_lgp_read_shared()
+    moved_bytes = total_bytes - (sum(4 * (N - 1) * int(n2[i]) for i in range(K)) if lgp_shared
+                                 and not element else 0)
+    if lgp_shared and element:                  # masked sweep: whole arena per replica, P once
+        moved_bytes = None
 
     # dominant kernel: the aggregate+update kernel, launched twice per step
     agg_launches = 2 * K
@@ -212,6 +220,9 @@ def main() -> int:
         "sync_steps_per_s": round(K / elapsed, 2),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "GB_per_step": round(total_bytes / K / 1e9, 4),
+        "lgp_reads_ps_once": bool(lgp_shared),
+        "GB_moved_per_step": None if moved_bytes is None else round(moved_bytes / K / 1e9, 4),
+        "GBps_on_bytes_moved": None if moved_bytes is None else round(moved_bytes / elapsed / 1e9, 1),
         "calls_second_pass": calls,
         "copy_GBps_same_box": round(copy_gbps, 1),
         "roofline": roofline,

@@ -102,6 +102,12 @@ typedef struct {
     int64_t worker_param_stride;   /* elements, multiple of 4, >= arena_elems */
     void *workspace;               /* 256-byte aligned scratch, >= osp_workspace_bytes() */
     size_t workspace_bytes;
+    int32_t replicas_in_sync;      /* nonzero: the caller asserts that every replica equals
+                                      ps_param on every tensor element right now.  Lets the
+                                      first iteration's LGP read the PS values once instead of
+                                      N replica values; from the second iteration on the
+                                      library knows by itself.  While bound, replicas must be
+                                      written through this library only. */
 } osp_buffers;
 
 /* Create / destroy a context (host only; no GPU needed). *out is NULL on error. */
@@ -197,6 +203,11 @@ osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *strea
 /* Message for the last error on this context ("" if none).  With ctx == NULL,
  * the message of the last failed osp_create on this thread. */
 const char *osp_last_error(const osp_ctx *ctx);
+
+/* 1 if the last osp_lgp_correct read the stale stage-2 values once from the PS
+ * arena (replicas known to be in sync) instead of once per replica; 0 otherwise.
+ * For callers that account for the bytes a step really moves. */
+int32_t osp_lgp_read_shared(const osp_ctx *ctx);
 
 /* Geometry, for callers that size launches or report traffic. */
 int32_t osp_chunk_elems(const osp_ctx *ctx);

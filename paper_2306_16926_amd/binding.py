@@ -40,7 +40,8 @@ class osp_config(C.Structure):
 class osp_buffers(C.Structure):
     _fields_ = [("ps_param", C.c_void_p), ("ps_momentum", C.c_void_p),
                 ("worker_param", C.c_void_p), ("worker_param_stride", C.c_int64),
-                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t)]
+                ("workspace", C.c_void_p), ("workspace_bytes", C.c_size_t),
+                ("replicas_in_sync", C.c_int32)]
 
 
 def _load() -> C.CDLL:
@@ -82,6 +83,8 @@ def _load() -> C.CDLL:
     lib.osp_stream_copy.restype = C.c_int
     lib.osp_last_error.argtypes = [vp]
     lib.osp_last_error.restype = C.c_char_p
+    lib.osp_lgp_read_shared.argtypes = [vp]
+    lib.osp_lgp_read_shared.restype = C.c_int32
     lib.osp_chunk_elems.argtypes = [vp]
     lib.osp_chunk_elems.restype = C.c_int32
     lib.osp_n_chunks.argtypes = [vp]
@@ -95,7 +98,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
            "osp_stream_copy",
-           "osp_last_error", "osp_chunk_elems", "osp_n_chunks"]
+           "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared"]
 
 
 def _ptr(t) -> int:
@@ -164,15 +167,20 @@ class Context:
     def osp_chunk_elems(self) -> int:
         return int(lib.osp_chunk_elems(self._h))
 
+    def osp_lgp_read_shared(self) -> bool:
+        return bool(lib.osp_lgp_read_shared(self._h))
+
     def osp_n_chunks(self) -> int:
         return int(lib.osp_n_chunks(self._h))
 
     def osp_bind(self, ps_param, ps_momentum, worker_param, worker_param_stride: int,
-                 workspace, workspace_bytes: Optional[int] = None, stream=None) -> None:
+                 workspace, workspace_bytes: Optional[int] = None, stream=None,
+                 replicas_in_sync: bool = False) -> None:
         if workspace_bytes is None:
             workspace_bytes = workspace.numel() * workspace.element_size()
         buf = osp_buffers(_ptr(ps_param), _ptr(ps_momentum), _ptr(worker_param),
-                          int(worker_param_stride), _ptr(workspace), int(workspace_bytes))
+                          int(worker_param_stride), _ptr(workspace), int(workspace_bytes),
+                          1 if replicas_in_sync else 0)
         self._check(lib.osp_bind(self._h, C.byref(buf), _stream(stream)))
         self._keep = (ps_param, ps_momentum, worker_param, workspace)   # borrowed buffers stay alive
 

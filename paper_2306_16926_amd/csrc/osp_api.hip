@@ -66,6 +66,10 @@ struct osp_ctx {
     bool agg1 = false, agg2 = false, single_pass = false, lgp_done = false, applied1 = false,
          applied2 = false;
     bool have_layer_importance = false;
+    // replicas_synced: every replica equals the PS on every element (after an iteration that
+    // installed both stages, or by the caller's word at bind).  iter_synced: that held when
+    // the current iteration began, i.e. the stage-2 replica values are the PS's stale ones.
+    bool replicas_synced = false, iter_synced = false, last_lgp_shared = false;
 
     // ---- stage-table lengths (layer-granular GIB) ----
     // The split runs on the device; the ranking kernel publishes the two table
@@ -362,6 +366,8 @@ size_t osp_workspace_bytes(const osp_ctx *ctx) { return ctx ? ctx->ws_bytes : 0;
 
 int32_t osp_chunk_elems(const osp_ctx *ctx) { return ctx ? ctx->chunk_elems : 0; }
 
+int32_t osp_lgp_read_shared(const osp_ctx *ctx) { return ctx && ctx->last_lgp_shared ? 1 : 0; }
+
 int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->n_chunks : 0; }
 
 const char *osp_last_error(const osp_ctx *ctx)
@@ -447,6 +453,8 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     ctx->Pw = buf->worker_param;
     ctx->param_stride = buf->worker_param_stride;
     ctx->bound = true;
+    ctx->replicas_synced = buf->replicas_in_sync != 0;
+    ctx->iter_synced = false;
     ctx->have_gib = false;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     ctx->have_layer_importance = false;
@@ -610,6 +618,10 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     st = launch_check(ctx, "k_aggregate_update");
     if (st != OSP_OK)
         return st;
+    if (stage != 2) {                   // a new iteration begins: the PS moves away from the replicas
+        ctx->iter_synced = ctx->replicas_synced;
+        ctx->replicas_synced = false;
+    }
     if (stage == 1) {
         ctx->agg1 = true;
         ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
@@ -640,35 +652,72 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
     if (ctx->applied2)
         return fail(ctx, OSP_ERR_BAD_STATE, "LGP after the stage-2 correction would undo it");
     const bool masked = ctx->gib_gran == OSP_GRAN_ELEMENT;
-    unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
+    unsigned n_spans = (unsigned)ctx->spans.size();
     if (!masked) {
         st = stage_counts(ctx);
         if (st != OSP_OK)
             return st;
-        n_groups = (unsigned)ctx->stage_spans[1] * kSpanChunks;
+        n_spans = (unsigned)ctx->stage_spans[1];
     }
-    LgpArgs a;
-    a.spans = masked ? ctx->d_spans() : ctx->d_list(2);
-    a.chunk_elems = ctx->chunk_elems;
-    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
-    a.Pw = ctx->Pw;
-    a.param_stride = ctx->param_stride;
-    a.grads = grads;
-    a.worker_stride = worker_stride;
-    a.lr = ctx->lr;
+    const Span *table = masked ? ctx->d_spans() : ctx->d_list(2);
+    const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     hipStream_t s = (hipStream_t)stream;
-    if (n_groups > 0) {
-        // grid.y is limited to 65535: sweep the workers in slabs of that size
-        for (int w0 = 0; w0 < ctx->n_workers; w0 += 65535) {
-            const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
-            LgpArgs b = a;
-            b.Pw = a.Pw + (long long)w0 * a.param_stride;
-            b.grads = a.grads + (long long)w0 * a.worker_stride;
-            const dim3 grid(n_groups, (unsigned)nw), block(kBlock);
+    // The replicas' stage-2 values are still the PS's (stale) ones: read them once from the PS.
+    // Needs the PS's stage-2 values untouched (stage 2 not aggregated yet) and, for an
+    // element-granular GIB, this iteration's stage 1 already installed.
+    const bool shared_read = ctx->iter_synced && !ctx->agg2 && (!masked || ctx->applied1);
+    ctx->last_lgp_shared = shared_read;
+    if (shared_read) {
+        LgpSweepArgs a;
+        a.spans = table;
+        a.bitmap = bitmap;
+        a.P = ctx->P;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.grads = grads;
+        a.worker_stride = worker_stride;
+        a.n_spans = n_spans;
+        a.pieces_per_span = (unsigned)(kSpanChunks * ctx->chunk_elems / kPiece);
+        const long long span_bytes = (long long)kSpanChunks * ctx->chunk_elems * 4;
+        a.spans_per_block = (unsigned)((8LL << 20) / span_bytes > 0 ? (8LL << 20) / span_bytes : 1);
+        a.n_workers = (unsigned)ctx->n_workers;
+        a.lr = ctx->lr;
+        const long long n_blocks = (n_spans + a.spans_per_block - 1) / a.spans_per_block;
+        const long long n_groups = n_blocks * a.spans_per_block * a.pieces_per_span * a.n_workers;
+        if (n_groups > 0x7FFFFFFFLL)
+            return fail(ctx, OSP_ERR_UNSUPPORTED, "LGP launch of %lld workgroups exceeds the grid limit",
+                        n_groups);
+        const dim3 grid((unsigned)n_groups), block(kApplyBlock);
+        if (n_groups > 0) {
             if (masked)
-                k_lgp_correct<true><<<grid, block, 0, s>>>(b);
+                k_lgp_sweep<true><<<grid, block, 0, s>>>(a);
             else
-                k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+                k_lgp_sweep<false><<<grid, block, 0, s>>>(a);
+        }
+    } else {
+        LgpArgs a;
+        a.spans = table;
+        a.chunk_elems = ctx->chunk_elems;
+        a.bitmap = bitmap;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.grads = grads;
+        a.worker_stride = worker_stride;
+        a.lr = ctx->lr;
+        const unsigned n_groups = n_spans * kSpanChunks;
+        if (n_groups > 0) {
+            // grid.y is limited to 65535: sweep the workers in slabs of that size
+            for (int w0 = 0; w0 < ctx->n_workers; w0 += 65535) {
+                const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
+                LgpArgs b = a;
+                b.Pw = a.Pw + (long long)w0 * a.param_stride;
+                b.grads = a.grads + (long long)w0 * a.worker_stride;
+                const dim3 grid(n_groups, (unsigned)nw), block(kBlock);
+                if (masked)
+                    k_lgp_correct<true><<<grid, block, 0, s>>>(b);
+                else
+                    k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+            }
         }
     }
     st = launch_check(ctx, "k_lgp_correct");
@@ -759,6 +808,8 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         ctx->applied2 = true;
     if (stage != 2)
         ctx->applied1 = true;
+    if (ctx->applied1 && ctx->applied2)
+        ctx->replicas_synced = true;    // every element of every replica equals the PS again
     return OSP_OK;
 }
 

@@ -439,4 +439,65 @@ __global__ __launch_bounds__(kBlock) void k_stream_copy(float *__restrict__ dst,
         st_stream(dst + v * kVec, ld_stream(src + v * kVec));
 }
 
+// ---------------------------------------------------------------------------
+// LGP when every replica is known to equal the PS on the stage-2 elements (the
+// previous iteration installed both stages and nothing else writes replicas):
+// P_w = P - lr g_w then gives bit for bit what P_w = P_w - lr g_w gives, and the
+// N reads of stale replica values become one read of the PS values.  Same
+// blocked per-replica sweep as the install: the parameter block comes from HBM
+// once and from cache N-1 times; per replica one gradient stream in, one
+// parameter stream out.
+// Element-granular GIB (MASKED): legal once this iteration's stage 1 has been
+// installed; the unselected elements of a group then already equal the PS, so
+// the group is written whole as "P, minus lr g on the stage-2 elements".
+// ---------------------------------------------------------------------------
+struct LgpSweepArgs {
+    const Span *spans;
+    const uint32_t *bitmap;
+    const float *P;
+    float *Pw;
+    long long param_stride;
+    const float *grads;
+    long long worker_stride;
+    unsigned n_spans;
+    unsigned pieces_per_span;
+    unsigned spans_per_block;
+    unsigned n_workers;
+    float lr;
+};
+
+template <bool MASKED>
+__global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
+{
+    const unsigned per_worker = a.spans_per_block * a.pieces_per_span;
+    const unsigned per_block = per_worker * a.n_workers;
+    const unsigned blk = blockIdx.x / per_block, r = blockIdx.x % per_block;
+    const unsigned w = r / per_worker, q = r % per_worker;
+    const unsigned si = blk * a.spans_per_block + q / a.pieces_per_span;
+    if (si >= a.n_spans)
+        return;
+    const Span s = a.spans[si];
+    const int off = (int)(q % a.pieces_per_span) * kPiece + (int)threadIdx.x * kVec;
+    if (off >= s.n_elems)
+        return;
+    const int rem = s.n_elems - off;
+    const long long e = s.start + off;
+    float *dst = a.Pw + (long long)w * a.param_stride + e;
+    const unsigned m = lane_mask<MASKED>(rem, e, 2, a.bitmap);
+    const f4 p = ld_keep(a.P + e);             // kept in cache for the other replicas' sweeps
+    const f4 g = ld_stream(a.grads + (long long)w * a.worker_stride + e);
+    const f4 step = g * a.lr;
+    const f4 pn = p - step;
+    if (!MASKED && m == 0xFu) {
+        st_stream(dst, pn);
+    } else if (MASKED && rem >= kVec) {
+        st_stream(dst, blend(m, pn, p));
+    } else {
+#pragma unroll
+        for (int j = 0; j < kVec; ++j)
+            if (m & (1u << j))
+                dst[j] = pn[j];
+    }
+}
+
 } // namespace osp

@@ -18,7 +18,7 @@ class DeviceJob:
                  momentum: float, params_host: np.ndarray,
                  worker_weight=None, element_keys: bool = False, chunk_elems: int = 0,
                  param_stride: Optional[int] = None, device: str = "cuda:0",
-                 pad_fill: Optional[float] = None):
+                 pad_fill: Optional[float] = None, declare_in_sync: bool = True):
         self.dev = torch.device(device)
         self.arena = int(arena_elems)
         self.N = int(n_workers)
@@ -36,7 +36,9 @@ class DeviceJob:
         nbytes = self.ctx.osp_workspace_bytes()
         # torch's caching allocator hands out 512-byte aligned blocks
         self.workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.dev)
-        self.ctx.osp_bind(self.P, self.V, self.Pw, self.param_stride, self.workspace, nbytes)
+        # the replicas were just filled from P, so the job may say so
+        self.ctx.osp_bind(self.P, self.V, self.Pw, self.param_stride, self.workspace, nbytes,
+                          replicas_in_sync=declare_in_sync)
 
     def upload_grads(self, grads_host: np.ndarray) -> torch.Tensor:
         assert grads_host.dtype == np.float32 and grads_host.ndim == 2

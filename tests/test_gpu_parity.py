@@ -25,13 +25,15 @@ def say(*a):
 
 
 def device_job(wl, seed=0, align=None, weights=None, element_keys=False, chunk_elems=0,
-               lr=None, mu=None, param_stride=None, pad_fill=None, params=None):
+               lr=None, mu=None, param_stride=None, pad_fill=None, params=None,
+               declare_in_sync=True):
     from paper_2306_16926_amd.device import DeviceJob
     p = wl.make_params(seed, align) if params is None else params
     return DeviceJob(wl.numel, wl.offsets(align), wl.arena_elems(align), wl.n_workers,
                      wl.lr if lr is None else lr, wl.momentum if mu is None else mu, p,
                      worker_weight=weights, element_keys=element_keys, chunk_elems=chunk_elems,
-                     param_stride=param_stride, pad_fill=pad_fill)
+                     param_stride=param_stride, pad_fill=pad_fill,
+                     declare_in_sync=declare_in_sync)
 
 
 def close_enough(got, want, what):
@@ -291,6 +293,46 @@ def test_calls_one_by_one_with_injected_gib(gran):
     compare_gib(job, o, "split layer after staged " + str(gran))
     imp = job.ctx.osp_get_importance()
     assert np.allclose(imp, o.importance, rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("order", ["rs_lgp_last", "lgp_before_install", "lgp_after_stage2", "no_install1"])
+@pytest.mark.parametrize("n_workers", [3, 12])
+def test_lgp_paths_and_call_orders(gran, order, n_workers):
+    """LGP has two implementations (per-replica values, or the PS values read once when the
+    replicas are known to be in sync); every legal order of calls must give the oracle's
+    result whichever one runs, over iterations that do and do not restore consistency."""
+    say("lgp paths", gran, order, n_workers)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 70000], n_workers, 0.5, align=4, config_id=60 + n_workers)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True, declare_in_sync=(order != "lgp_before_install"))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    for step in range(4):
+        g = wl.make_grads(0, step); gd = job.upload_grads(g); s_ = g.shape[1]
+        if order == "rs_lgp_last":
+            seq = ["agg1", "apply1", "lgp", "agg2", "apply2"]
+        elif order == "lgp_before_install":
+            seq = ["agg1", "lgp", "apply1", "agg2", "apply2"]
+        elif order == "lgp_after_stage2":
+            seq = ["agg1", "apply1", "agg2", "lgp", "apply2"]
+        else:                                   # stage 1 never installed on odd steps: replicas drift
+            seq = ["agg1", "lgp", "agg2", "apply2"] if step % 2 else ["agg1", "apply1", "lgp", "agg2", "apply2"]
+        for call in seq:
+            if call == "agg1":
+                o.ps_aggregate_update(1, g); c.osp_ps_aggregate_update(1, gd, s_)
+            elif call == "agg2":
+                o.ps_aggregate_update(2, g); c.osp_ps_aggregate_update(2, gd, s_)
+            elif call == "apply1":
+                o.apply_stage(1); c.osp_apply_stage(1)
+            elif call == "apply2":
+                o.apply_stage(2); c.osp_apply_stage(2)
+            else:
+                o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+            compare_state(job, o, f"{order} step {step} after {call}")
+        o.split(gran, wl.budget); c.osp_split(gran, wl.budget)
+        compare_gib(job, o, f"{order} step {step}")
 
 
 def test_single_pass_equals_two_stages():
