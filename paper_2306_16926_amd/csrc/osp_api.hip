@@ -741,10 +741,17 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 1 has not been aggregated in this iteration");
     if (stage != 1 && !(ctx->agg1 && ctx->agg2))
         return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
-    // Element-granular stage 2 after this iteration's stage 1 was installed: the stage-1
-    // elements of every replica already equal the PS and have not changed since, so writing
-    // ALL elements gives the same result as writing the stage-2 ones, with full-width stores.
-    const bool overwrite_all = stage == 2 && ctx->gib_gran == OSP_GRAN_ELEMENT && ctx->applied1;
+    // Element-granular GIB: two situations in which writing ALL elements gives the same result
+    // as writing the stage's elements only, with full-width stores and no read of old values:
+    //  * stage 2 after this iteration's stage 1 was installed: the stage-1 elements of every
+    //    replica already equal the PS and have not changed since;
+    //  * stage 1 when the replicas were in sync as the iteration began and neither LGP nor the
+    //    stage-2 aggregate has run yet: the stage-2 elements of every replica still equal the
+    //    PS's (both hold the stale value).
+    const bool element = ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const bool overwrite_all =
+        element && ((stage == 2 && ctx->applied1) ||
+                    (stage == 1 && ctx->iter_synced && !ctx->agg2 && !ctx->lgp_done));
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
     unsigned n_spans = (unsigned)ctx->spans.size();
