@@ -54,8 +54,14 @@ _libs = {}
 
 def _load(omp: bool):
     if omp not in _libs:
-        build()
-        lib = C.CDLL(_LIB_OMP if omp else _LIB)
+        # OSP_ORACLE_LIB: load this library instead (the test that plants mistakes into
+        # copies of the oracle source uses it to show that the pins notice them)
+        override = os.environ.get("OSP_ORACLE_LIB")
+        if override:
+            lib = C.CDLL(override)
+        else:
+            build()
+            lib = C.CDLL(_LIB_OMP if omp else _LIB)
         mp, gp, fp = C.POINTER(_Model), C.POINTER(_Gib), C.POINTER(C.c_float)
         lib.osp_oracle_aggregate_update.argtypes = [mp, gp, C.c_int, fp, fp, fp, C.c_int64, fp]
         lib.osp_oracle_aggregate_update.restype = None

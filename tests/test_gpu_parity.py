@@ -389,7 +389,8 @@ def _split_from_keys(keys_f32, budget, numel=None):
 
 
 @pytest.mark.parametrize("case", ["all_equal", "all_zero", "inside_ties", "ties_across_tiles",
-                                  "nan_inf", "neg_zero", "denormal", "two_values_multi_tensor"])
+                                  "nan_inf", "neg_zero", "denormal", "two_values_multi_tensor",
+                                  "nan_payloads"])
 def test_split_element_adversarial(case):
     say("adversarial", case)
     rng = np.random.default_rng(4)
@@ -409,6 +410,11 @@ def test_split_element_adversarial(case):
         k = n - 3
     elif case == "neg_zero":
         keys = np.zeros(n, F); keys[::2] = -0.0; keys[7] = 1.0; k = 25_000
+    elif case == "nan_payloads":
+        keys = rng.standard_normal(n).astype(F)
+        bits = keys.view(np.uint32)
+        bits[10] = 0x7FFFFFFF; bits[9000] = 0x7FC00001; bits[30_000] = 0xFFC12345; bits[30_001] = 0x7F800001
+        k = n - 2                               # two of the four NaNs stay in stage 1: the last two
     elif case == "denormal":
         keys = (rng.standard_normal(n) * 1e-41).astype(F)      # subnormal magnitudes
         keys[::5] = 0.0

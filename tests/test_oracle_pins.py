@@ -161,6 +161,36 @@ def test_aggregate_matches_bruteforce(weighted):
         assert same(o.P, b.P) and same(o.V, b.V) and same(o.q, b.q)
 
 
+@pytest.mark.parametrize("weighted", [False, True])
+def test_worker_and_replica_strides_are_honoured(weighted):
+    """Gradient arenas and replicas that are further apart than one arena: a full
+    step must match the brute force (which slices the arena out of every row),
+    and the gap between arenas must stay untouched."""
+    wl = small_wl(n_workers=3)
+    arena = wl.arena_elems()
+    gs, ps = arena + 12, arena + 8
+    wts = np.array([0.5, 0.125, 0.375], F) if weighted else None
+    o = make_oracle(wl, weights=wts, param_stride=ps)
+    o.Pw[:, arena:] = 77.0
+    b = brute.Brute(wl.numel, wl.offsets(), arena, 3, wl.lr, wl.momentum, wts)
+    b.load(o.P.copy())
+    rng = np.random.default_rng(1)
+    gib = random_layer_gib(rng, wl.n_tensors)
+    o.set_gib(GRAN_LAYER, gib)
+    b.s2 = brute.stage2_mask_from_layer_gib(gib, wl.numel, wl.offsets(), arena)
+    g = np.full((3, gs), 5.0, F)                 # garbage in the gap
+    g[:, :arena] = wl.make_grads(0, 0)
+    for call in ("agg1", "apply1", "lgp", "agg2", "apply2"):
+        if call.startswith("agg"):
+            o.ps_aggregate_update(int(call[-1]), g); b.agg(int(call[-1]), g)
+        elif call.startswith("apply"):
+            o.apply_stage(int(call[-1])); b.apply(int(call[-1]))
+        else:
+            o.lgp_correct(g); b.lgp(g)
+        assert same(o.P, b.P) and same(o.V, b.V) and same(o.Pw[:, :arena], b.Pw), call
+    assert (o.Pw[:, arena:] == 77.0).all()
+
+
 def test_power_of_two_weights_equal_plain_mean():
     """alpha_w = 1/4 for four workers: scaling by a power of two commutes with
     rounding, so the weighted form must reproduce the unweighted one bit for bit
@@ -390,7 +420,7 @@ def _element_case(keys_f32, budget):
 
 
 @pytest.mark.parametrize("case", ["all_equal", "all_zero", "k0", "kM", "inside_ties",
-                                  "ties_across_word", "nan_inf", "neg_zero"])
+                                  "ties_across_word", "nan_inf", "neg_zero", "nan_payloads"])
 def test_split_element_adversarial(case):
     n = 200
     rng = np.random.default_rng(2)
@@ -410,6 +440,14 @@ def test_split_element_adversarial(case):
         keys = rng.standard_normal(n).astype(F)
         keys[5] = np.nan; keys[100] = np.inf; keys[150] = -np.inf; keys[160] = np.nan
         k = n - 3
+    elif case == "nan_payloads":
+        # NaNs with different payloads are ONE value: among them the index decides.
+        # The NaN at the lower index carries the larger payload, so an order on raw
+        # bit patterns would put it last instead of first.
+        keys = rng.standard_normal(n).astype(F)
+        bits = keys.view(np.uint32)
+        bits[10] = 0x7FFFFFFF; bits[60] = 0x7FC00001; bits[120] = 0xFFC12345
+        k = n - 2                                # exactly one NaN goes to stage 2: the first
     else:
         keys = np.zeros(n, F); keys[::2] = -0.0; keys[7] = 1.0; k = 100
     imp, o = _element_case(keys, k)
@@ -429,6 +467,8 @@ def test_split_element_adversarial(case):
         assert imp[5] and imp[160] and imp[150] and not imp[100]
     if case == "all_equal":
         assert not imp[:k].any() and imp[k:].all()
+    if case == "nan_payloads":
+        assert not imp[10] and imp[60] and imp[120]
 
 
 @pytest.mark.parametrize("frac", [0.0, 0.3, 0.5, 1.0])
