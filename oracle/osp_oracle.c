@@ -31,8 +31,8 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py
  * against closed forms, a NumPy brute force, torch.optim.SGD and the
- * invariants the paper states (Sec. 4.3 degradation to BSP / ASP, "no
- * gradients are dropped" in Sec. 2.2.2 / 3.2).
+ * invariants the paper states (Sec. 4.3 degradation to BSP / ASP; Sec. 2.2.2
+ * and 3.2: OSP discards no gradient).
  */
 #include <math.h>
 #include <stdint.h>
