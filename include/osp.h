@@ -200,6 +200,26 @@ osp_status osp_get_keys(osp_ctx *ctx, uint32_t *key_host, void *stream);
  * part of the synchronization step.  At most 2^31 KiB per call. */
 osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/*
+ * S(G^u) tuning (Sec. 4.1.2).  Host-only scalar functions: no context, no GPU.
+ *
+ * osp_ics_upper_bound: Eq. 5 as printed, U_max = b (1 + lr) T_c / N, the most
+ * that fits into one iteration's compute window; bandwidth in elements per
+ * second, loss_rate in [0, 1], t_compute in seconds.  Returns 0 for arguments
+ * that are not finite and non-negative or for n_workers < 1.
+ *
+ * osp_tune_budget: Algorithm 1.  U_max is first capped at 80 % of the model;
+ * epoch 1 synchronizes everything in stage 1 (returns 0 and the caller keeps
+ * loss_1 as L); epoch i > 1 returns floor((1 - loss_i / L) * U_max), clamped to
+ * [0, capped U_max] (a loss above L gives 0).  The result is the budget_elems
+ * argument of osp_split.  Returns -1 for arguments that are not finite, a
+ * non-positive L, epoch < 1 or a negative model size.
+ */
+double osp_ics_upper_bound(double bandwidth_elems_per_s, double loss_rate, double t_compute_s,
+                           int32_t n_workers);
+int64_t osp_tune_budget(int32_t epoch, double loss_i, double loss_1, double u_max,
+                        int64_t model_elems);
+
 /* Message for the last error on this context ("" if none).  With ctx == NULL,
  * the message of the last failed osp_create on this thread. */
 const char *osp_last_error(const osp_ctx *ctx);

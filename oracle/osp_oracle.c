@@ -330,3 +330,35 @@ int64_t osp_oracle_split_element(const osp_oracle_model *m, const float *q,
     free(a);
     return budget_elems;
 }
+
+/*
+ * S(G^u) tuning.  Eq. 5: the in-computation stage must fit into the compute
+ * time of one iteration, T_c >= N S(G^u) / (b (1 + lr)), lr being the loss rate
+ * of the link, hence U_max = b (1 + lr) T_c / N (taken as printed).
+ */
+double osp_oracle_ics_upper_bound(double b, double loss_rate, double t_c, int n_workers)
+{
+    return b * (1.0 + loss_rate) * t_c / (double)n_workers;
+}
+
+/*
+ * Algorithm 1, one epoch of it: U_max is limited to 80 % of the model size; in
+ * epoch 1 everything is synchronized in stage 1 (S = 0) and the loss of that
+ * epoch becomes L; in epoch i > 1, S = (1 - loss_i / L) U_max.  Whole elements,
+ * never negative (a loss above L means no stage 2), never above U_max.
+ */
+int64_t osp_oracle_tune_budget(int epoch, double loss_i, double L, double u_max,
+                               int64_t model_elems)
+{
+    double limit = 0.8 * (double)model_elems;
+    if (u_max > limit)
+        u_max = limit;
+    if (epoch == 1)
+        return 0;
+    double share = 1.0 - loss_i / L;
+    if (share < 0.0)
+        share = 0.0;
+    if (share > 1.0)
+        share = 1.0;
+    return (int64_t)floor(share * u_max);
+}

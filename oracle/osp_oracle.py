@@ -81,8 +81,22 @@ def _load(omp: bool):
         lib.osp_oracle_keys.restype = None
         lib.osp_oracle_split_element.argtypes = [mp, fp, C.c_int64, C.POINTER(C.c_uint32)]
         lib.osp_oracle_split_element.restype = C.c_int64
+        lib.osp_oracle_ics_upper_bound.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int]
+        lib.osp_oracle_ics_upper_bound.restype = C.c_double
+        lib.osp_oracle_tune_budget.argtypes = [C.c_int, C.c_double, C.c_double, C.c_double, C.c_int64]
+        lib.osp_oracle_tune_budget.restype = C.c_int64
         _libs[omp] = lib
     return _libs[omp]
+
+
+def ics_upper_bound(b: float, loss_rate: float, t_c: float, n_workers: int) -> float:
+    """Eq. 5."""
+    return float(_load(False).osp_oracle_ics_upper_bound(b, loss_rate, t_c, n_workers))
+
+
+def tune_budget(epoch: int, loss_i: float, L: float, u_max: float, model_elems: int) -> int:
+    """Algorithm 1, one epoch."""
+    return int(_load(False).osp_oracle_tune_budget(epoch, loss_i, L, u_max, model_elems))
 
 
 class OracleOSP:

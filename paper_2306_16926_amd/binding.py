@@ -81,6 +81,10 @@ def _load() -> C.CDLL:
     lib.osp_get_keys.restype = C.c_int
     lib.osp_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.osp_stream_copy.restype = C.c_int
+    lib.osp_ics_upper_bound.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int32]
+    lib.osp_ics_upper_bound.restype = C.c_double
+    lib.osp_tune_budget.argtypes = [C.c_int32, C.c_double, C.c_double, C.c_double, i64]
+    lib.osp_tune_budget.restype = i64
     lib.osp_last_error.argtypes = [vp]
     lib.osp_last_error.restype = C.c_char_p
     lib.osp_lgp_read_shared.argtypes = [vp]
@@ -97,7 +101,7 @@ lib = _load()
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
-           "osp_stream_copy",
+           "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared"]
 
 
@@ -237,6 +241,14 @@ def osp_stream_copy(dst, src, nbytes: int, stream=None) -> None:
     st = lib.osp_stream_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream))
     if st != OSP_OK:
         raise OspError(st, "osp_stream_copy")
+
+
+def osp_ics_upper_bound(bandwidth_elems_per_s, loss_rate, t_compute_s, n_workers) -> float:
+    return float(lib.osp_ics_upper_bound(bandwidth_elems_per_s, loss_rate, t_compute_s, n_workers))
+
+
+def osp_tune_budget(epoch, loss_i, loss_1, u_max, model_elems) -> int:
+    return int(lib.osp_tune_budget(epoch, loss_i, loss_1, u_max, model_elems))
 
 
 # module-level aliases with the C names, taking the context first

@@ -9,6 +9,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <chrono>
+#include <cmath>
 #include <cstring>
 #include <new>
 #include <string>
@@ -890,6 +891,34 @@ osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *strea
         k_stream_copy<<<(unsigned)groups, kBlock, 0, (hipStream_t)stream>>>((float *)dst,
                                                                            (const float *)src, n_vec);
     return hipGetLastError() == hipSuccess ? OSP_OK : OSP_ERR_HIP;
+}
+
+double osp_ics_upper_bound(double bandwidth_elems_per_s, double loss_rate, double t_compute_s,
+                           int32_t n_workers)
+{
+    if (!(std::isfinite(bandwidth_elems_per_s) && bandwidth_elems_per_s >= 0.0) ||
+        !(std::isfinite(loss_rate) && loss_rate >= 0.0) ||
+        !(std::isfinite(t_compute_s) && t_compute_s >= 0.0) || n_workers < 1)
+        return 0.0;
+    return bandwidth_elems_per_s * (1.0 + loss_rate) * t_compute_s / (double)n_workers;
+}
+
+int64_t osp_tune_budget(int32_t epoch, double loss_i, double loss_1, double u_max,
+                        int64_t model_elems)
+{
+    if (epoch < 1 || model_elems < 0 || !std::isfinite(loss_i) || !std::isfinite(loss_1) ||
+        !(loss_1 > 0.0) || !std::isfinite(u_max) || u_max < 0.0)
+        return -1;
+    const double cap = 0.8 * (double)model_elems;
+    const double u = u_max < cap ? u_max : cap;
+    if (epoch == 1)
+        return 0;
+    double s = (1.0 - loss_i / loss_1) * u;
+    if (!(s > 0.0))
+        s = 0.0;
+    if (s > u)
+        s = u;
+    return (int64_t)std::floor(s);
 }
 
 osp_status osp_get_importance(osp_ctx *ctx, double *imp_host, void *stream)

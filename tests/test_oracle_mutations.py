@@ -40,6 +40,10 @@ MUTATIONS = [
     ("element_takes_largest", "return x->key < y->key ? -1 : 1;", "return x->key < y->key ? 1 : -1;"),
     ("nan_not_canonical", "if (isnan(q))\n        return 0x7FC00000u;", "if (0)\n        return 0x7FC00000u;"),
     ("apply_wrong_source", "Pw[(int64_t)w * param_stride + k] = P[k];", "Pw[(int64_t)w * param_stride + k] = P[k + 1 < m->arena_elems ? k + 1 : k];"),
+    ("tuner_cap", "double limit = 0.8 * (double)model_elems;", "double limit = 0.9 * (double)model_elems;"),
+    ("tuner_first_epoch", "    if (epoch == 1)\n        return 0;\n    double share", "    if (epoch == 0)\n        return 0;\n    double share"),
+    ("tuner_share_inverted", "double share = 1.0 - loss_i / L;", "double share = loss_i / L;"),
+    ("tuner_bound_divides_by_workers", "return b * (1.0 + loss_rate) * t_c / (double)n_workers;", "return b * (1.0 + loss_rate) * t_c;"),
     ("layer_sum_drops_last", "for (int64_t j = 0; j < m->numel[l]; ++j) {\n            double x", "for (int64_t j = 0; j + 1 < m->numel[l]; ++j) {\n            double x"),
 ]
 
@@ -59,7 +63,8 @@ def test_pins_catch_planted_mistake(tmp_path, name, old, new):
     subprocess.check_call(["gcc", *CFLAGS, str(src), "-o", str(lib), "-lm"])
     env = dict(os.environ, OSP_ORACLE_LIB=str(lib))
     r = subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-p", "no:cacheprovider",
-                        os.path.join(ROOT, "tests", "test_oracle_pins.py")],
+                        os.path.join(ROOT, "tests", "test_oracle_pins.py"),
+                        os.path.join(ROOT, "tests", "test_tuner.py")],
                        cwd=ROOT, env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, timeout=300)
     assert r.returncode != 0, f"no pin noticed the planted mistake '{name}'"
     assert b"failed" in r.stdout or b"error" in r.stdout.lower()
