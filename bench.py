@@ -61,7 +61,7 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=40)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16",
-                    choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16"])
+                    choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16", "bert_base"])
     ap.add_argument("--granularity", default="layer", choices=["layer", "element"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-elems", type=int, default=0)

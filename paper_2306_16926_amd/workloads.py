@@ -84,6 +84,20 @@ def vgg16_shapes(n_classes: int = 1000) -> List[int]:
     return out
 
 
+def bert_base_shapes(vocab: int = 30522, hidden: int = 768, layers: int = 12,
+                     intermediate: int = 3072, max_pos: int = 512, type_vocab: int = 2) -> List[int]:
+    """BERT-base encoder with pooler, parameter tensors in PyTorch order."""
+    out = [vocab * hidden, max_pos * hidden, type_vocab * hidden, hidden, hidden]
+    for _ in range(layers):
+        for _ in range(4):                       # query, key, value, attention output
+            out += [hidden * hidden, hidden]
+        out += [hidden, hidden]                  # LayerNorm
+        out += [hidden * intermediate, intermediate, intermediate * hidden, hidden]
+        out += [hidden, hidden]                  # LayerNorm
+    out += [hidden * hidden, hidden]             # pooler
+    return out
+
+
 # ----------------------------------------------------------------------------
 # gradient distributions (one call fills one tensor of one worker)
 # ----------------------------------------------------------------------------
@@ -249,6 +263,10 @@ WORKLOADS = {
     "resnet152": _mk("resnet152", 3, 8, resnet_bottleneck_shapes((3, 8, 36, 3), 1000), 0.7,
                      _grad_outliers),
     "vgg16": _mk("vgg16", 4, 16, vgg16_shapes(), 0.5, _grad_normal(5e-4)),
+    # not one of the five stated configurations: the paper's NLP model (Sec. 5.1.2), same
+    # recipe as resnet18 (8 workers, per-tensor gradient scale)
+    "bert_base": _mk("bert_base", 5, 8, bert_base_shapes(), 0.5, _grad_per_tensor_scale,
+                     per_tensor_scale=True),
 }
 
 # exact tensor and parameter counts of the shape rules above
@@ -258,6 +276,7 @@ EXPECTED_COUNTS = {
     "resnet50": (161, 25_557_032),
     "resnet152": (467, 60_192_808),
     "vgg16": (32, 138_357_544),
+    "bert_base": (199, 109_482_240),
 }
 
 

@@ -197,6 +197,12 @@ def test_full_size_resnet152_layer():
     assert sizes[-1] > 0
 
 
+def test_full_size_bert_base_layer():
+    say("full size bert_base")
+    sizes = full_size_steps("bert_base", 2)
+    assert sizes[-1] > 0
+
+
 def test_full_size_vgg16_layer():
     say("full size vgg16")
     sizes = full_size_steps("vgg16", 2)
