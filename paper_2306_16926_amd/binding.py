@@ -45,6 +45,11 @@ class osp_buffers(C.Structure):
 
 
 def _load() -> C.CDLL:
+    # PyTorch ships its own copy of the HIP runtime (same soname as the system one).  Two
+    # copies in one process do not share a device context: memory allocated by torch would be
+    # foreign to this library, and the second copy reports that it finds no device.  Importing
+    # torch first makes libosp.so bind to the runtime torch has already loaded.
+    import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
         raise ImportError(
             f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
