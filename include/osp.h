@@ -89,8 +89,8 @@ typedef struct {
                                       NULL for equal shares 1/N; copied */
     int32_t element_keys;          /* nonzero: osp_ps_aggregate_update also stores every
                                       element's importance key, which makes
-                                      osp_split(OSP_GRAN_ELEMENT) legal (costs 4 B/element of
-                                      workspace and of traffic) */
+                                      osp_split(OSP_GRAN_ELEMENT) legal (costs 8 B/element of
+                                      workspace: the keys and the kept stage-2 aggregate) */
     int32_t chunk_elems;           /* work-chunk size in elements, multiple of 256;
                                       0 = library default (256: one float4 per lane) */
 } osp_config;
@@ -171,6 +171,13 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
  * Every operation is a separately rounded fp32 operation (no fused
  * multiply-add).  grads: DEVICE, read-only; worker w's arena starts at
  * grads + w*worker_stride (elements, multiple of 4, >= arena_elems).
+ *
+ * Both stages of an iteration see one gradient per worker, cut in two by the
+ * GIB (Sec. 3.1).  With an element-granular GIB the stage-1 call therefore
+ * keeps the aggregate of the stage-2 elements in the workspace, and a stage-2
+ * call that is handed the same `grads` pointer and stride reuses it instead of
+ * reading the N arenas again: between the two calls these arenas must not
+ * change.  A stage-2 call with any other pointer or stride aggregates afresh.
  */
 osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
                                    int64_t worker_stride, void *stream);

@@ -52,7 +52,7 @@ struct osp_ctx {
 
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0,
+           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -71,6 +71,11 @@ struct osp_ctx {
     // installed both stages, or by the caller's word at bind).  iter_synced: that held when
     // the current iteration began, i.e. the stage-2 replica values are the PS's stale ones.
     bool replicas_synced = false, iter_synced = false, last_lgp_shared = false;
+    // element-granular stage 1 leaves the aggregate of the stage-2 elements in the stash;
+    // valid for a stage-2 call on the same gradient arenas
+    bool stash_valid = false;
+    const float *stash_grads = nullptr;
+    long long stash_stride = 0;
 
     // ---- stage-table lengths (layer-granular GIB) ----
     // The split runs on the device; the ranking kernel publishes the two table
@@ -104,6 +109,7 @@ struct osp_ctx {
     SplitState *d_state() const { return at<SplitState>(off_state); }
     float *d_weights() const { return at<float>(off_weights); }
     uint32_t *d_key() const { return at<uint32_t>(off_key); }
+    float *d_stash() const { return at<float>(off_stash); }
     uint32_t *d_bitmap() const { return at<uint32_t>(off_bitmap); }
     unsigned long long *d_hist(int pass) const
     {
@@ -170,6 +176,7 @@ void layout_workspace(osp_ctx *c)
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
     if (c->element_keys) {
         c->off_key = take((size_t)c->arena * sizeof(uint32_t));
+        c->off_stash = take((size_t)c->arena * sizeof(float));
         c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
         c->off_hist = take((size_t)3 * kRadixBins * sizeof(unsigned long long));
         c->off_tile_ties = take((size_t)c->n_tiles * sizeof(unsigned int));
@@ -456,6 +463,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     ctx->bound = true;
     ctx->replicas_synced = buf->replicas_in_sync != 0;
     ctx->iter_synced = false;
+    ctx->stash_valid = false;
     ctx->have_gib = false;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     ctx->have_layer_importance = false;
@@ -596,6 +604,14 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     a.weights = ctx->d_weights();
     a.partial = ctx->d_partial(stage == 2 ? 1 : 0);
     a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+    a.partial_other = nullptr;
+    a.stash = nullptr;
+    if (masked && stage == 1) {
+        a.stash = ctx->d_stash();
+        a.partial_other = ctx->d_partial(1);
+    }
+    const bool from_stash = masked && stage == 2 && ctx->stash_valid && ctx->stash_grads == grads &&
+                            ctx->stash_stride == (long long)worker_stride;
     a.n_workers = ctx->n_workers;
     a.stage = stage;
     a.inv_n = 1.0f / (float)ctx->n_workers;
@@ -604,7 +620,18 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     const dim3 grid(n_groups), block(kBlock);
     hipStream_t s = (hipStream_t)stream;
     const int variant = (masked ? 4 : 0) | (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
-    if (n_groups > 0) {               // an empty stage launches nothing
+    if (from_stash) {
+        StashArgs sa;
+        sa.spans = a.spans;
+        sa.chunk_elems = a.chunk_elems;
+        sa.bitmap = a.bitmap;
+        sa.P = ctx->P;
+        sa.V = ctx->V;
+        sa.stash = ctx->d_stash();
+        sa.lr = ctx->lr;
+        sa.mu = ctx->mu;
+        k_update_from_stash<<<grid, block, 0, s>>>(sa);
+    } else if (n_groups > 0) {        // an empty stage launches nothing
     switch (variant) {
     case 0: k_aggregate_update<false, false, false><<<grid, block, 0, s>>>(a); break;
     case 1: k_aggregate_update<false, false, true><<<grid, block, 0, s>>>(a); break;
@@ -622,6 +649,9 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     if (stage != 2) {                   // a new iteration begins: the PS moves away from the replicas
         ctx->iter_synced = ctx->replicas_synced;
         ctx->replicas_synced = false;
+        ctx->stash_valid = masked && stage == 1;
+        ctx->stash_grads = grads;
+        ctx->stash_stride = (long long)worker_stride;
     }
     if (stage == 1) {
         ctx->agg1 = true;

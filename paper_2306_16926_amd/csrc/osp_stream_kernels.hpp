@@ -161,7 +161,9 @@ struct AggArgs {
     long long worker_stride;
     const float *weights;              // [N] device, used when WEIGHTED
     double *partial;                   // [n_chunks] importance partial of this stage
+    double *partial_other;             // [n_chunks] partial of the other stage (with stash)
     uint32_t *key;                     // [arena] when KEYS
+    float *stash;                      // [arena] or null: see k_aggregate_update
     int n_workers;
     int stage;
     float inv_n, lr, mu;
@@ -206,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
     float *Pc = a.P + c.start;
     float *Vc = a.V + c.start;
     const float *Gc = a.grads + c.start;
-    double imp = 0.0;
+    double imp = 0.0, imp_other = 0.0;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         // (masked: the data loads do not wait for the bitmap word; a group with no
         // selected element is written back unchanged)
@@ -233,12 +235,25 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         const f4 vn = mv + gbar;
         const f4 step = vn * a.lr;
         const f4 pn = p - step;
-        const bool whole = MASKED ? (int)c.len - (int)i >= kVec : m == 0xFu;
+        const int rem = (int)c.len - (int)i;
+        const bool whole = MASKED ? rem >= kVec : m == 0xFu;
+        // Element-granular stage 1 with a stash: every group that holds a stage-1 element is
+        // read whole, so the aggregate of its stage-2 elements is at hand too.  It is kept
+        // (stash), together with their keys and importance, which depend only on the aggregate
+        // and on PS values that stay untouched until stage 2; the stage-2 call of the same
+        // gradients then needs one stream instead of N (k_update_from_stash).
+        const bool stashing = MASKED && a.stash != nullptr;
+        const unsigned valid = rem >= kVec ? 0xFu : ((1u << rem) - 1u);
+        const unsigned other = stashing ? (valid & ~m) : 0u;
         if (whole) {
             if (m & 1u) imp += (double)q.x;
             if (m & 2u) imp += (double)q.y;
             if (m & 4u) imp += (double)q.z;
             if (m & 8u) imp += (double)q.w;
+            if (other & 1u) imp_other += (double)q.x;
+            if (other & 2u) imp_other += (double)q.y;
+            if (other & 4u) imp_other += (double)q.z;
+            if (other & 8u) imp_other += (double)q.w;
             st_stream(Vc + i, MASKED ? blend(m, vn, v) : vn);
             st_stream(Pc + i, MASKED ? blend(m, pn, p) : pn);
             if (KEYS) {
@@ -247,13 +262,15 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
                 k.z = importance_key(q.z); k.w = importance_key(q.w);
                 f4 kf = __builtin_bit_cast(f4, k);
                 float *kp = reinterpret_cast<float *>(a.key + c.start + i);
-                if (MASKED)
+                if (MASKED && !stashing)
                     kf = blend(m, kf, ld_stream(kp));
                 st_stream(kp, kf);
             }
+            if (stashing)
+                st_stream(a.stash + c.start + i, gbar);
         } else {
 #pragma unroll
-            for (int j = 0; j < kVec; ++j)
+            for (int j = 0; j < kVec; ++j) {
                 if (m & (1u << j)) {
                     imp += (double)q[j];
                     Vc[i + j] = vn[j];
@@ -261,11 +278,67 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
                     if (KEYS)
                         a.key[c.start + i + j] = importance_key(q[j]);
                 }
+                if (other & (1u << j)) {
+                    imp_other += (double)q[j];
+                    a.key[c.start + i + j] = importance_key(q[j]);
+                    a.stash[c.start + i + j] = gbar[j];
+                }
+            }
         }
     }
     const double total = wave_sum(imp);
     if (threadIdx.x == 0)
         a.partial[c.chunk] = total;
+    if (MASKED && a.stash != nullptr) {
+        const double total_other = wave_sum(imp_other);
+        if (threadIdx.x == 0)
+            a.partial_other[c.chunk] = total_other;
+    }
+}
+
+// Stage 2 of an element-granular iteration whose stage 1 left the aggregate in the
+// stash: V = mu V + gbar, P = P - lr V on the stage-2 elements; keys and importance
+// of these elements were written by stage 1.
+struct StashArgs {
+    const Span *spans;
+    int chunk_elems;
+    const uint32_t *bitmap;
+    float *P;
+    float *V;
+    const float *stash;
+    float lr, mu;
+};
+
+__global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
+{
+    Piece c;
+    if (!owned_piece(a.spans, a.chunk_elems, c))
+        return;
+    float *Pc = a.P + c.start;
+    float *Vc = a.V + c.start;
+    const float *Sc = a.stash + c.start;
+    for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        const int rem = (int)c.len - (int)i;
+        const unsigned m = lane_mask<true>(rem, c.start + i, 2, a.bitmap);
+        const f4 p = ld_stream(Pc + i);
+        const f4 v = ld_stream(Vc + i);
+        const f4 gbar = ld_stream(Sc + i);
+        const f4 mv = v * a.mu;
+        const f4 vn = mv + gbar;
+        const f4 step = vn * a.lr;
+        const f4 pn = p - step;
+        if (rem >= kVec) {
+            st_stream(Vc + i, blend(m, vn, v));
+            st_stream(Pc + i, blend(m, pn, p));
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j)
+                if (m & (1u << j)) {
+                    Vc[i + j] = vn[j];
+                    Pc[i + j] = pn[j];
+                }
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------

@@ -301,6 +301,55 @@ def test_calls_one_by_one_with_injected_gib(gran):
     assert np.allclose(imp, o.importance, rtol=1e-12, atol=0)
 
 
+@pytest.mark.parametrize("stage2_input", ["same_buffer", "copy_elsewhere", "other_values", "other_stride"])
+def test_element_stage2_gradient_sources(stage2_input):
+    """Element-granular stage 1 keeps the aggregate of the stage-2 elements, and stage 2
+    uses it only when it is handed the very gradient arenas of stage 1.  Any other
+    buffer (equal values or not) must be aggregated afresh; keys and importance of the
+    stage-2 elements then follow the stage-2 gradients, as in the oracle."""
+    say("stage-2 gradient source", stage2_input)
+    wl = W.custom([37, 1, 128, 5, 9000, 64, 3, 4096, 4097, 30001], 6, 0.5, align=4, config_id=23)
+    rng = np.random.default_rng(11)
+    arena = wl.arena_elems()
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    for step in range(3):
+        gib = random_bits(rng, arena, real)
+        o.set_gib(GRAN_ELEMENT, gib); c.osp_set_gib(GRAN_ELEMENT, gib)
+        g1 = wl.make_grads(0, step)
+        stride1 = g1.shape[1]
+        if stage2_input == "other_values":
+            g2 = wl.make_grads(1, step)
+        elif stage2_input == "other_stride":
+            g2 = np.zeros((wl.n_workers, stride1 + 8), F)
+            g2[:, :stride1] = g1
+        else:
+            g2 = g1
+        gd1 = job.upload_grads(g1)
+        gd2 = gd1 if stage2_input == "same_buffer" else job.upload_grads(g2)
+        o.ps_aggregate_update(1, g1); c.osp_ps_aggregate_update(1, gd1, stride1)
+        compare_state(job, o, "agg1")
+        o.apply_stage(1); c.osp_apply_stage(1)
+        o.lgp_correct(g1); c.osp_lgp_correct(gd1, stride1)
+        compare_state(job, o, "lgp")
+        o.ps_aggregate_update(2, g2); c.osp_ps_aggregate_update(2, gd2, g2.shape[1])
+        compare_state(job, o, "agg2")
+        o.apply_stage(2); c.osp_apply_stage(2)
+        compare_state(job, o, "apply2")
+        keys = c.osp_get_keys()
+        assert np.array_equal(keys[real], o.keys()[real]), "element keys"
+        if step % 2 == 0:
+            o.split(GRAN_LAYER, wl.budget); c.osp_split(GRAN_LAYER, wl.budget)
+            imp = c.osp_get_importance()
+            assert np.allclose(imp, o.importance, rtol=1e-12, atol=0)
+            compare_gib(job, o, f"layer split after element stages, step {step}")
+        else:
+            o.split(GRAN_ELEMENT, wl.budget); c.osp_split(GRAN_ELEMENT, wl.budget)
+            compare_gib(job, o, f"element split, step {step}")
+
+
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
 @pytest.mark.parametrize("order", ["rs_lgp_last", "lgp_before_install", "lgp_after_stage2", "no_install1"])
 @pytest.mark.parametrize("n_workers", [3, 12])
