@@ -63,6 +63,8 @@ def main() -> int:
     ap.add_argument("--workload", default="vgg16",
                     choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16", "bert_base"])
     ap.add_argument("--granularity", default="layer", choices=["layer", "element"])
+    ap.add_argument("--calls", default="six", choices=["six", "windows"],
+                    help="six single-stage calls per step, or the RS and ICS window calls")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -106,8 +108,12 @@ def main() -> int:
     c.osp_set_gib(0, np.ones(wl.n_tensors, np.uint8))     # iteration 1 is BSP (Algorithm 1)
     n2_log = torch.zeros(K + 1, dtype=torch.int64).pin_memory()
     n2_ptr = n2_log.data_ptr()
+    windows = args.calls == "windows"
     for i in range(Wm):
-        job.sync_step(gsets[i % 2], gran, wl.budget)
+        if windows:
+            job.sync_step_windows(gsets[i % 2], gran, wl.budget)
+        else:
+            job.sync_step(gsets[i % 2], gran, wl.budget)
     c.osp_read_n_stage2_async(n2_ptr)                      # E2 in effect during timed step 0
     names = ["agg1", "apply1", "lgp", "agg2", "apply2", "split"]
     # Timed region: K whole steps.  Inside it only the dominant kernel (the aggregate, launched
@@ -121,12 +127,16 @@ def main() -> int:
     for i in range(K):
         g = gsets[(Wm + i) % 2]
         e = ev[i]
-        e[0].record(); c.osp_ps_aggregate_update(1, g, stride); e[1].record()
-        c.osp_apply_stage(1)
-        c.osp_lgp_correct(g, stride)
-        e[2].record(); c.osp_ps_aggregate_update(2, g, stride); e[3].record()
-        c.osp_apply_stage(2)
-        c.osp_split(gran, wl.budget)
+        if windows:                              # the RS window is the bracketed launch
+            e[0].record(); c.osp_rs_window(g, stride); e[1].record()
+            c.osp_ics_window(g, stride, gran, wl.budget)
+        else:
+            e[0].record(); c.osp_ps_aggregate_update(1, g, stride); e[1].record()
+            c.osp_apply_stage(1)
+            c.osp_lgp_correct(g, stride)
+            e[2].record(); c.osp_ps_aggregate_update(2, g, stride); e[3].record()
+            c.osp_apply_stage(2)
+            c.osp_split(gran, wl.budget)
         c.osp_read_n_stage2_async(n2_ptr + 8 * (i + 1))
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
@@ -137,25 +147,33 @@ def main() -> int:
     agg_bytes_sum = 0
     for i in range(K):
         b = step_bytes(N, M, int(n2[i]), element)
-        agg_ms_sum += ev[i][0].elapsed_time(ev[i][1]) + ev[i][2].elapsed_time(ev[i][3])
-        agg_bytes_sum += b["agg1"] + b["agg2"]
+        if windows:
+            agg_ms_sum += ev[i][0].elapsed_time(ev[i][1])
+            agg_bytes_sum += b["agg1"] + b["apply1"] + b["lgp"]
+        else:
+            agg_ms_sum += ev[i][0].elapsed_time(ev[i][1]) + ev[i][2].elapsed_time(ev[i][3])
+            agg_bytes_sum += b["agg1"] + b["agg2"]
         total_bytes += sum(b.values())
     ms_per_step = elapsed * 1e3 / K
     gbps = total_bytes / elapsed / 1e9
     lgp_shared = c.osp_lgp_read_shared()
     moved_bytes = total_bytes - (sum(4 * (N - 1) * int(n2[i]) for i in range(K)) if lgp_shared
                                  and not element else 0)
-    if lgp_shared and element:                  # masked sweep: whole arena per replica, P once
+    if (lgp_shared and element) or windows:     # whole groups / fused passes: not itemised here
         moved_bytes = None
 
     # dominant kernel: the aggregate+update kernel, launched twice per step
-    agg_launches = 2 * K
+    agg_launches = K if windows else 2 * K
+    fused_rs = windows and (c.osp_windows_fused() & 1) != 0
+    kernel = ("k_aggregate_update" if not windows else
+              ("k_rs_window_element" if element else "k_window_layer") if fused_rs else
+              "osp_rs_window (three single-stage kernels)")
     agg_ms = agg_ms_sum / agg_launches
     agg_bytes = agg_bytes_sum / agg_launches
     agg_gbps = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0
-    roofline = {"bound": "hbm", "kernel": "k_aggregate_update", "achieved": round(agg_gbps, 1),
+    roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
-                "traffic": (AGG_TRAFFIC_VGG16_LAYER if (wl.name == "vgg16" and not element
+                "traffic": (AGG_TRAFFIC_VGG16_LAYER if (wl.name == "vgg16" and not element and not windows
                                                         and c.osp_chunk_elems() == 256) else None),
                 "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
@@ -168,13 +186,19 @@ def main() -> int:
     for i in range(K2):
         g = gsets[(Wm + K + i) % 2]
         e = ev2[i]
-        e[0].record(); c.osp_ps_aggregate_update(1, g, stride)
-        e[1].record(); c.osp_apply_stage(1)
-        e[2].record(); c.osp_lgp_correct(g, stride)
-        e[3].record(); c.osp_ps_aggregate_update(2, g, stride)
-        e[4].record(); c.osp_apply_stage(2)
-        e[5].record(); c.osp_split(gran, wl.budget)
-        e[6].record()
+        if windows:                              # RS under "agg1", ICS + split under "agg2"
+            e[0].record(); c.osp_rs_window(g, stride)
+            e[1].record(); e[2].record(); e[3].record()
+            c.osp_ics_window(g, stride, gran, wl.budget)
+            e[4].record(); e[5].record(); e[6].record()
+        else:
+            e[0].record(); c.osp_ps_aggregate_update(1, g, stride)
+            e[1].record(); c.osp_apply_stage(1)
+            e[2].record(); c.osp_lgp_correct(g, stride)
+            e[3].record(); c.osp_ps_aggregate_update(2, g, stride)
+            e[4].record(); c.osp_apply_stage(2)
+            e[5].record(); c.osp_split(gran, wl.budget)
+            e[6].record()
         c.osp_read_n_stage2_async(n2b.data_ptr() + 8 * (i + 1))
     torch.cuda.synchronize()
     call_ms = {n: 0.0 for n in names}
@@ -184,6 +208,11 @@ def main() -> int:
         for j, n in enumerate(names):
             call_ms[n] += ev2[i][j].elapsed_time(ev2[i][j + 1])
             call_bytes[n] += b[n]
+    if windows:
+        names = ["rs_window", "ics_window"]
+        call_ms = {"rs_window": call_ms["agg1"], "ics_window": call_ms["agg2"]}
+        call_bytes = {"rs_window": call_bytes["agg1"] + call_bytes["apply1"] + call_bytes["lgp"],
+                      "ics_window": call_bytes["agg2"] + call_bytes["apply2"] + call_bytes["split"]}
     calls = {n: {"ms": round(call_ms[n] / K2, 5),
                  "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
              for n in names}
@@ -213,7 +242,9 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{wl.name}-shaped", "n_workers": N, "n_tensors": wl.n_tensors,
-                   "n_params": M, "granularity": args.granularity,
+                   "n_params": M, "granularity": args.granularity, "calls": args.calls,
+                   "windows_fused": ({"rs": bool(c.osp_windows_fused() & 1),
+                                      "ics": bool(c.osp_windows_fused() & 2)} if windows else None),
                    "stage2_fraction_nominal": wl.stage2_fraction,
                    "stage2_elems_achieved": int(n2[K - 1]), "lr": wl.lr, "momentum": wl.momentum,
                    "seed": args.seed, "chunk_elems": c.osp_chunk_elems()},

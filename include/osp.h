@@ -193,6 +193,32 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
  * global result (taken as an overwrite, P_{w,k} = P_k).  stage: 1, 2, or 0 = both. */
 osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream);
 
+/*
+ * The two synchronization windows of an iteration (Sec. 3.1, Fig. 4) as one
+ * call each.  Same arguments, same checks and, element for element, the same
+ * results as the calls they stand for:
+ *   osp_rs_window  = osp_ps_aggregate_update(1), osp_apply_stage(1), osp_lgp_correct
+ *                    (RS: the important gradients are synchronized inside the
+ *                    barrier and the workers advance their stale unimportant
+ *                    parameters by LGP, Eq. 6);
+ *   osp_ics_window = osp_ps_aggregate_update(2), osp_apply_stage(2), osp_split
+ *                    (ICS, overlapped by the caller with the next iteration's
+ *                    compute: Eq. 7, then the next GIB, Sec. 3.2).
+ * When the replicas equal the PS arena as the RS window begins (after
+ * osp_bind with replicas_in_sync, or after an iteration that installed both
+ * stages) the windows run fused kernels: one launch per window (plus the
+ * split's), no second read of data a lane already holds.  Otherwise, and
+ * where the single-stage kernels are as fast (layer-granular GIB: N > 8 or
+ * N x parameters > 2^27; element-granular GIB: RS window N > 16, ICS window
+ * N > 8), they enqueue the single-stage kernels.  The single calls and
+ * the windows may be mixed freely within the order of calls above.
+ * The rule on the gradient arenas between the two stages (see
+ * osp_ps_aggregate_update) applies.
+ */
+osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream);
+osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_stride,
+                          int granularity, int64_t budget_elems, void *stream);
+
 /* Inspection (each synchronizes `stream`): the fp64 layer importances I^l of
  * the last osp_split(LAYER) into imp_host[L]; the element keys (bit pattern of
  * I_k, NaN canonicalised to 0x7FC00000, padding 0xFFFFFFFF) into
@@ -235,6 +261,10 @@ const char *osp_last_error(const osp_ctx *ctx);
  * arena (replicas known to be in sync) instead of once per replica; 0 otherwise.
  * For callers that account for the bytes a step really moves. */
 int32_t osp_lgp_read_shared(const osp_ctx *ctx);
+
+/* Which of the last osp_rs_window (bit 0) and osp_ics_window (bit 1) ran as a
+ * fused kernel rather than as the single-stage kernels.  For reports. */
+int32_t osp_windows_fused(const osp_ctx *ctx);
 
 /* Geometry, for callers that size launches or report traffic. */
 int32_t osp_chunk_elems(const osp_ctx *ctx);

@@ -80,6 +80,10 @@ def _load() -> C.CDLL:
     lib.osp_lgp_correct.restype = C.c_int
     lib.osp_apply_stage.argtypes = [vp, C.c_int, vp]
     lib.osp_apply_stage.restype = C.c_int
+    lib.osp_rs_window.argtypes = [vp, vp, i64, vp]
+    lib.osp_rs_window.restype = C.c_int
+    lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
+    lib.osp_ics_window.restype = C.c_int
     lib.osp_get_importance.argtypes = [vp, vp, vp]
     lib.osp_get_importance.restype = C.c_int
     lib.osp_get_keys.argtypes = [vp, vp, vp]
@@ -94,6 +98,8 @@ def _load() -> C.CDLL:
     lib.osp_last_error.restype = C.c_char_p
     lib.osp_lgp_read_shared.argtypes = [vp]
     lib.osp_lgp_read_shared.restype = C.c_int32
+    lib.osp_windows_fused.argtypes = [vp]
+    lib.osp_windows_fused.restype = C.c_int32
     lib.osp_chunk_elems.argtypes = [vp]
     lib.osp_chunk_elems.restype = C.c_int32
     lib.osp_n_chunks.argtypes = [vp]
@@ -105,9 +111,10 @@ lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
-           "osp_lgp_correct", "osp_apply_stage", "osp_get_importance", "osp_get_keys",
+           "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window",
+           "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
-           "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared"]
+           "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
 
 
 def _ptr(t) -> int:
@@ -179,6 +186,9 @@ class Context:
     def osp_lgp_read_shared(self) -> bool:
         return bool(lib.osp_lgp_read_shared(self._h))
 
+    def osp_windows_fused(self) -> int:
+        return int(lib.osp_windows_fused(self._h))
+
     def osp_n_chunks(self) -> int:
         return int(lib.osp_n_chunks(self._h))
 
@@ -231,6 +241,14 @@ class Context:
     def osp_apply_stage(self, stage: int, stream=None) -> None:
         self._check(lib.osp_apply_stage(self._h, stage, _stream(stream)))
 
+    def osp_rs_window(self, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_rs_window(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
+
+    def osp_ics_window(self, grads, worker_stride: int, granularity: int, budget_elems: int,
+                       stream=None) -> None:
+        self._check(lib.osp_ics_window(self._h, _ptr(grads), int(worker_stride), int(granularity),
+                                       int(budget_elems), _stream(stream)))
+
     def osp_get_importance(self, stream=None) -> np.ndarray:
         imp = np.zeros(self.n_tensors, np.float64)
         self._check(lib.osp_get_importance(self._h, imp.ctypes.data, _stream(stream)))
@@ -271,3 +289,11 @@ def osp_lgp_correct(ctx: Context, grads, worker_stride, stream=None):
 
 def osp_apply_stage(ctx: Context, stage, stream=None):
     return ctx.osp_apply_stage(stage, stream)
+
+
+def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):
+    return ctx.osp_rs_window(grads, worker_stride, stream)
+
+
+def osp_ics_window(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
+    return ctx.osp_ics_window(grads, worker_stride, granularity, budget_elems, stream)

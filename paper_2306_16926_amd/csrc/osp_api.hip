@@ -5,6 +5,7 @@
 // exercised on a machine without one.
 #include "../../include/osp.h"
 #include "osp_split_kernels.hpp"
+#include "osp_window_kernels.hpp"
 
 #include <cstdarg>
 #include <cstdio>
@@ -73,6 +74,7 @@ struct osp_ctx {
     bool replicas_synced = false, iter_synced = false, last_lgp_shared = false;
     // element-granular stage 1 leaves the aggregate of the stage-2 elements in the stash;
     // valid for a stage-2 call on the same gradient arenas
+    int windows_fused = 0;              // bit 0: last RS window ran fused, bit 1: last ICS window
     bool stash_valid = false;
     const float *stash_grads = nullptr;
     long long stash_stride = 0;
@@ -375,6 +377,8 @@ size_t osp_workspace_bytes(const osp_ctx *ctx) { return ctx ? ctx->ws_bytes : 0;
 int32_t osp_chunk_elems(const osp_ctx *ctx) { return ctx ? ctx->chunk_elems : 0; }
 
 int32_t osp_lgp_read_shared(const osp_ctx *ctx) { return ctx && ctx->last_lgp_shared ? 1 : 0; }
+
+int32_t osp_windows_fused(const osp_ctx *ctx) { return ctx ? ctx->windows_fused : 0; }
 
 int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->n_chunks : 0; }
 
@@ -849,6 +853,228 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     if (ctx->applied1 && ctx->applied2)
         ctx->replicas_synced = true;    // every element of every replica equals the PS again
     return OSP_OK;
+}
+
+static void launch_window_layer(osp_ctx *ctx, const WindowLayerArgs &a, unsigned n_groups, hipStream_t s)
+{
+    if (n_groups == 0)
+        return;
+    const dim3 grid(n_groups), block(kBlock);
+    const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    switch (variant) {
+    case 0: k_window_layer<false, false><<<grid, block, 0, s>>>(a); break;
+    case 1: k_window_layer<false, true><<<grid, block, 0, s>>>(a); break;
+    case 2: k_window_layer<true, false><<<grid, block, 0, s>>>(a); break;
+    default: k_window_layer<true, true><<<grid, block, 0, s>>>(a); break;
+    }
+}
+
+// Largest N for which the element-granular RS window keeps all gradients of a group in registers.
+constexpr int kRsElementMaxWorkers = 16;
+// Layer-granular windows run fused up to this many gradient elements (N x parameters): measured
+// on MI355X the fused launch wins below about 1e8 (launch-bound steps) and loses 1-2 % above.
+constexpr long long kWindowLayerMaxGradElems = 128LL << 20;
+
+static bool layer_window_fused(const osp_ctx *ctx)
+{
+    return ctx->n_workers <= kWindowMaxWorkers &&
+           (long long)ctx->n_workers * ctx->n_params <= kWindowLayerMaxGradElems;
+}
+
+osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    osp_status st = check_grads(ctx, grads, worker_stride);
+    if (st != OSP_OK)
+        return st;
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB (osp_set_gib or osp_split)");
+    if (stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE,
+                    "stage 2 of the previous iteration is still pending (ICS must complete first)");
+    const bool element = ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const int N = ctx->n_workers;
+    // The fused kernels take LGP's stale values from the PS arena: every replica must equal it.
+    const bool fused = ctx->replicas_synced &&
+                       (element ? N <= kRsElementMaxWorkers : layer_window_fused(ctx));
+    ctx->windows_fused = fused ? 1 : 0;
+    if (!fused) {
+        st = osp_ps_aggregate_update(ctx, 1, grads, worker_stride, stream);
+        if (st == OSP_OK)
+            st = osp_apply_stage(ctx, 1, stream);
+        if (st == OSP_OK)
+            st = osp_lgp_correct(ctx, grads, worker_stride, stream);
+        return st;
+    }
+    hipStream_t s = (hipStream_t)stream;
+    if (element) {
+        RsElementArgs a;
+        a.spans = ctx->d_spans();
+        a.chunk_elems = ctx->chunk_elems;
+        a.bitmap = ctx->d_bitmap();
+        a.P = ctx->P;
+        a.V = ctx->V;
+        a.grads = grads;
+        a.worker_stride = worker_stride;
+        a.weights = ctx->d_weights();
+        a.partial1 = ctx->d_partial(0);
+        a.partial2 = ctx->d_partial(1);
+        a.key = ctx->d_key();
+        a.stash = ctx->d_stash();
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.n_workers = N;
+        a.inv_n = 1.0f / (float)N;
+        a.lr = ctx->lr;
+        a.mu = ctx->mu;
+        const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
+        const int cap = N <= 4 ? 4 : (N <= 8 ? 8 : 16);
+        if (ctx->weighted) {
+            if (cap == 4) k_rs_window_element<4, true><<<grid, block, 0, s>>>(a);
+            else if (cap == 8) k_rs_window_element<8, true><<<grid, block, 0, s>>>(a);
+            else k_rs_window_element<16, true><<<grid, block, 0, s>>>(a);
+        } else {
+            if (cap == 4) k_rs_window_element<4, false><<<grid, block, 0, s>>>(a);
+            else if (cap == 8) k_rs_window_element<8, false><<<grid, block, 0, s>>>(a);
+            else k_rs_window_element<16, false><<<grid, block, 0, s>>>(a);
+        }
+    } else {
+        // No wait for the table lengths of a split that may still be running: the launch covers
+        // both tables (all spans), and the kernel reads where the first one ends.
+        WindowLayerArgs a;
+        a.agg_spans = ctx->d_list(1);
+        a.n_agg_groups = 0;
+        a.n_agg_spans = &ctx->d_state()->stage_spans[0];
+        a.lgp_spans = ctx->d_list(2);
+        a.chunk_elems = ctx->chunk_elems;
+        a.P = ctx->P;
+        a.V = ctx->V;
+        a.grads = grads;
+        a.worker_stride = worker_stride;
+        a.weights = ctx->d_weights();
+        a.partial = ctx->d_partial(0);
+        a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.n_workers = N;
+        a.inv_n = 1.0f / (float)N;
+        a.lr = ctx->lr;
+        a.mu = ctx->mu;
+        const unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
+        launch_window_layer(ctx, a, n_groups, s);
+    }
+    st = launch_check(ctx, "osp_rs_window");
+    if (st != OSP_OK)
+        return st;
+    ctx->iter_synced = true;
+    ctx->replicas_synced = false;
+    ctx->stash_valid = element;
+    ctx->stash_grads = grads;
+    ctx->stash_stride = (long long)worker_stride;
+    ctx->agg1 = ctx->applied1 = ctx->lgp_done = ctx->last_lgp_shared = true;
+    ctx->agg2 = ctx->single_pass = ctx->applied2 = false;
+    return OSP_OK;
+}
+
+osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,
+                          int64_t budget_elems, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    osp_status st = check_grads(ctx, grads, worker_stride);
+    if (st != OSP_OK)
+        return st;
+    // the split's arguments are checked before anything is launched
+    if (granularity != OSP_GRAN_LAYER && granularity != OSP_GRAN_ELEMENT)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "unknown granularity %d", granularity);
+    if (budget_elems < 0 || budget_elems > ctx->n_params)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "budget %lld outside [0, %lld]",
+                    (long long)budget_elems, ctx->n_params);
+    if (granularity == OSP_GRAN_ELEMENT && !ctx->element_keys)
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "element granularity needs cfg.element_keys");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 needs this iteration's stage 1 first");
+    const bool element = ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const int N = ctx->n_workers;
+    // element-granular: whole groups of PS values go into the replicas, which is an install of
+    // stage 2 only if stage 1 is in place there
+    // (above 8 replicas the per-replica install sweep beats writing them all from one lane)
+    const bool fused = element ? (ctx->applied1 && N <= kWindowMaxWorkers) : layer_window_fused(ctx);
+    ctx->windows_fused = (ctx->windows_fused & 1) | (fused ? 2 : 0);
+    hipStream_t s = (hipStream_t)stream;
+    if (!fused) {
+        st = osp_ps_aggregate_update(ctx, 2, grads, worker_stride, stream);
+        if (st == OSP_OK)
+            st = osp_apply_stage(ctx, 2, stream);
+        if (st != OSP_OK)
+            return st;
+    } else {
+        if (element) {
+            const bool from_stash = ctx->stash_valid && ctx->stash_grads == grads &&
+                                    ctx->stash_stride == (long long)worker_stride;
+            IcsElementArgs a;
+            a.spans = ctx->d_spans();
+            a.chunk_elems = ctx->chunk_elems;
+            a.bitmap = ctx->d_bitmap();
+            a.P = ctx->P;
+            a.V = ctx->V;
+            a.stash = ctx->d_stash();
+            a.grads = grads;
+            a.worker_stride = worker_stride;
+            a.weights = ctx->d_weights();
+            a.partial2 = ctx->d_partial(1);
+            a.key = ctx->d_key();
+            a.Pw = ctx->Pw;
+            a.param_stride = ctx->param_stride;
+            a.n_workers = N;
+            a.inv_n = 1.0f / (float)N;
+            a.lr = ctx->lr;
+            a.mu = ctx->mu;
+            const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
+            if (from_stash)
+                k_ics_window_element<true, false><<<grid, block, 0, s>>>(a);
+            else if (ctx->weighted)
+                k_ics_window_element<false, true><<<grid, block, 0, s>>>(a);
+            else
+                k_ics_window_element<false, false><<<grid, block, 0, s>>>(a);
+        } else {
+            st = stage_counts(ctx);
+            if (st != OSP_OK)
+                return st;
+            WindowLayerArgs a;
+            a.agg_spans = ctx->d_list(2);
+            a.n_agg_groups = (unsigned)ctx->stage_spans[1] * kSpanChunks;
+            a.n_agg_spans = nullptr;
+            a.lgp_spans = nullptr;
+            a.chunk_elems = ctx->chunk_elems;
+            a.P = ctx->P;
+            a.V = ctx->V;
+            a.grads = grads;
+            a.worker_stride = worker_stride;
+            a.weights = ctx->d_weights();
+            a.partial = ctx->d_partial(1);
+            a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+            a.Pw = ctx->Pw;
+            a.param_stride = ctx->param_stride;
+            a.n_workers = N;
+            a.inv_n = 1.0f / (float)N;
+            a.lr = ctx->lr;
+            a.mu = ctx->mu;
+            launch_window_layer(ctx, a, a.n_agg_groups, s);
+        }
+        st = launch_check(ctx, "osp_ics_window");
+        if (st != OSP_OK)
+            return st;
+        ctx->agg2 = ctx->applied2 = true;
+        if (ctx->applied1)
+            ctx->replicas_synced = true;
+    }
+    return osp_split(ctx, granularity, budget_elems, stream);
 }
 
 osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream)

@@ -54,6 +54,12 @@ class DeviceJob:
         c.osp_apply_stage(2)
         c.osp_split(granularity, budget_elems)
 
+    # the same step as its two windows
+    def sync_step_windows(self, grads: torch.Tensor, granularity: int, budget_elems: int) -> None:
+        c, s = self.ctx, grads.shape[1]
+        c.osp_rs_window(grads, s)
+        c.osp_ics_window(grads, s, granularity, budget_elems)
+
     def download(self):
         torch.cuda.synchronize(self.dev)
         return self.P.cpu().numpy(), self.V.cpu().numpy(), self.Pw.cpu().numpy()

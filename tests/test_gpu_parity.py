@@ -67,7 +67,7 @@ def compare_gib(job, o, what):
 
 
 def run_steps(wl, gran, steps, seed=0, align=None, weights=None, chunk_elems=0, budget=None,
-              threads=4):
+              threads=4, windows=False):
     budget = wl.budget if budget is None else budget
     o = make_oracle(wl, seed, align, weights)
     job = device_job(wl, seed, align, weights, element_keys=(gran == GRAN_ELEMENT),
@@ -79,7 +79,10 @@ def run_steps(wl, gran, steps, seed=0, align=None, weights=None, chunk_elems=0, 
         g = wl.make_grads(seed, step, align, threads=threads)
         gd = job.upload_grads(g)
         o.sync_step(g, gran, budget)
-        job.sync_step(gd, gran, budget)
+        if windows:
+            job.sync_step_windows(gd, gran, budget)
+        else:
+            job.sync_step(gd, gran, budget)
         compare_state(job, o, f"{wl.name} step {step}")
         compare_gib(job, o, f"{wl.name} step {step}")
         if gran == GRAN_LAYER:
@@ -151,7 +154,7 @@ def test_cnn_shaped_two_steps(name, gran):
 # run under OpenMP here, which a CPU test shows to be bit-identical)
 # --------------------------------------------------------------------------
 
-def full_size_steps(name, steps):
+def full_size_steps(name, steps, windows=False):
     from paper_2306_16926_amd.device import DeviceJob
     wl = W.get(name)
     stride = wl.worker_stride()
@@ -170,7 +173,10 @@ def full_size_steps(name, steps):
         say(" ", name, "step", step, "oracle")
         o.sync_step(g, GRAN_LAYER, wl.budget)
         say(" ", name, "step", step, "gpu")
-        job.sync_step(gd, GRAN_LAYER, wl.budget)
+        if windows:
+            job.sync_step_windows(gd, GRAN_LAYER, wl.budget)
+        else:
+            job.sync_step(gd, GRAN_LAYER, wl.budget)
         compare_gib(job, o, f"{name} step {step}")
         imp = job.ctx.osp_get_importance()
         rel = np.abs(imp - o.importance) / np.maximum(np.abs(o.importance), 1e-300)
@@ -194,6 +200,12 @@ def full_size_steps(name, steps):
 def test_full_size_resnet152_layer():
     say("full size resnet152")
     sizes = full_size_steps("resnet152", 3)
+    assert sizes[-1] > 0
+
+
+def test_full_size_resnet152_layer_windows():
+    say("full size resnet152, windows")
+    sizes = full_size_steps("resnet152", 3, windows=True)
     assert sizes[-1] > 0
 
 
@@ -256,6 +268,123 @@ def test_full_size_resnet152_element_properties():
     close_enough(P, o.P, "P"); close_enough(V, o.V, "V")
     for w in range(wl.n_workers):
         close_enough(Pw[w, :arena], o.Pw[w, :arena], f"Pw[{w}]")
+    # and once more through the two windows (fused kernels at full size); the element split that
+    # closes the window is checked through the keys it ranks
+    say("  windows")
+    g = wl.make_grads(0, 2, stride=stride, threads=16, out=g)
+    gd = job.upload_grads(g)
+    o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+    o.ps_aggregate_update(2, g); o.apply_stage(2)
+    c.osp_rs_window(gd, stride); c.osp_ics_window(gd, stride, GRAN_ELEMENT, k)
+    P, V, Pw = job.download()
+    close_enough(P, o.P, "P"); close_enough(V, o.V, "V")
+    for w in range(wl.n_workers):
+        close_enough(Pw[w, :arena], o.Pw[w, :arena], f"Pw[{w}]")
+    assert np.array_equal(c.osp_get_keys()[real], o.keys()[real])
+    _, bits, n2 = c.osp_get_gib()
+    assert n2 == k
+
+
+# --------------------------------------------------------------------------
+# the two windows (one call each) against the oracle's six calls
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_windows_tiny_three_chained_steps(gran, weighted):
+    say("windows tiny", gran, weighted)
+    wl = W.get("tiny")
+    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
+    sizes = run_steps(wl, gran, 3, weights=wts, windows=True)
+    assert sizes[0] > 0
+    run_steps(wl, gran, 2, align=64, chunk_elems=1024, windows=True)
+
+
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 8, 9, 16, 17])
+def test_windows_worker_counts(n_workers):
+    """Fused kernels up to 8 (layer) / 16 (element, RS) workers, single-stage kernels above."""
+    say("windows workers", n_workers)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 1], n_workers, 0.4, align=4, config_id=140 + n_workers)
+    run_steps(wl, GRAN_LAYER, 3, windows=True)
+    run_steps(wl, GRAN_ELEMENT, 3, windows=True)
+    wts = np.random.default_rng(n_workers).random(n_workers).astype(F)
+    wts /= wts.sum()
+    run_steps(wl, GRAN_ELEMENT, 2, weights=wts, windows=True)
+    run_steps(wl, GRAN_LAYER, 2, weights=wts, windows=True)
+
+
+@pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT)])
+def test_windows_cnn_shaped(name, gran):
+    say("windows", name, gran)
+    sizes = run_steps(W.get(name), gran, 3, threads=8, windows=True)
+    assert sizes[-1] > 0
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("in_sync", [True, False])
+def test_windows_mixed_with_single_calls(gran, in_sync):
+    """Windows and single calls in one run, starting from replicas that are or are not declared
+    equal to the PS, over iterations that do and do not restore consistency; stage 2 from
+    another gradient buffer on some steps."""
+    say("windows mixed", gran, in_sync)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 70000, 2], 6, 0.5, align=4, config_id=170)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True, declare_in_sync=in_sync)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    plans = ["ww", "ws", "sw", "ww", "w-", "ww", "s-", "ww", "wW", "ww"]
+    for step, plan in enumerate(plans):
+        g = wl.make_grads(0, step); gd = job.upload_grads(g); s_ = g.shape[1]
+        g2, gd2 = g, gd
+        if plan[1] == "W":                      # ICS window from a different gradient buffer
+            g2 = wl.make_grads(3, step); gd2 = job.upload_grads(g2)
+        o.ps_aggregate_update(1, g)
+        if plan[0] == "w":
+            o.apply_stage(1); o.lgp_correct(g)
+            c.osp_rs_window(gd, s_)
+        else:                                   # single calls, stage 1 never installed
+            o.lgp_correct(g)
+            c.osp_ps_aggregate_update(1, gd, s_); c.osp_lgp_correct(gd, s_)
+        compare_state(job, o, f"step {step} {plan} RS")
+        o.ps_aggregate_update(2, g2)
+        if plan[1] in "wW":
+            o.apply_stage(2); o.split(gran, wl.budget)
+            c.osp_ics_window(gd2, s_, gran, wl.budget)
+        elif plan[1] == "s":
+            o.apply_stage(2); o.split(gran, wl.budget)
+            c.osp_ps_aggregate_update(2, gd2, s_); c.osp_apply_stage(2); c.osp_split(gran, wl.budget)
+        else:                                   # stage 2 aggregated but not installed, old GIB stays
+            c.osp_ps_aggregate_update(2, gd2, s_)
+        compare_state(job, o, f"step {step} {plan} ICS")
+        compare_gib(job, o, f"step {step} {plan}")
+
+
+def test_windows_reject_bad_arguments_before_launching():
+    say("windows errors")
+    from paper_2306_16926_amd.binding import OspError
+    wl = W.get("tiny")
+    o = make_oracle(wl)
+    job = device_job(wl)                        # no element keys
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s_ = g.shape[1]
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)        # no stage 1 yet
+    c.osp_rs_window(gd, s_)
+    o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+    with pytest.raises(OspError):
+        c.osp_rs_window(gd, s_)                                # stage 2 pending
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_ELEMENT, wl.budget)      # needs element keys
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.n_params + 1)
+    compare_state(job, o, "after rejected calls")              # nothing was touched
+    c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)
+    o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(GRAN_LAYER, wl.budget)
+    compare_state(job, o, "after ICS")
+    compare_gib(job, o, "after ICS")
 
 
 # --------------------------------------------------------------------------
