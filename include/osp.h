@@ -155,6 +155,12 @@ osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap,
  * without stalling the stream. */
 osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream);
 
+/* The current stage-2 element count, on the host, without a stream operation:
+ * the split publishes it in pinned host memory.  Waits (bounded) only if a
+ * layer-granular osp_split is still running; any staged call made after that
+ * split has already waited, so calling this behind one costs nothing. */
+osp_status osp_n_stage2(osp_ctx *ctx, int64_t *n_stage2);
+
 /* Install a GIB from the host (first iteration, tests, resume).  gib_host is
  * uint8[L] for LAYER or uint32[ceil(arena_elems/32)] for ELEMENT, same encoding
  * as osp_get_gib; padding bits are ignored.  Synchronizes `stream`. */

@@ -72,6 +72,8 @@ def _load() -> C.CDLL:
     lib.osp_get_gib.restype = C.c_int
     lib.osp_read_n_stage2_async.argtypes = [vp, vp, vp]
     lib.osp_read_n_stage2_async.restype = C.c_int
+    lib.osp_n_stage2.argtypes = [vp, C.POINTER(i64)]
+    lib.osp_n_stage2.restype = C.c_int
     lib.osp_set_gib.argtypes = [vp, C.c_int, vp, vp]
     lib.osp_set_gib.restype = C.c_int
     lib.osp_ps_aggregate_update.argtypes = [vp, C.c_int, vp, i64, vp]
@@ -110,7 +112,7 @@ def _load() -> C.CDLL:
 lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
-           "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_gib", "osp_ps_aggregate_update",
+           "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window",
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
@@ -182,6 +184,11 @@ class Context:
 
     def osp_chunk_elems(self) -> int:
         return int(lib.osp_chunk_elems(self._h))
+
+    def osp_n_stage2(self) -> int:
+        out = C.c_int64(0)
+        self._check(lib.osp_n_stage2(self._h, C.byref(out)))
+        return int(out.value)
 
     def osp_lgp_read_shared(self) -> bool:
         return bool(lib.osp_lgp_read_shared(self._h))

@@ -83,13 +83,14 @@ struct osp_ctx {
     // The split runs on the device; the ranking kernel publishes the two table
     // lengths and a sequence number in pinned host memory.  counts_pending: a split
     // with sequence number split_seq has been enqueued and its lengths have not been
-    // read yet.  counts_ready is an event recorded behind the split (fallback wait).
+    // read yet.  counts_stream is the stream that split was enqueued on (fallback wait).
     int stage_spans[2] = {0, 0};
     bool counts_pending = false;
     unsigned split_seq = 0;
     StageCounts *pinned_counts = nullptr;      // hipHostMalloc (mapped)
     StageCounts *pinned_counts_dev = nullptr;  // the same memory as the device sees it
-    hipEvent_t counts_ready = nullptr;
+    hipStream_t counts_stream = nullptr;
+    long long n_stage2_host = 0;        // stage-2 elements under the current GIB (see counts_pending)
 
     std::string err;
 
@@ -210,8 +211,8 @@ osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
     k_stage_lists<<<(ns + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
         ns, ctx->d_spans(), ctx->d_slayer(), ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
         ctx->d_list(1), ctx->d_list(2));
-    // the table lengths were written straight into pinned host memory by the kernel before
-    OSP_HIP(hipEventRecord(ctx->counts_ready, s));
+    // (the table lengths were written straight into pinned host memory by the kernel before)
+    ctx->counts_stream = s;
     ctx->counts_pending = true;
     return OSP_OK;
 }
@@ -231,7 +232,7 @@ osp_status stage_counts(osp_ctx *ctx)
         while (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq) {
             if ((++spins & 1023u) == 0 &&
                 std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
-                OSP_HIP(hipEventSynchronize(ctx->counts_ready));
+                OSP_HIP(hipStreamSynchronize(ctx->counts_stream));
                 if (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq)
                     return fail(ctx, OSP_ERR_HIP, "the split did not publish its stage-table lengths");
                 break;
@@ -240,6 +241,7 @@ osp_status stage_counts(osp_ctx *ctx)
         }
         ctx->stage_spans[0] = ctx->pinned_counts->n[0];
         ctx->stage_spans[1] = ctx->pinned_counts->n[1];
+        ctx->n_stage2_host = ctx->pinned_counts->n_stage2;
         ctx->counts_pending = false;
         const long long ns = (long long)ctx->spans.size();
         if (ctx->stage_spans[0] < 0 || ctx->stage_spans[1] < 0 ||
@@ -367,8 +369,6 @@ void osp_destroy(osp_ctx *ctx)
         return;
     if (ctx->pinned_counts)
         (void)hipHostFree(ctx->pinned_counts);
-    if (ctx->counts_ready)
-        (void)hipEventDestroy(ctx->counts_ready);
     delete ctx;
 }
 
@@ -429,8 +429,6 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         ctx->pinned_counts->seq = 0;
         ctx->split_seq = 0;
     }
-    if (!ctx->counts_ready)
-        OSP_HIP(hipEventCreateWithFlags(&ctx->counts_ready, hipEventDisableTiming));
     ctx->counts_pending = false;
     ctx->ws = (char *)buf->workspace;
     OSP_HIP(hipMemcpyAsync(ctx->d_spans(), ctx->spans.data(), ctx->spans.size() * sizeof(Span),
@@ -527,6 +525,8 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
                                hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
         OSP_HIP(hipStreamSynchronize(s));
+        ctx->counts_pending = false;
+        ctx->n_stage2_host = n2;
     }
     ctx->have_gib = true;
     ctx->gib_gran = granularity;
@@ -565,6 +565,21 @@ osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream
         return fail(ctx, OSP_ERR_BAD_STATE, "no GIB yet (osp_set_gib or osp_split first)");
     OSP_HIP(hipMemcpyAsync(out_host, &ctx->d_state()->n_stage2, sizeof(int64_t),
                            hipMemcpyDeviceToHost, (hipStream_t)stream));
+    return OSP_OK;
+}
+
+osp_status osp_n_stage2(osp_ctx *ctx, int64_t *n_stage2)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (!n_stage2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "n_stage2 is NULL");
+    if (!ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "there is no GIB");
+    osp_status st = stage_counts(ctx);
+    if (st != OSP_OK)
+        return st;
+    *n_stage2 = ctx->n_stage2_host;
     return OSP_OK;
 }
 
@@ -1125,6 +1140,8 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
                                                       ctx->d_tile_ties(), ctx->d_tile_before(),
                                                       ctx->d_bitmap());
+        ctx->counts_pending = false;    // stage tables belong to layer-granular GIBs only
+        ctx->n_stage2_host = budget_elems;
     }
     osp_status st = launch_check(ctx, "split kernels");
     if (st != OSP_OK)

@@ -20,18 +20,21 @@ constexpr int kSplitBlock = 256;       // 4 wavefronts
 constexpr int kSplitStride = kSplitBlock * kVec;
 
 // Written by the device into pinned host memory: the lengths of the two stage
-// tables, then a sequence number (released at system scope) that tells the
-// host which split they belong to.
+// tables and the number of stage-2 elements, then a sequence number (released
+// at system scope) that tells the host which split they belong to.
 struct StageCounts {
     int n[2];
+    long long n_stage2;
     unsigned int seq;
     unsigned int pad;
 };
 
-__device__ __forceinline__ void publish_counts(StageCounts *out, int n1, int n2, unsigned seq)
+__device__ __forceinline__ void publish_counts(StageCounts *out, int n1, int n2,
+                                               long long n_stage2, unsigned seq)
 {
     out->n[0] = n1;
     out->n[1] = n2;
+    out->n_stage2 = n_stage2;
     __hip_atomic_store(&out->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
@@ -256,7 +259,7 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     if (threadIdx.x == 0) {
         st->stage_spans[0] = carry1;
         st->stage_spans[1] = carry2;
-        publish_counts(counts_out, carry1, carry2, seq);   // the host shapes the next launches
+        publish_counts(counts_out, carry1, carry2, st->n_stage2, seq);   // the host shapes the next launches
     }
 }
 
@@ -281,7 +284,7 @@ __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
     }
     st->stage_spans[0] = n1;
     st->stage_spans[1] = n2;
-    publish_counts(counts_out, n1, n2, seq);
+    publish_counts(counts_out, n1, n2, st->n_stage2, seq);
 }
 
 // Fill the two stage tables: span k of layer l goes to position

@@ -638,6 +638,34 @@ def test_split_layer_ties_nan_and_zero_layers():
     del o, job
 
 
+@pytest.mark.parametrize("n_layers", [1025, 2500, 4200])
+def test_split_layer_many_layers(n_layers):
+    """More layers than the ranking workgroup has threads (1024) and than one of its
+    LDS tiles holds (2048); sizes repeat, so importances tie and the index decides."""
+    say("many layers", n_layers)
+    rng = np.random.default_rng(n_layers)
+    numel = rng.integers(1, 40, n_layers).tolist()
+    numel[7] = 3000
+    wl = W.custom(numel, 2, 0.45, align=4, config_id=34)
+    run_steps(wl, GRAN_LAYER, 3)
+    run_steps(wl, GRAN_LAYER, 2, windows=True)
+    # identical layers: every importance ties within its group
+    wl = W.custom([16] * n_layers, 1, 0.5, align=4, config_id=35)
+    arena = wl.arena_elems()
+    P = np.ones(arena, F)
+    g = np.zeros((1, arena), F)
+    g[0, :] = 1e-3
+    g[0, ::3 * 16] = 2e-3
+    o = OracleOSP(wl.numel, wl.offsets(), arena, 1, 0.1, 0.0); o.load_params(P)
+    job = device_job(wl, mu=0.0, params=P)
+    gd = job.upload_grads(g)
+    o.ps_aggregate_update(0, g); job.ctx.osp_ps_aggregate_update(0, gd, arena)
+    for budget in (16 * 7, 16 * 1024, 16 * 1024 + 15, wl.budget):
+        o.split(GRAN_LAYER, budget); job.ctx.osp_split(GRAN_LAYER, budget)
+        compare_gib(job, o, f"ties, budget {budget}")
+        o.ps_aggregate_update(0, g); job.ctx.osp_ps_aggregate_update(0, gd, arena)
+
+
 def test_nonfinite_gradients_flow_through_every_call():
     say("nonfinite")
     wl = W.custom([3000, 7, 2049], 3, 0.5, align=4, config_id=33)
