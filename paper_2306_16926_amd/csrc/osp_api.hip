@@ -49,11 +49,12 @@ struct osp_ctx {
     long long n_chunks = 0;
     std::vector<Segment> segments;             // fixed-order reduction tree, level 1
     std::vector<int> layer_seg_begin;          // [L+1]
+    std::vector<int> big_layers;               // layers with more than kFewSegments segments
     long long n_vec = 0, n_words = 0, n_tiles = 0;
 
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0,
+           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_big = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -106,6 +107,7 @@ struct osp_ctx {
     long long *d_rscratch() const { return at<long long>(off_rscratch); }
     Segment *d_segs() const { return at<Segment>(off_segs); }
     int *d_lsb() const { return at<int>(off_lsb); }
+    int *d_big() const { return at<int>(off_big); }
     double *d_segsum() const { return at<double>(off_segsum); }
     Span *d_list(int stage) const { return at<Span>(off_lists) + (size_t)(stage - 1) * spans.size(); }
     uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
@@ -167,6 +169,7 @@ void layout_workspace(osp_ctx *c)
     c->off_numel = take((size_t)c->n_tensors * sizeof(long long));
     c->off_segs = take(c->segments.size() * sizeof(Segment));
     c->off_lsb = take((size_t)(c->n_tensors + 1) * sizeof(int));
+    c->off_big = take((size_t)(c->big_layers.size() + 1) * sizeof(int));
     c->off_lists = take(2 * ns * sizeof(Span));
     c->off_partial = take(2 * nc * sizeof(double));
     c->off_segsum = take(c->segments.size() * sizeof(double));
@@ -351,6 +354,9 @@ osp_status osp_create(const osp_config *cfg, osp_ctx **out)
             }
         }
         c->layer_seg_begin.push_back((int)c->segments.size());
+        for (int l = 0; l < c->n_tensors; ++l)
+            if (c->layer_seg_begin[l + 1] - c->layer_seg_begin[l] > kFewSegments)
+                c->big_layers.push_back(l);
     } catch (const std::bad_alloc &) {
         delete c;
         return fail(ctx, OSP_ERR_NOMEM, "out of host memory");
@@ -441,6 +447,9 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
                            hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_lsb(), ctx->layer_seg_begin.data(),
                            ctx->layer_seg_begin.size() * sizeof(int), hipMemcpyHostToDevice, s));
+    if (!ctx->big_layers.empty())
+        OSP_HIP(hipMemcpyAsync(ctx->d_big(), ctx->big_layers.data(), ctx->big_layers.size() * sizeof(int),
+                               hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_numel(), ctx->numel.data(), ctx->numel.size() * sizeof(long long),
                            hipMemcpyHostToDevice, s));
     OSP_HIP(hipMemcpyAsync(ctx->d_weights(), ctx->weights.data(), ctx->weights.size() * sizeof(float),
@@ -1114,6 +1123,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
             ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
         k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
+                                              ctx->d_big(), (int)ctx->big_layers.size(),
                                               ctx->d_imp(), ctx->d_numel(),
                                               ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                                               ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
@@ -1136,7 +1146,8 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         k_select_pick<<<1, kSplitBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state());
         const unsigned tiles = (unsigned)ctx->n_tiles;
         k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
-        k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_tile_before());
+        k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_state(),
+                                                     ctx->d_tile_before());
         k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
                                                       ctx->d_tile_ties(), ctx->d_tile_before(),
                                                       ctx->d_bitmap());

@@ -46,7 +46,7 @@ struct SplitState {                    // one per context, in the workspace
     unsigned int prefix;               // key bits decided so far (right-aligned)
     unsigned int threshold;            // T
     unsigned int done;                 // 1: budget 0, nothing is selected
-    unsigned int pad;
+    unsigned int all_ties;             // 1: every key equal to T is taken (no per-tile counts needed)
 };
 
 // ---------------------------------------------------------------------------
@@ -149,6 +149,7 @@ __device__ __forceinline__ T block_scan_exclusive(T x, T *total)
 }
 
 constexpr int kRankTile = 2048;        // importance keys staged in LDS per pass of the ranking
+constexpr int kFewSegments = 16;       // up to here one thread sums a layer's segments
 
 // One workgroup: finish the layer importances (Eq. 4), rank the layers by
 // (importance, index), cut the ranking where the running size first exceeds
@@ -156,19 +157,18 @@ constexpr int kRankTile = 2048;        // importance keys staged in LDS per pass
 // scratch: [L] long long.
 __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
-    double *__restrict__ imp, const long long *__restrict__ numel,
+    const int *__restrict__ big_layers, int n_big, double *__restrict__ imp, const long long *__restrict__ numel,
     const int *__restrict__ layer_span_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
     long long *__restrict__ scratch, SplitState *__restrict__ st,
     StageCounts *__restrict__ counts_out, unsigned seq)
 {
-    __shared__ unsigned long long tile[kRankTile];
+    __shared__ __align__(16) unsigned long long tile[kRankTile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
 
     // I^l = sum of the layer's segment sums (fixed order per layer).  Layers with
     // few segments: one thread each, ascending.  Layers with many: one wavefront
     // each, lanes take segments lane, lane+64, ... in order, then a fixed butterfly.
-    constexpr int kFewSegments = 16;
     for (int l = threadIdx.x; l < L; l += kRankBlock) {
         const int g0 = layer_seg_begin[l], g1 = layer_seg_begin[l + 1];
         if (g1 - g0 <= kFewSegments) {
@@ -178,10 +178,9 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
             imp[l] = s;
         }
     }
-    for (int l = wave; l < L; l += kRankBlock / 64) {
+    for (int i = wave; i < n_big; i += kRankBlock / 64) {
+        const int l = big_layers[i];   // the layers with more than kFewSegments segments
         const int g0 = layer_seg_begin[l], g1 = layer_seg_begin[l + 1];
-        if (g1 - g0 <= kFewSegments)
-            continue;
         double s = 0.0;
         for (int g = g0 + lane; g < g1; g += 64)
             s += seg_sum[g];
@@ -191,28 +190,75 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     }
     __syncthreads();
 
-    // rank[l] = number of layers that come before l in the order (importance, index);
-    // a thread owns layers t, t+1024, ...; all keys pass through LDS in tiles
     const int per = (L + kRankBlock - 1) / kRankBlock;
-    for (int rep = 0; rep < per; ++rep) {
-        const int l = rep * kRankBlock + (int)threadIdx.x;
-        const unsigned long long mine = l < L ? importance_rank_key(imp[l]) : 0ull;
-        int rank = 0;
-        for (int t0 = 0; t0 < L; t0 += kRankTile) {
-            const int tn = L - t0 < kRankTile ? L - t0 : kRankTile;
-            __syncthreads();
-            for (int j = threadIdx.x; j < tn; j += kRankBlock)
-                tile[j] = importance_rank_key(imp[t0 + j]);
-            __syncthreads();
-            if (l < L)
-                for (int j = 0; j < tn; ++j) {
-                    const unsigned long long other = tile[j];
-                    rank += (other < mine) || (other == mine && t0 + j < l);
-                }
+    if (L <= kRankTile) {
+        // The usual case: all keys fit in LDS.  Bitonic sort of (key, layer index) pairs,
+        // padded to a power of two with entries that sort last.
+        __shared__ int sorted_layer[kRankTile];
+        int n = 1;
+        while (n < L)
+            n <<= 1;
+        for (int j = threadIdx.x; j < n; j += kRankBlock) {
+            tile[j] = j < L ? importance_rank_key(imp[j]) : ~0ull;
+            sorted_layer[j] = j;
         }
-        if (l < L) {
-            order[rank] = l;
-            scratch[rank] = numel[l];
+        __syncthreads();
+        for (int k = 2; k <= n; k <<= 1)
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                for (int t = threadIdx.x; t < (n >> 1); t += kRankBlock) {
+                    const int i = ((t & ~(j - 1)) << 1) | (t & (j - 1));   // bit j of i is clear
+                    const int p = i | j;
+                    const bool ascending = (i & k) == 0;
+                    const unsigned long long a = tile[i], b = tile[p];
+                    const int la = sorted_layer[i], lb = sorted_layer[p];
+                    const bool a_after_b = a > b || (a == b && la > lb);
+                    if (a_after_b == ascending) {
+                        tile[i] = b; tile[p] = a;
+                        sorted_layer[i] = lb; sorted_layer[p] = la;
+                    }
+                }
+                __syncthreads();
+            }
+        for (int r = threadIdx.x; r < L; r += kRankBlock) {
+            const int l = sorted_layer[r];
+            order[r] = l;
+            scratch[r] = numel[l];
+        }
+    } else {
+        // rank[l] = number of layers that come before l in the order (importance, index);
+        // a thread owns layers t, t+1024, ...; all keys pass through LDS in tiles
+        for (int rep = 0; rep < per; ++rep) {
+            const int l = rep * kRankBlock + (int)threadIdx.x;
+            const unsigned long long mine = l < L ? importance_rank_key(imp[l]) : 0ull;
+            int rank = 0;
+            for (int t0 = 0; t0 < L; t0 += kRankTile) {
+                const int tn = L - t0 < kRankTile ? L - t0 : kRankTile;
+                __syncthreads();
+                for (int j = threadIdx.x; j < tn; j += kRankBlock)
+                    tile[j] = importance_rank_key(imp[t0 + j]);
+                __syncthreads();
+                if (l < L) {
+                    // every thread reads the same keys (LDS broadcast); four per iteration as two
+                    // 16-byte reads, so the loop is not bound by the latency of one read per key
+                    int j = 0;
+                    for (; j + 4 <= tn; j += 4) {
+                        const ulonglong2 a = *reinterpret_cast<const ulonglong2 *>(&tile[j]);
+                        const ulonglong2 b = *reinterpret_cast<const ulonglong2 *>(&tile[j + 2]);
+                        rank += (a.x < mine) || (a.x == mine && t0 + j < l);
+                        rank += (a.y < mine) || (a.y == mine && t0 + j + 1 < l);
+                        rank += (b.x < mine) || (b.x == mine && t0 + j + 2 < l);
+                        rank += (b.y < mine) || (b.y == mine && t0 + j + 3 < l);
+                    }
+                    for (; j < tn; ++j) {
+                        const unsigned long long other = tile[j];
+                        rank += (other < mine) || (other == mine && t0 + j < l);
+                    }
+                }
+            }
+            if (l < L) {
+                order[rank] = l;
+                scratch[rank] = numel[l];
+            }
         }
     }
     if (threadIdx.x == 0)
@@ -381,7 +427,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
                                                         SplitState *__restrict__ st)
 {
     __shared__ int found_bin;
-    __shared__ unsigned long long found_below;
+    __shared__ unsigned long long found_below, found_count;
     if (pass == 0 && threadIdx.x == 0) {
         st->done = budget == 0 ? 1u : 0u;
         st->n_stage2 = budget;
@@ -394,6 +440,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             st->ties_to_take = 0;
             st->prefix = 0;
             st->k_rem = 0;
+            st->all_ties = 0;
         }
         return;
     }
@@ -416,6 +463,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             if (below < k && k <= below + c[j]) {
                 found_bin = threadIdx.x * per + j;
                 found_below = below;
+                found_count = c[j];
             }
             below += c[j];
         }
@@ -426,6 +474,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             st->done = 1;
             st->threshold = 0;
             st->ties_to_take = 0;
+            st->all_ties = 0;
         } else {
             const unsigned prefix = pass == 0 ? 0u : st->prefix;
             const unsigned np = (prefix << radix_bits(pass)) | (unsigned)found_bin;
@@ -434,6 +483,9 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             if (pass == 2) {
                 st->threshold = np;
                 st->ties_to_take = k - found_below;
+                // the usual case (distinct keys around the threshold): all keys equal to T
+                // are taken, and the order among them does not matter
+                st->all_ties = (k - found_below == found_count) ? 1u : 0u;
             }
         }
     }
@@ -454,6 +506,8 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
     unsigned int *__restrict__ tile_ties)
 {
+    if (st->all_ties || st->done)      // uniform: the bitmap pass will not read the counts
+        return;
     const unsigned T = st->threshold;
     const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
     unsigned long long n = 0;
@@ -470,8 +524,10 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
 // One workgroup: exclusive scan of the per-tile tie counts, in tile order.
 __global__ __launch_bounds__(kSplitBlock) void k_select_scan_tiles(
     const unsigned int *__restrict__ tile_ties, long long n_tiles,
-    unsigned long long *__restrict__ tile_before)
+    const SplitState *__restrict__ st, unsigned long long *__restrict__ tile_before)
 {
+    if (st->all_ties || st->done)
+        return;
     const long long per = (n_tiles + kSplitBlock - 1) / kSplitBlock;
     const long long b = (long long)threadIdx.x * per;
     const long long e = b + per < n_tiles ? b + per : n_tiles;
@@ -495,11 +551,14 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
     const unsigned T = st->threshold;
     const unsigned long long r = st->ties_to_take;
     const bool none = st->done != 0;
-    const unsigned long long before = tile_before[blockIdx.x];
-    const unsigned long long ties = tile_ties[blockIdx.x];
+    const bool all = st->all_ties != 0;
+    const unsigned long long before = (none || all) ? 0 : tile_before[blockIdx.x];
+    const unsigned long long ties = (none || all) ? 0 : tile_ties[blockIdx.x];
     // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
     int tie_mode;
-    if (none || ties == 0 || before >= r)
+    if (all)
+        tie_mode = 1;
+    else if (none || ties == 0 || before >= r)
         tie_mode = 0;
     else if (before + ties <= r)
         tie_mode = 1;
