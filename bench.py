@@ -41,6 +41,10 @@ BRACKET_EVERY = 4               # steps between two event-bracketed steps of the
 # ((7226989 + 815437) + (2503511 + 282450)) / 2 KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
 # 1.0 (what each reads for the 2 GiB k_stream_copy).  Algorithmic: 5534301760.
 AGG_TRAFFIC_VGG16_LAYER = 5544134144
+# HBM bytes per launch of k_rs_window_element on VGG-16-shaped, element granularity, --calls windows,
+# from profiles/window_kernels_vgg16_element.txt: (9814899 + 10846517) KiB.  The launch does the work the
+# metric counts as stage-1 aggregate + install + LGP (30.4 GB) in one pass over 21.2 GB.
+RS_TRAFFIC_VGG16_ELEMENT = 21157289984
 
 
 def step_bytes(N, M, E2, element):
@@ -187,8 +191,9 @@ def main() -> int:
     agg_gbps = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
-                "traffic": (AGG_TRAFFIC_VGG16_LAYER if (wl.name == "vgg16" and not element and not windows
-                                                        and c.osp_chunk_elems() == 256) else None),
+                "traffic": (None if wl.name != "vgg16" or c.osp_chunk_elems() != 256 else
+                            AGG_TRAFFIC_VGG16_LAYER if not element and not windows else
+                            RS_TRAFFIC_VGG16_ELEMENT if element and fused_rs else None),
                 "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
 
