@@ -20,6 +20,8 @@
  *                           worker's own local gradient.
  *   correction Sec. 4.2, Eq. 7: the local estimate is replaced by the global
  *                           result once stage 2 has been synchronized.
+ *   splitter   Sec. 4.5   : a worker's gradient cut by the GIB into the dense
+ *                           arrays G^i and G^u, and the PS update fed by them.
  *
  * Readings taken where the paper is silent (each also listed in the design
  * document): sequential fp32 summation over workers in ascending index;
@@ -78,6 +80,45 @@ static int selected(const osp_oracle_gib *gib, int stage, int32_t l, int64_t k)
     return stage == 0 || stage_of(gib, l, k) == stage;
 }
 
+/* The aggregate of one element (Sec. 2.1.1): the workers' gradients weighted
+ * by their data shares and merged, sequentially in ascending worker order;
+ * with equal shares the plain sum times fl(1/N).  g points at worker 0's value,
+ * worker w's is stride elements further on. */
+static float aggregate_element(const osp_oracle_model *m, const float *g, int64_t stride)
+{
+    const int N = m->n_workers;
+    const float inv_n = 1.0f / (float)N;
+    float gbar;
+    if (m->worker_weight) {
+        float acc = m->worker_weight[0] * g[0];
+        for (int w = 1; w < N; ++w) {
+            float term = m->worker_weight[w] * g[(int64_t)w * stride];
+            acc = acc + term;
+        }
+        gbar = acc;
+    } else {
+        float acc = g[0];
+        for (int w = 1; w < N; ++w)
+            acc = acc + g[(int64_t)w * stride];
+        gbar = acc * inv_n;
+    }
+    return gbar;
+}
+
+/* PGP product with the parameter before the update (text after Eq. 3), then
+ * SGD with momentum on the PS. */
+static void update_element(const osp_oracle_model *m, float gbar, float *P, float *V, float *q,
+                           int64_t k)
+{
+    float prod = gbar * P[k];
+    q[k] = fabsf(prod);
+    float mv = m->momentum * V[k];
+    float v = mv + gbar;
+    float step = m->lr * v;
+    V[k] = v;
+    P[k] = P[k] - step;
+}
+
 /*
  * PS side of one stage (Sec. 2.1.1; per stage as in Sec. 3.1).
  * For every element k of the stage:
@@ -90,8 +131,6 @@ void osp_oracle_aggregate_update(const osp_oracle_model *m, const osp_oracle_gib
                                  int stage, float *P, float *V, const float *grads,
                                  int64_t worker_stride, float *q)
 {
-    const int N = m->n_workers;
-    const float inv_n = 1.0f / (float)N;
     for (int32_t l = 0; l < m->n_tensors; ++l) {
 #ifdef _OPENMP
 #pragma omp parallel for schedule(static)
@@ -100,27 +139,7 @@ void osp_oracle_aggregate_update(const osp_oracle_model *m, const osp_oracle_gib
             const int64_t k = m->offset[l] + j;
             if (!selected(gib, stage, l, k))
                 continue;
-            float gbar;
-            if (m->worker_weight) {
-                float acc = m->worker_weight[0] * grads[k];
-                for (int w = 1; w < N; ++w) {
-                    float term = m->worker_weight[w] * grads[(int64_t)w * worker_stride + k];
-                    acc = acc + term;
-                }
-                gbar = acc;
-            } else {
-                float acc = grads[k];
-                for (int w = 1; w < N; ++w)
-                    acc = acc + grads[(int64_t)w * worker_stride + k];
-                gbar = acc * inv_n;
-            }
-            float prod = gbar * P[k];
-            q[k] = fabsf(prod);
-            float mv = m->momentum * V[k];
-            float v = mv + gbar;
-            float step = m->lr * v;
-            V[k] = v;
-            P[k] = P[k] - step;
+            update_element(m, aggregate_element(m, grads + k, worker_stride), P, V, q, k);
         }
     }
 }
@@ -162,6 +181,54 @@ void osp_oracle_lgp_correct(const osp_oracle_model *m, const osp_oracle_gib *gib
                 float *p = &Pw[(int64_t)w * param_stride + k];
                 *p = *p - step;
             }
+        }
+}
+
+/*
+ * Gradient splitter (Sec. 4.5): a worker separates its local gradient,
+ * according to the GIB, into the important gradients G^i (stage 1) and the
+ * unimportant gradients G^u (stage 2).  Each part is dense: the elements of its
+ * stage in arena order, nothing in between.  g is ONE worker's arena; g_i and
+ * g_u may each be NULL.  Returns the number of elements of G^u.
+ */
+int64_t osp_oracle_split_gradients(const osp_oracle_model *m, const osp_oracle_gib *gib,
+                                   const float *g, float *g_i, float *g_u)
+{
+    int64_t n_i = 0, n_u = 0;
+    for (int32_t l = 0; l < m->n_tensors; ++l)
+        for (int64_t j = 0; j < m->numel[l]; ++j) {
+            const int64_t k = m->offset[l] + j;
+            if (stage_of(gib, l, k) == 1) {
+                if (g_i)
+                    g_i[n_i] = g[k];
+                ++n_i;
+            } else {
+                if (g_u)
+                    g_u[n_u] = g[k];
+                ++n_u;
+            }
+        }
+    return n_u;
+}
+
+/*
+ * PS side of one stage when the stage's gradients arrive in the dense form
+ * above (worker w's part at packed + w * packed_stride): the same aggregate,
+ * PGP product and update as osp_oracle_aggregate_update, element i of the
+ * dense arrays belonging to the i-th element of the stage in arena order.
+ */
+void osp_oracle_aggregate_update_packed(const osp_oracle_model *m, const osp_oracle_gib *gib,
+                                        int stage, float *P, float *V, const float *packed,
+                                        int64_t packed_stride, float *q)
+{
+    int64_t i = 0;
+    for (int32_t l = 0; l < m->n_tensors; ++l)
+        for (int64_t j = 0; j < m->numel[l]; ++j) {
+            const int64_t k = m->offset[l] + j;
+            if (stage_of(gib, l, k) != stage)
+                continue;
+            update_element(m, aggregate_element(m, packed + i, packed_stride), P, V, q, k);
+            ++i;
         }
 }
 

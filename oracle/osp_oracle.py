@@ -69,6 +69,10 @@ def _load(omp: bool):
         lib.osp_oracle_apply_stage.restype = None
         lib.osp_oracle_lgp_correct.argtypes = [mp, gp, fp, C.c_int64, fp, C.c_int64]
         lib.osp_oracle_lgp_correct.restype = None
+        lib.osp_oracle_split_gradients.argtypes = [mp, gp, fp, fp, fp]
+        lib.osp_oracle_split_gradients.restype = C.c_int64
+        lib.osp_oracle_aggregate_update_packed.argtypes = [mp, gp, C.c_int, fp, fp, fp, C.c_int64, fp]
+        lib.osp_oracle_aggregate_update_packed.restype = None
         lib.osp_oracle_eq7_literal.argtypes = [mp, gp, fp, C.c_int64, fp, C.c_int64, fp, fp,
                                                C.POINTER(C.c_double)]
         lib.osp_oracle_eq7_literal.restype = None
@@ -167,6 +171,32 @@ class OracleOSP:
         self.lib.osp_oracle_aggregate_update(C.byref(self.model), C.byref(g), stage,
                                              _fp(self.P), _fp(self.V), _fp(grads),
                                              grads.shape[1], _fp(self.q))
+
+    def split_gradients(self, grads: np.ndarray):
+        """Gradient splitter (Sec. 4.5): per worker the dense arrays G^i and G^u.
+        Returns (g_i [N, E1], g_u [N, E2])."""
+        assert grads.dtype == np.float32 and grads.ndim == 2 and grads.shape[0] == self.N
+        n_real = int(np.sum(self.numel))
+        e2 = self.n_stage2
+        g_i = np.zeros((self.N, n_real - e2), np.float32)
+        g_u = np.zeros((self.N, e2), np.float32)
+        g = self._gib()
+        for w in range(self.N):
+            row = np.ascontiguousarray(grads[w])
+            got = self.lib.osp_oracle_split_gradients(C.byref(self.model), C.byref(g), _fp(row),
+                                                      _fp(g_i[w]) if g_i.shape[1] else None,
+                                                      _fp(g_u[w]) if g_u.shape[1] else None)
+            assert got == e2
+        return g_i, g_u
+
+    def ps_aggregate_update_packed(self, stage: int, packed: np.ndarray) -> None:
+        """Stage 1 or 2 fed by the dense arrays of split_gradients."""
+        assert stage in (1, 2) and packed.dtype == np.float32 and packed.ndim == 2
+        assert packed.flags.c_contiguous and packed.shape[0] == self.N
+        g = self._gib()
+        self.lib.osp_oracle_aggregate_update_packed(C.byref(self.model), C.byref(g), stage,
+                                                    _fp(self.P), _fp(self.V), _fp(packed),
+                                                    packed.shape[1], _fp(self.q))
 
     def apply_stage(self, stage: int) -> None:
         g = self._gib()

@@ -14,16 +14,16 @@ CFLAGS = ["-O2", "-std=c11", "-fPIC", "-shared", "-ffp-contract=off", "-fno-fast
 # (name, text in the oracle, replacement): each is one plausible slip
 MUTATIONS = [
     ("pgp_uses_updated_parameter",
-     "            float prod = gbar * P[k];\n            q[k] = fabsf(prod);\n            float mv = m->momentum * V[k];\n            float v = mv + gbar;\n            float step = m->lr * v;\n            V[k] = v;\n            P[k] = P[k] - step;",
-     "            float mv = m->momentum * V[k];\n            float v = mv + gbar;\n            float step = m->lr * v;\n            V[k] = v;\n            P[k] = P[k] - step;\n            float prod = gbar * P[k];\n            q[k] = fabsf(prod);"),
+     "    float prod = gbar * P[k];\n    q[k] = fabsf(prod);\n    float mv = m->momentum * V[k];\n    float v = mv + gbar;\n    float step = m->lr * v;\n    V[k] = v;\n    P[k] = P[k] - step;",
+     "    float mv = m->momentum * V[k];\n    float v = mv + gbar;\n    float step = m->lr * v;\n    V[k] = v;\n    P[k] = P[k] - step;\n    float prod = gbar * P[k];\n    q[k] = fabsf(prod);"),
     ("momentum_dropped", "float mv = m->momentum * V[k];", "float mv = 0.0f * V[k];"),
     ("update_sign", "P[k] = P[k] - step;", "P[k] = P[k] + step;"),
     ("mean_missing", "gbar = acc * inv_n;", "gbar = acc;"),
     ("weight_of_wrong_worker",
-     "float term = m->worker_weight[w] * grads[(int64_t)w * worker_stride + k];",
-     "float term = m->worker_weight[w - 1] * grads[(int64_t)w * worker_stride + k];"),
-    ("worker_stride_ignored", "acc = acc + grads[(int64_t)w * worker_stride + k];",
-     "acc = acc + grads[(int64_t)w * m->arena_elems + k];"),
+     "float term = m->worker_weight[w] * g[(int64_t)w * stride];",
+     "float term = m->worker_weight[w - 1] * g[(int64_t)w * stride];"),
+    ("worker_stride_ignored", "acc = acc + g[(int64_t)w * stride];",
+     "acc = acc + g[(int64_t)w * m->arena_elems];"),
     ("lgp_sign", "*p = *p - step;", "*p = *p + step;"),
     ("lgp_on_wrong_stage", "if (stage_of(gib, l, k) != 2)\n                    continue;\n                float step",
      "if (stage_of(gib, l, k) != 1)\n                    continue;\n                float step"),
@@ -44,6 +44,11 @@ MUTATIONS = [
     ("tuner_first_epoch", "    if (epoch == 1)\n        return 0;\n    double share", "    if (epoch == 0)\n        return 0;\n    double share"),
     ("tuner_share_inverted", "double share = 1.0 - loss_i / L;", "double share = loss_i / L;"),
     ("tuner_bound_divides_by_workers", "return b * (1.0 + loss_rate) * t_c / (double)n_workers;", "return b * (1.0 + loss_rate) * t_c;"),
+    ("splitter_parts_swapped", "if (stage_of(gib, l, k) == 1) {\n                if (g_i)", "if (stage_of(gib, l, k) == 2) {\n                if (g_i)"),
+    ("splitter_reads_tensor_local_index", "                    g_u[n_u] = g[k];", "                    g_u[n_u] = g[j];"),
+    ("packed_update_wrong_stage", "            if (stage_of(gib, l, k) != stage)\n                continue;", "            if (stage_of(gib, l, k) == stage)\n                continue;"),
+    ("packed_update_position_not_advanced", "            ++i;\n        }\n}", "        }\n}"),
+    ("packed_update_uses_arena_index", "aggregate_element(m, packed + i, packed_stride)", "aggregate_element(m, packed + k, packed_stride)"),
     ("layer_sum_drops_last", "for (int64_t j = 0; j < m->numel[l]; ++j) {\n            double x", "for (int64_t j = 0; j + 1 < m->numel[l]; ++j) {\n            double x"),
 ]
 

@@ -513,6 +513,83 @@ def test_gib_is_under_1kb_below_1k_layers():
 
 
 # --------------------------------------------------------------------------
+# gradient splitter (Sec. 4.5): dense G^i / G^u, and the PS update fed by them
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_split_gradients_is_boolean_indexing(gran):
+    """NumPy's boolean indexing is the definition: the stage's elements, in arena order."""
+    wl = small_wl(4)
+    rng = np.random.default_rng(3)
+    arena = wl.arena_elems(); off = wl.offsets()
+    real = brute.real_mask(wl.numel, off, arena)
+    o = make_oracle(wl)
+    if gran == GRAN_LAYER:
+        gib = random_layer_gib(rng, wl.n_tensors)
+        s2 = brute.stage2_mask_from_layer_gib(gib, wl.numel, off, arena)
+    else:
+        gib = random_bits(rng, arena, real)
+        s2 = brute.stage2_mask_from_bits(gib, wl.numel, off, arena)
+    o.set_gib(gran, gib)
+    g = wl.make_grads(0, 0)
+    g[:, ~real] = 9.0                        # padding must not reach either part
+    g_i, g_u = o.split_gradients(g)
+    assert g_i.shape[1] + g_u.shape[1] == wl.n_params and g_u.shape[1] == int(s2.sum())
+    for w in range(wl.n_workers):
+        assert same(g_i[w], g[w, :arena][real & ~s2])
+        assert same(g_u[w], g[w, :arena][s2])
+    # nothing dropped, nothing duplicated (Sec. 3.2): scattering both parts back gives g
+    back = np.zeros(arena, F)
+    back[real & ~s2] = g_i[1]; back[s2] = g_u[1]
+    assert same(back[real], g[1, :arena][real])
+
+
+def test_split_gradients_hand_example():
+    # arena [a b . . c . . .], layers {a b} and {c}; element bitmap: a, c important, b not
+    numel = np.array([2, 1], np.int64); off = np.array([0, 4], np.int64)
+    o = OracleOSP(numel, off, 8, 2, 0.5, 0.5)
+    o.load_params(np.zeros(8, F))
+    g = np.zeros((2, 8), F)
+    g[0, [0, 1, 4]] = [1.0, 2.0, 3.0]; g[1, [0, 1, 4]] = [-1.0, -2.0, -3.0]
+    o.set_gib(GRAN_ELEMENT, np.array([0b11111101], np.uint32))
+    g_i, g_u = o.split_gradients(g)
+    assert g_i.tolist() == [[1.0, 3.0], [-1.0, -3.0]] and g_u.tolist() == [[2.0], [-2.0]]
+    o.set_gib(GRAN_LAYER, np.array([0, 1], np.uint8))
+    g_i, g_u = o.split_gradients(g)
+    assert g_i.tolist() == [[3.0], [-3.0]] and g_u.tolist() == [[1.0, 2.0], [-1.0, -2.0]]
+    # degenerate GIBs: one part is empty
+    o.set_gib(GRAN_LAYER, np.array([1, 1], np.uint8))
+    g_i, g_u = o.split_gradients(g)
+    assert g_i.shape == (2, 3) and g_u.shape == (2, 0)
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_update_from_packed_gradients_equals_update_in_place(gran, weighted):
+    """Feeding the PS the dense parts gives, bit for bit, what the gradients give in place,
+    which in turn is pinned against torch.optim.SGD and the brute force above."""
+    wl = small_wl(3)
+    rng = np.random.default_rng(5)
+    arena = wl.arena_elems()
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    wts = np.array([0.5, 0.2, 0.3], F) if weighted else None
+    a = make_oracle(wl, weights=wts); b = make_oracle(wl, weights=wts)
+    for step in range(2):
+        gib = (random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER
+               else random_bits(rng, arena, real))
+        a.set_gib(gran, gib); b.set_gib(gran, gib)
+        g = wl.make_grads(0, step)
+        g_i, g_u = b.split_gradients(g)
+        # strides larger than the part, garbage behind it
+        pad_i = np.full((wl.n_workers, g_i.shape[1] + 5), 7.0, F); pad_i[:, :g_i.shape[1]] = g_i
+        pad_u = np.full((wl.n_workers, g_u.shape[1] + 3), 7.0, F); pad_u[:, :g_u.shape[1]] = g_u
+        a.ps_aggregate_update(1, g); b.ps_aggregate_update_packed(1, pad_i)
+        assert same(a.P, b.P) and same(a.V, b.V) and same(a.q, b.q)
+        a.ps_aggregate_update(2, g); b.ps_aggregate_update_packed(2, pad_u)
+        assert same(a.P, b.P) and same(a.V, b.V) and same(a.q, b.q)
+
+
+# --------------------------------------------------------------------------
 # chained sync steps against the independent brute force
 # --------------------------------------------------------------------------
 
