@@ -57,7 +57,32 @@ def step_bytes(N, M, E2, element):
         b["agg1"] += 4 * E1
         b["agg2"] += 4 * E2
         b["split"] = 4 * M + M // 8
+    b["rs_window"] = b["agg1"] + b["apply1"] + b["lgp"]
+    b["ics_window"] = b["agg2"] + b["apply2"] + b["split"]
+    b["split_gradients"] = 8 * N * M        # every gradient read once, written once
     return b
+
+
+def step_calls(mode, c, stride, gran, budget, dense):
+    """One sync step as a list of (name, call(g)); names index step_bytes()."""
+    if mode == "windows":
+        return [("rs_window", lambda g: c.osp_rs_window(g, stride)),
+                ("ics_window", lambda g: c.osp_ics_window(g, stride, gran, budget))]
+    six = [("agg1", lambda g: c.osp_ps_aggregate_update(1, g, stride)),
+           ("apply1", lambda g: c.osp_apply_stage(1)),
+           ("lgp", lambda g: c.osp_lgp_correct(g, stride)),
+           ("agg2", lambda g: c.osp_ps_aggregate_update(2, g, stride)),
+           ("apply2", lambda g: c.osp_apply_stage(2)),
+           ("split", lambda g: c.osp_split(gran, budget))]
+    if mode == "six":
+        return six
+    gi, gu, ds = dense                          # the PS is fed by the splitter's dense parts
+    six[0] = ("agg1", lambda g: c.osp_ps_aggregate_update_packed(1, gi, ds))
+    six[3] = ("agg2", lambda g: c.osp_ps_aggregate_update_packed(2, gu, ds))
+    return [("split_gradients", lambda g: c.osp_split_gradients(g, stride, gi, ds, gu, ds))] + six
+
+
+BRACKETED = {"six": ("agg1", "agg2"), "windows": ("rs_window",), "packed": ("split_gradients",)}
 
 
 def main() -> int:
@@ -68,8 +93,9 @@ def main() -> int:
     ap.add_argument("--workload", default="vgg16",
                     choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16", "bert_base"])
     ap.add_argument("--granularity", default="layer", choices=["layer", "element"])
-    ap.add_argument("--calls", default="six", choices=["six", "windows"],
-                    help="six single-stage calls per step, or the RS and ICS window calls")
+    ap.add_argument("--calls", default="six", choices=["six", "windows", "packed"],
+                    help="six single-stage calls per step, the RS and ICS window calls, or the "
+                         "gradient splitter followed by the six calls with the PS fed by its dense parts")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -113,45 +139,39 @@ def main() -> int:
     c.osp_set_gib(0, np.ones(wl.n_tensors, np.uint8))     # iteration 1 is BSP (Algorithm 1)
     n2_log = np.zeros(K, dtype=np.int64)
     windows = args.calls == "windows"
+    mode = args.calls
+    dense = None
+    if mode == "packed":
+        ds = -(-M // 64) * 64 + 64
+        dense = (torch.empty((N, ds), dtype=torch.float32, device="cuda"),
+                 torch.empty((N, ds), dtype=torch.float32, device="cuda"), ds)
+    calls_of_step = step_calls(mode, c, stride, gran, wl.budget, dense)
     for i in range(Wm):
-        if windows:
-            job.sync_step_windows(gsets[i % 2], gran, wl.budget)
-        else:
-            job.sync_step(gsets[i % 2], gran, wl.budget)
-    names = ["agg1", "apply1", "lgp", "agg2", "apply2", "split"]
-    # Timed region: K whole steps.  Inside it only the dominant kernel (the aggregate, launched
-    # twice per step) is bracketed by events, on the stream it is launched on, and only in every
-    # BRACKET_EVERY-th step: an event record between two kernels costs about 5 us of idle GPU.
-    # The per-call breakdown of the other calls comes from a second pass after the timed region.
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(4)] if i % BRACKET_EVERY == 0 else None
-          for i in range(K)]
+        for _, call in calls_of_step:
+            call(gsets[i % 2])
+    # Timed region: K whole steps.  Inside it only the dominant kernel (six calls: the aggregate,
+    # launched twice per step; windows: the RS window; packed: the splitter) is bracketed by events,
+    # on the stream it is launched on, and only in every BRACKET_EVERY-th step: an event record
+    # between two kernels costs about 5 us of idle GPU.  The per-call breakdown of the other calls
+    # comes from a second pass after the timed region.
+    bracketed = BRACKETED[mode]
+    ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+           for n in bracketed} if i % BRACKET_EVERY == 0 else None for i in range(K)]
     torch.cuda.synchronize()
 
     t_start = time.perf_counter()
     for i in range(K):
         g = gsets[(Wm + i) % 2]
         e = ev[i]
-        if windows:                              # the RS window is the bracketed launch
-            if e:
-                e[0].record(); c.osp_rs_window(g, stride); e[1].record()
+        for j, (name, call) in enumerate(calls_of_step):
+            if e and name in e:
+                e[name][0].record(); call(g); e[name][1].record()
             else:
-                c.osp_rs_window(g, stride)
-            n2_log[i] = c.osp_n_stage2()         # host-side; the ICS call waits for the same split
-            c.osp_ics_window(g, stride, gran, wl.budget)
-        else:
-            if e:
-                e[0].record(); c.osp_ps_aggregate_update(1, g, stride); e[1].record()
-            else:
-                c.osp_ps_aggregate_update(1, g, stride)
-            n2_log[i] = c.osp_n_stage2()         # host-side; the call above has waited for that split
-            c.osp_apply_stage(1)
-            c.osp_lgp_correct(g, stride)
-            if e:
-                e[2].record(); c.osp_ps_aggregate_update(2, g, stride); e[3].record()
-            else:
-                c.osp_ps_aggregate_update(2, g, stride)
-            c.osp_apply_stage(2)
-            c.osp_split(gran, wl.budget)
+                call(g)
+            if j == 0:
+                # host-side; every step's first call has waited for the split that set this size,
+                # or (fused RS window) the next call waits for it anyway
+                n2_log[i] = c.osp_n_stage2()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t_start
 
@@ -160,30 +180,28 @@ def main() -> int:
     agg_ms_sum = 0.0
     agg_bytes_sum = 0
     agg_launches = 0
+    step_names = [n for n, _ in calls_of_step]
     for i in range(K):
         b = step_bytes(N, M, int(n2[i]), element)
-        total_bytes += sum(b.values())
+        total_bytes += sum(b[n] for n in step_names)
         if not ev[i]:
             continue
-        if windows:
-            agg_ms_sum += ev[i][0].elapsed_time(ev[i][1])
-            agg_bytes_sum += b["agg1"] + b["apply1"] + b["lgp"]
+        for n in bracketed:
+            agg_ms_sum += ev[i][n][0].elapsed_time(ev[i][n][1])
+            agg_bytes_sum += b[n]
             agg_launches += 1
-        else:
-            agg_ms_sum += ev[i][0].elapsed_time(ev[i][1]) + ev[i][2].elapsed_time(ev[i][3])
-            agg_bytes_sum += b["agg1"] + b["agg2"]
-            agg_launches += 2
     ms_per_step = elapsed * 1e3 / K
     gbps = total_bytes / elapsed / 1e9
     lgp_shared = c.osp_lgp_read_shared()
     moved_bytes = total_bytes - (sum(4 * (N - 1) * int(n2[i]) for i in range(K)) if lgp_shared
                                  and not element else 0)
-    if (lgp_shared and element) or windows:     # whole groups / fused passes: not itemised here
+    if (lgp_shared and element) or mode != "six":  # whole groups / fused passes: not itemised here
         moved_bytes = None
 
     # dominant kernel: the aggregate+update kernel, launched twice per step
     fused_rs = windows and (c.osp_windows_fused() & 1) != 0
-    kernel = ("k_aggregate_update" if not windows else
+    kernel = ("k_aggregate_update" if mode == "six" else
+              "k_split_gradients" if mode == "packed" else
               ("k_rs_window_element" if element else "k_window_layer") if fused_rs else
               "osp_rs_window (three single-stage kernels)")
     agg_ms = agg_ms_sum / agg_launches
@@ -192,34 +210,26 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
                 "traffic": (None if wl.name != "vgg16" or c.osp_chunk_elems() != 256 else
-                            AGG_TRAFFIC_VGG16_LAYER if not element and not windows else
+                            AGG_TRAFFIC_VGG16_LAYER if not element and mode == "six" else
                             RS_TRAFFIC_VGG16_ELEMENT if element and fused_rs else None),
                 "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
 
     # second pass (not part of `value`): every call bracketed, for the per-call breakdown
     K2 = min(K, 10)
-    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(7)] for _ in range(K2)]
+    ev2 = [[torch.cuda.Event(enable_timing=True) for _ in range(len(calls_of_step) + 1)]
+           for _ in range(K2)]
     n2b = torch.zeros(K2 + 1, dtype=torch.int64).pin_memory()
     c.osp_read_n_stage2_async(n2b.data_ptr())
     for i in range(K2):
         g = gsets[(Wm + K + i) % 2]
         e = ev2[i]
-        if windows:                              # RS under "agg1", ICS + split under "agg2"
-            e[0].record(); c.osp_rs_window(g, stride)
-            e[1].record(); e[2].record(); e[3].record()
-            c.osp_ics_window(g, stride, gran, wl.budget)
-            e[4].record(); e[5].record(); e[6].record()
-        else:
-            e[0].record(); c.osp_ps_aggregate_update(1, g, stride)
-            e[1].record(); c.osp_apply_stage(1)
-            e[2].record(); c.osp_lgp_correct(g, stride)
-            e[3].record(); c.osp_ps_aggregate_update(2, g, stride)
-            e[4].record(); c.osp_apply_stage(2)
-            e[5].record(); c.osp_split(gran, wl.budget)
-            e[6].record()
+        for j, (_, call) in enumerate(calls_of_step):
+            e[j].record(); call(g)
+        e[len(calls_of_step)].record()
         c.osp_read_n_stage2_async(n2b.data_ptr() + 8 * (i + 1))
     torch.cuda.synchronize()
+    names = step_names
     call_ms = {n: 0.0 for n in names}
     call_bytes = {n: 0 for n in names}
     for i in range(K2):
@@ -227,11 +237,6 @@ def main() -> int:
         for j, n in enumerate(names):
             call_ms[n] += ev2[i][j].elapsed_time(ev2[i][j + 1])
             call_bytes[n] += b[n]
-    if windows:
-        names = ["rs_window", "ics_window"]
-        call_ms = {"rs_window": call_ms["agg1"], "ics_window": call_ms["agg2"]}
-        call_bytes = {"rs_window": call_bytes["agg1"] + call_bytes["apply1"] + call_bytes["lgp"],
-                      "ics_window": call_bytes["agg2"] + call_bytes["apply2"] + call_bytes["split"]}
     calls = {n: {"ms": round(call_ms[n] / K2, 5),
                  "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
              for n in names}

@@ -188,6 +188,29 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
 osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
                                    int64_t worker_stride, void *stream);
 
+/*
+ * Gradient splitter (Sec. 4.5): every worker's gradient arena is separated,
+ * according to the current GIB, into the important gradients G^i (stage 1) and
+ * the unimportant gradients G^u (stage 2).  Each part is dense: the stage's
+ * elements in arena order, nothing in between; worker w's parts start at
+ * g_important + w*important_stride and g_unimportant + w*unimportant_stride
+ * (DEVICE, 4-byte aligned, strides in elements, at least the part's size:
+ * n_params - n_stage2 and n_stage2, see osp_n_stage2).  Either output may be
+ * NULL.  These are the payloads a transport would carry in the two stages; the
+ * other calls of this library read the arenas in place and do not need them.
+ * Does not change the iteration state.
+ */
+osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_stride,
+                               float *g_important, int64_t important_stride,
+                               float *g_unimportant, int64_t unimportant_stride, void *stream);
+
+/* osp_ps_aggregate_update(stage), stage 1 or 2, with the stage's gradients
+ * arriving as the dense parts above (worker w's at packed + w*packed_stride):
+ * same arithmetic in the same order, same results, same place in the order of
+ * calls.  A stage 1 given this way leaves nothing for stage 2 to reuse. */
+osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *packed,
+                                          int64_t packed_stride, void *stream);
+
 /* LGP (Sec. 4.2, Eq. 6): for every stage-2 element and every worker,
  * P_{w,k} = P_{w,k} - lr g_{w,k}: the stale parameter advances by the worker's
  * own local gradient.  Stage-1 elements are not touched. */

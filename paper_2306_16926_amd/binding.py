@@ -82,6 +82,10 @@ def _load() -> C.CDLL:
     lib.osp_lgp_correct.restype = C.c_int
     lib.osp_apply_stage.argtypes = [vp, C.c_int, vp]
     lib.osp_apply_stage.restype = C.c_int
+    lib.osp_split_gradients.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.osp_split_gradients.restype = C.c_int
+    lib.osp_ps_aggregate_update_packed.argtypes = [vp, C.c_int, vp, i64, vp]
+    lib.osp_ps_aggregate_update_packed.restype = C.c_int
     lib.osp_rs_window.argtypes = [vp, vp, i64, vp]
     lib.osp_rs_window.restype = C.c_int
     lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
@@ -114,6 +118,7 @@ lib = _load()
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window",
+           "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
@@ -248,6 +253,18 @@ class Context:
     def osp_apply_stage(self, stage: int, stream=None) -> None:
         self._check(lib.osp_apply_stage(self._h, stage, _stream(stream)))
 
+    def osp_split_gradients(self, grads, worker_stride: int, g_important, important_stride: int,
+                            g_unimportant, unimportant_stride: int, stream=None) -> None:
+        self._check(lib.osp_split_gradients(self._h, _ptr(grads), int(worker_stride),
+                                            _ptr(g_important), int(important_stride),
+                                            _ptr(g_unimportant), int(unimportant_stride),
+                                            _stream(stream)))
+
+    def osp_ps_aggregate_update_packed(self, stage: int, packed, packed_stride: int,
+                                       stream=None) -> None:
+        self._check(lib.osp_ps_aggregate_update_packed(self._h, stage, _ptr(packed),
+                                                       int(packed_stride), _stream(stream)))
+
     def osp_rs_window(self, grads, worker_stride: int, stream=None) -> None:
         self._check(lib.osp_rs_window(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
 
@@ -296,6 +313,16 @@ def osp_lgp_correct(ctx: Context, grads, worker_stride, stream=None):
 
 def osp_apply_stage(ctx: Context, stage, stream=None):
     return ctx.osp_apply_stage(stage, stream)
+
+
+def osp_split_gradients(ctx: Context, grads, worker_stride, g_important, important_stride,
+                        g_unimportant, unimportant_stride, stream=None):
+    return ctx.osp_split_gradients(grads, worker_stride, g_important, important_stride,
+                                   g_unimportant, unimportant_stride, stream)
+
+
+def osp_ps_aggregate_update_packed(ctx: Context, stage, packed, packed_stride, stream=None):
+    return ctx.osp_ps_aggregate_update_packed(stage, packed, packed_stride, stream)
 
 
 def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):

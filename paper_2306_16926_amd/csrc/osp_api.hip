@@ -6,6 +6,7 @@
 #include "../../include/osp.h"
 #include "osp_split_kernels.hpp"
 #include "osp_window_kernels.hpp"
+#include "osp_pack_kernels.hpp"
 
 #include <cstdarg>
 #include <cstdio>
@@ -54,7 +55,7 @@ struct osp_ctx {
 
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
-           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_big = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0,
+           off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_big = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0, off_pack = 0,
            off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
@@ -75,6 +76,7 @@ struct osp_ctx {
     bool replicas_synced = false, iter_synced = false, last_lgp_shared = false;
     // element-granular stage 1 leaves the aggregate of the stage-2 elements in the stash;
     // valid for a stage-2 call on the same gradient arenas
+    bool pack_index_valid = false;      // the pack index matches the current GIB
     int windows_fused = 0;              // bit 0: last RS window ran fused, bit 1: last ICS window
     bool stash_valid = false;
     const float *stash_grads = nullptr;
@@ -115,6 +117,10 @@ struct osp_ctx {
     float *d_weights() const { return at<float>(off_weights); }
     uint32_t *d_key() const { return at<uint32_t>(off_key); }
     float *d_stash() const { return at<float>(off_stash); }
+    // pack index: base1 [n_chunks+1], base2 [n_chunks+1], block totals 2 x [n_pack_blocks]
+    long long n_pack_blocks() const { return (n_chunks + kScanBlock - 1) / kScanBlock; }
+    long long *d_pack_base(int stage) const { return at<long long>(off_pack) + (size_t)(stage - 1) * (size_t)(n_chunks + 1); }
+    long long *d_pack_tot(int stage) const { return at<long long>(off_pack) + 2 * (size_t)(n_chunks + 1) + (size_t)(stage - 1) * (size_t)n_pack_blocks(); }
     uint32_t *d_bitmap() const { return at<uint32_t>(off_bitmap); }
     unsigned long long *d_hist(int pass) const
     {
@@ -180,6 +186,7 @@ void layout_workspace(osp_ctx *c)
     c->off_gib = take((size_t)c->n_tensors);
     c->off_state = take(sizeof(SplitState));
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
+    c->off_pack = take((2 * (nc + 1) + 2 * (size_t)c->n_pack_blocks()) * sizeof(long long));
     if (c->element_keys) {
         c->off_key = take((size_t)c->arena * sizeof(uint32_t));
         c->off_stash = take((size_t)c->arena * sizeof(float));
@@ -538,6 +545,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         ctx->n_stage2_host = n2;
     }
     ctx->have_gib = true;
+    ctx->pack_index_valid = false;
     ctx->gib_gran = granularity;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     return OSP_OK;
@@ -1101,6 +1109,166 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
     return osp_split(ctx, granularity, budget_elems, stream);
 }
 
+// Build the pack index of the current GIB if it is not there yet (four small launches).
+static osp_status ensure_pack_index(osp_ctx *ctx, hipStream_t s)
+{
+    if (ctx->pack_index_valid)
+        return OSP_OK;
+    PackIndexArgs a;
+    a.spans = ctx->d_spans();
+    a.span_layer = ctx->d_slayer();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.chunk_elems = ctx->chunk_elems;
+    a.element = ctx->gib_gran == OSP_GRAN_ELEMENT ? 1 : 0;
+    a.base1 = ctx->d_pack_base(1);
+    a.base2 = ctx->d_pack_base(2);
+    const unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
+    const unsigned nb = (unsigned)ctx->n_pack_blocks();
+    k_pack_count<<<n_groups, kBlock, 0, s>>>(a);
+    k_pack_block_totals<<<nb, kScanBlock, 0, s>>>(ctx->n_chunks, a.base1, a.base2,
+                                                 ctx->d_pack_tot(1), ctx->d_pack_tot(2));
+    k_pack_scan_totals<<<1, kScanBlock, 0, s>>>((long long)nb, ctx->n_chunks, ctx->d_pack_tot(1),
+                                               ctx->d_pack_tot(2), a.base1, a.base2);
+    k_pack_scan_chunks<<<nb, kScanBlock, 0, s>>>(ctx->n_chunks, ctx->d_pack_tot(1), ctx->d_pack_tot(2),
+                                                a.base1, a.base2);
+    osp_status st = launch_check(ctx, "pack index kernels");
+    if (st != OSP_OK)
+        return st;
+    ctx->pack_index_valid = true;
+    return OSP_OK;
+}
+
+osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_stride,
+                               float *g_important, int64_t important_stride,
+                               float *g_unimportant, int64_t unimportant_stride, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    osp_status st = check_grads(ctx, grads, worker_stride);
+    if (st != OSP_OK)
+        return st;
+    if (!g_important && !g_unimportant)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "both outputs are NULL");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "the splitter needs a GIB");
+    st = stage_counts(ctx);             // the stage-2 size of a split that may still be running
+    if (st != OSP_OK)
+        return st;
+    const long long e2 = ctx->n_stage2_host, e1 = ctx->n_params - e2;
+    if (g_important && important_stride < e1)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "important_stride %lld is below the %lld stage-1 elements",
+                    (long long)important_stride, e1);
+    if (g_unimportant && unimportant_stride < e2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "unimportant_stride %lld is below the %lld stage-2 elements",
+                    (long long)unimportant_stride, e2);
+    hipStream_t s = (hipStream_t)stream;
+    st = ensure_pack_index(ctx, s);
+    if (st != OSP_OK)
+        return st;
+    SplitGradArgs a;
+    a.spans = ctx->d_spans();
+    a.span_layer = ctx->d_slayer();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.chunk_elems = ctx->chunk_elems;
+    a.element = ctx->gib_gran == OSP_GRAN_ELEMENT ? 1 : 0;
+    a.base1 = ctx->d_pack_base(1);
+    a.base2 = ctx->d_pack_base(2);
+    a.worker_stride = worker_stride;
+    a.stride_i = important_stride;
+    a.stride_u = unimportant_stride;
+    const unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
+    for (int w0 = 0; w0 < ctx->n_workers; w0 += 65535) {   // grid.y is limited to 65535
+        const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
+        a.grads = grads + (long long)w0 * worker_stride;
+        a.g_i = g_important ? g_important + (long long)w0 * important_stride : nullptr;
+        a.g_u = g_unimportant ? g_unimportant + (long long)w0 * unimportant_stride : nullptr;
+        k_split_gradients<<<dim3(n_groups, (unsigned)nw), kBlock, 0, s>>>(a);
+    }
+    return launch_check(ctx, "k_split_gradients");
+}
+
+osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *packed,
+                                          int64_t packed_stride, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (stage != 1 && stage != 2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 1 or 2 (got %d)", stage);
+    if (!packed)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "packed is NULL");
+    if (reinterpret_cast<uintptr_t>(packed) % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "packed must be 4-byte aligned");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (!ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB (osp_set_gib or osp_split)");
+    if (stage == 1 && stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE,
+                    "stage 2 of the previous iteration is still pending (ICS must complete first)");
+    if (stage == 2 && !stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 needs this iteration's stage 1 first");
+    osp_status st = stage_counts(ctx);
+    if (st != OSP_OK)
+        return st;
+    const long long e2 = ctx->n_stage2_host, need = stage == 1 ? ctx->n_params - e2 : e2;
+    if (packed_stride < need)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "packed_stride %lld is below the %lld elements of stage %d",
+                    (long long)packed_stride, need, stage);
+    hipStream_t s = (hipStream_t)stream;
+    st = ensure_pack_index(ctx, s);
+    if (st != OSP_OK)
+        return st;
+    PackedAggArgs a;
+    a.spans = ctx->d_spans();
+    a.span_layer = ctx->d_slayer();
+    a.gib_layer = ctx->d_gib();
+    a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
+    a.chunk_elems = ctx->chunk_elems;
+    a.element = ctx->gib_gran == OSP_GRAN_ELEMENT ? 1 : 0;
+    a.base = ctx->d_pack_base(stage);
+    a.P = ctx->P;
+    a.V = ctx->V;
+    a.packed = packed;
+    a.packed_stride = packed_stride;
+    a.weights = ctx->d_weights();
+    a.partial = ctx->d_partial(stage == 2 ? 1 : 0);
+    a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+    a.n_workers = ctx->n_workers;
+    a.stage = stage;
+    a.inv_n = 1.0f / (float)ctx->n_workers;
+    a.lr = ctx->lr;
+    a.mu = ctx->mu;
+    const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
+    // an empty stage launches nothing, unless the GIB is element-granular: a layer split sums
+    // both stages' importance partials of every chunk, so each call has to leave its own
+    if (need > 0 || a.element) {
+        const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+        switch (variant) {
+        case 0: k_aggregate_update_packed<false, false><<<grid, block, 0, s>>>(a); break;
+        case 1: k_aggregate_update_packed<false, true><<<grid, block, 0, s>>>(a); break;
+        case 2: k_aggregate_update_packed<true, false><<<grid, block, 0, s>>>(a); break;
+        default: k_aggregate_update_packed<true, true><<<grid, block, 0, s>>>(a); break;
+        }
+    }
+    st = launch_check(ctx, "k_aggregate_update_packed");
+    if (st != OSP_OK)
+        return st;
+    if (stage == 1) {                   // a new iteration begins: the PS moves away from the replicas
+        ctx->iter_synced = ctx->replicas_synced;
+        ctx->replicas_synced = false;
+        ctx->stash_valid = false;       // the stage-2 gradients were not at hand
+        ctx->agg1 = true;
+        ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
+    } else {
+        ctx->agg2 = true;
+    }
+    return OSP_OK;
+}
+
 osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream)
 {
     if (!ctx)
@@ -1158,6 +1326,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     if (st != OSP_OK)
         return st;
     ctx->have_gib = true;
+    ctx->pack_index_valid = false;
     ctx->gib_gran = granularity;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     return OSP_OK;

@@ -148,6 +148,32 @@ __device__ __forceinline__ uint32_t importance_key(float q)
     return (q != q) ? 0x7FC00000u : (__float_as_uint(q) & 0x7FFFFFFFu);
 }
 
+__device__ __forceinline__ f4 abs4(f4 x)
+{
+    f4 q;
+    q.x = __builtin_fabsf(x.x); q.y = __builtin_fabsf(x.y);
+    q.z = __builtin_fabsf(x.z); q.w = __builtin_fabsf(x.w);
+    return q;
+}
+
+__device__ __forceinline__ f4 keys4(f4 q)
+{
+    u4 k;
+    k.x = importance_key(q.x); k.y = importance_key(q.y);
+    k.z = importance_key(q.z); k.w = importance_key(q.w);
+    return __builtin_bit_cast(f4, k);
+}
+
+__device__ __forceinline__ double masked_sum(unsigned m, f4 q)
+{
+    double s = 0.0;
+    if (m & 1u) s += (double)q.x;
+    if (m & 2u) s += (double)q.y;
+    if (m & 4u) s += (double)q.z;
+    if (m & 8u) s += (double)q.w;
+    return s;
+}
+
 // ---------------------------------------------------------------------------
 // PS aggregate + update (+ PGP importance), one stage.
 // ---------------------------------------------------------------------------
