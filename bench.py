@@ -47,11 +47,12 @@ AGG_TRAFFIC_VGG16_LAYER = 5544134144
 RS_TRAFFIC_VGG16_ELEMENT = 21157289984
 
 
-def step_bytes(N, M, E2, element):
+def step_bytes(N, M, E2, element, gb=4):
+    """Algorithmic bytes per call; gb = bytes per stored gradient element (4, or 2 for bfloat16)."""
     E1 = M - E2
     b = {
-        "agg1": 4 * (N + 4) * E1, "apply1": 4 * (N + 1) * E1, "lgp": 12 * N * E2,
-        "agg2": 4 * (N + 4) * E2, "apply2": 4 * (N + 1) * E2, "split": 0,
+        "agg1": (gb * N + 16) * E1, "apply1": 4 * (N + 1) * E1, "lgp": (8 + gb) * N * E2,
+        "agg2": (gb * N + 16) * E2, "apply2": 4 * (N + 1) * E2, "split": 0,
     }
     if element:
         b["agg1"] += 4 * E1
@@ -63,8 +64,15 @@ def step_bytes(N, M, E2, element):
     return b
 
 
-def step_calls(mode, c, stride, gran, budget, dense):
+def step_calls(mode, c, stride, gran, budget, dense, bf16=False):
     """One sync step as a list of (name, call(g)); names index step_bytes()."""
+    if bf16:
+        return [("agg1", lambda g: c.osp_ps_aggregate_update_bf16(1, g, stride)),
+                ("apply1", lambda g: c.osp_apply_stage(1)),
+                ("lgp", lambda g: c.osp_lgp_correct_bf16(g, stride)),
+                ("agg2", lambda g: c.osp_ps_aggregate_update_bf16(2, g, stride)),
+                ("apply2", lambda g: c.osp_apply_stage(2)),
+                ("split", lambda g: c.osp_split(gran, budget))]
     if mode == "windows":
         return [("rs_window", lambda g: c.osp_rs_window(g, stride)),
                 ("ics_window", lambda g: c.osp_ics_window(g, stride, gran, budget))]
@@ -96,6 +104,8 @@ def main() -> int:
     ap.add_argument("--calls", default="six", choices=["six", "windows", "packed"],
                     help="six single-stage calls per step, the RS and ICS window calls, or the "
                          "gradient splitter followed by the six calls with the PS fed by its dense parts")
+    ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"],
+                    help="storage type of the gradient arenas (bf16: --calls six only)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -128,10 +138,23 @@ def main() -> int:
                     element_keys=element, chunk_elems=args.chunk_elems, param_stride=stride)
     # two gradient sets, alternated, so a step never re-reads what the last one left in cache
     host_g0 = wl.make_grads(args.seed, 0, stride=stride, threads=args.gen_threads)
-    gsets = [job.upload_grads(host_g0)]
-    tmp = wl.make_grads(args.seed, 1, stride=stride, threads=args.gen_threads)
-    gsets.append(job.upload_grads(tmp))
-    del tmp
+    bf16 = args.grad_dtype == "bf16"
+    if bf16 and args.calls != "six":
+        print("bench.py: --grad-dtype bf16 goes with --calls six", file=sys.stderr)
+        return 2
+    gb = 2 if bf16 else 4
+    if bf16:                                    # rounded once, on the host; the oracle leg gets the widened values
+        h = W.to_bf16(host_g0)
+        host_g0 = W.from_bf16(h)
+        gsets = [job.upload_grads_bf16(h)]
+        gsets.append(job.upload_grads_bf16(W.to_bf16(
+            wl.make_grads(args.seed, 1, stride=stride, threads=args.gen_threads))))
+        del h
+    else:
+        gsets = [job.upload_grads(host_g0)]
+        tmp = wl.make_grads(args.seed, 1, stride=stride, threads=args.gen_threads)
+        gsets.append(job.upload_grads(tmp))
+        del tmp
     print(f"[bench] {wl.name}: N={N} L={wl.n_tensors} M={M} inputs ready in {time.time()-t0:.1f}s",
           file=sys.stderr, flush=True)
 
@@ -145,7 +168,7 @@ def main() -> int:
         ds = -(-M // 64) * 64 + 64
         dense = (torch.empty((N, ds), dtype=torch.float32, device="cuda"),
                  torch.empty((N, ds), dtype=torch.float32, device="cuda"), ds)
-    calls_of_step = step_calls(mode, c, stride, gran, wl.budget, dense)
+    calls_of_step = step_calls(mode, c, stride, gran, wl.budget, dense, bf16)
     for i in range(Wm):
         for _, call in calls_of_step:
             call(gsets[i % 2])
@@ -182,7 +205,7 @@ def main() -> int:
     agg_launches = 0
     step_names = [n for n, _ in calls_of_step]
     for i in range(K):
-        b = step_bytes(N, M, int(n2[i]), element)
+        b = step_bytes(N, M, int(n2[i]), element, gb)
         total_bytes += sum(b[n] for n in step_names)
         if not ev[i]:
             continue
@@ -210,7 +233,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
                 "traffic": (None if wl.name != "vgg16" or c.osp_chunk_elems() != 256 else
-                            AGG_TRAFFIC_VGG16_LAYER if not element and mode == "six" else
+                            AGG_TRAFFIC_VGG16_LAYER if not element and mode == "six" and not bf16 else
                             RS_TRAFFIC_VGG16_ELEMENT if element and fused_rs else None),
                 "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
@@ -233,7 +256,7 @@ def main() -> int:
     call_ms = {n: 0.0 for n in names}
     call_bytes = {n: 0 for n in names}
     for i in range(K2):
-        b = step_bytes(N, M, int(n2b[i]), element)
+        b = step_bytes(N, M, int(n2b[i]), element, gb)
         for j, n in enumerate(names):
             call_ms[n] += ev2[i][j].elapsed_time(ev2[i][j + 1])
             call_bytes[n] += b[n]
@@ -264,7 +287,7 @@ def main() -> int:
         "metric": "osp_sync_step_GBps", "value": round(gbps, 1), "unit": "GB/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": round(ms_per_step, 4),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f32", "data": "synthetic",
+        "dtype": "f32" if not bf16 else "f32 (gradients stored as bf16)", "data": "synthetic",
         "config": {"workload": f"{wl.name}-shaped", "n_workers": N, "n_tensors": wl.n_tensors,
                    "n_params": M, "granularity": args.granularity, "calls": args.calls,
                    "windows_fused": ({"rs": bool(c.osp_windows_fused() & 1),
@@ -312,7 +335,8 @@ def cpu_baseline(wl, args, params, host_g, job, gran, element, stride):
             sample = "1 sync step without the element split (a full sort of M keys)"
         dt = time.perf_counter() - t
         b = step_bytes(N, M, n2, element)
-        res[omp] = (dt, sum(b.values()) / dt / 1e9, sample)
+        six = ("agg1", "apply1", "lgp", "agg2", "apply2", "split")
+        res[omp] = (dt, sum(b[n] for n in six) / dt / 1e9, sample)
         del o
     try:
         cores_all = len(os.sched_getaffinity(0))

@@ -217,6 +217,23 @@ osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *
 osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stride,
                            void *stream);
 
+/*
+ * The two calls that read gradients, for gradient arenas kept in bfloat16
+ * (fp32 master parameters and momentum as before): halves the N x M bytes the
+ * step reads most.  Not in the paper.  grads: DEVICE, 8-byte aligned, worker
+ * w's arena at grads + w*worker_stride (elements).  A bfloat16 widens to fp32
+ * exactly, and everything after the load is the fp32 arithmetic above on those
+ * values: the result is bit for bit that of the fp32 calls given the widened
+ * gradients.  Rounding gradients to bfloat16 is the caller's business.
+ * Same place in the order of calls; may be mixed with the fp32 calls from one
+ * iteration to the next, not between the two stages of one iteration if the
+ * kept stage-2 aggregate (element-granular GIB) is to be reused.
+ */
+osp_status osp_ps_aggregate_update_bf16(osp_ctx *ctx, int stage, const uint16_t *grads,
+                                        int64_t worker_stride, void *stream);
+osp_status osp_lgp_correct_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                                void *stream);
+
 /* Workers receive the global parameters of a stage (Sec. 2.1.1); for stage 2
  * this is the correction of Eq. 7, which replaces the local LGP estimate by the
  * global result (taken as an overwrite, P_{w,k} = P_k).  stage: 1, 2, or 0 = both. */

@@ -80,6 +80,10 @@ def _load() -> C.CDLL:
     lib.osp_ps_aggregate_update.restype = C.c_int
     lib.osp_lgp_correct.argtypes = [vp, vp, i64, vp]
     lib.osp_lgp_correct.restype = C.c_int
+    lib.osp_ps_aggregate_update_bf16.argtypes = [vp, C.c_int, vp, i64, vp]
+    lib.osp_ps_aggregate_update_bf16.restype = C.c_int
+    lib.osp_lgp_correct_bf16.argtypes = [vp, vp, i64, vp]
+    lib.osp_lgp_correct_bf16.restype = C.c_int
     lib.osp_apply_stage.argtypes = [vp, C.c_int, vp]
     lib.osp_apply_stage.restype = C.c_int
     lib.osp_split_gradients.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
@@ -119,6 +123,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
+           "osp_ps_aggregate_update_bf16", "osp_lgp_correct_bf16",
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
@@ -250,6 +255,14 @@ class Context:
     def osp_lgp_correct(self, grads, worker_stride: int, stream=None) -> None:
         self._check(lib.osp_lgp_correct(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
 
+    def osp_ps_aggregate_update_bf16(self, stage: int, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_ps_aggregate_update_bf16(self._h, stage, _ptr(grads), int(worker_stride),
+                                                     _stream(stream)))
+
+    def osp_lgp_correct_bf16(self, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_lgp_correct_bf16(self._h, _ptr(grads), int(worker_stride),
+                                             _stream(stream)))
+
     def osp_apply_stage(self, stage: int, stream=None) -> None:
         self._check(lib.osp_apply_stage(self._h, stage, _stream(stream)))
 
@@ -309,6 +322,14 @@ def osp_ps_aggregate_update(ctx: Context, stage, grads, worker_stride, stream=No
 
 def osp_lgp_correct(ctx: Context, grads, worker_stride, stream=None):
     return ctx.osp_lgp_correct(grads, worker_stride, stream)
+
+
+def osp_ps_aggregate_update_bf16(ctx: Context, stage, grads, worker_stride, stream=None):
+    return ctx.osp_ps_aggregate_update_bf16(stage, grads, worker_stride, stream)
+
+
+def osp_lgp_correct_bf16(ctx: Context, grads, worker_stride, stream=None):
+    return ctx.osp_lgp_correct_bf16(grads, worker_stride, stream)
 
 
 def osp_apply_stage(ctx: Context, stage, stream=None):

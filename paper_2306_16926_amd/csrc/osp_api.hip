@@ -79,8 +79,9 @@ struct osp_ctx {
     bool pack_index_valid = false;      // the pack index matches the current GIB
     int windows_fused = 0;              // bit 0: last RS window ran fused, bit 1: last ICS window
     bool stash_valid = false;
-    const float *stash_grads = nullptr;
+    const void *stash_grads = nullptr;
     long long stash_stride = 0;
+    bool stash_bf16 = false;
 
     // ---- stage-table lengths (layer-granular GIB) ----
     // The split runs on the device; the ranking kernel publishes the two table
@@ -198,12 +199,12 @@ void layout_workspace(osp_ctx *c)
     c->ws_bytes = o;
 }
 
-osp_status check_grads(osp_ctx *ctx, const float *grads, int64_t stride)
+osp_status check_grads(osp_ctx *ctx, const void *grads, int64_t stride, bool bf16 = false)
 {
     if (!grads)
         return fail(ctx, OSP_ERR_INVALID_ARG, "grads is NULL");
-    if (!aligned16(grads))
-        return fail(ctx, OSP_ERR_INVALID_ARG, "grads must be 16-byte aligned");
+    if (bf16 ? reinterpret_cast<uintptr_t>(grads) % 8 != 0 : !aligned16(grads))
+        return fail(ctx, OSP_ERR_INVALID_ARG, "grads must be %d-byte aligned", bf16 ? 8 : 16);
     if (stride < ctx->arena || stride % 4 != 0)
         return fail(ctx, OSP_ERR_INVALID_ARG,
                     "worker_stride %lld must be a multiple of 4 and >= arena_elems %lld",
@@ -271,6 +272,19 @@ osp_status launch_check(osp_ctx *ctx, const char *what)
 }
 
 } // namespace
+
+template <typename GT>
+static void launch_aggregate(int variant, dim3 grid, dim3 block, hipStream_t s, const AggArgs &a)
+{
+    switch (variant) {
+    case 0: k_aggregate_update<false, false, false, GT><<<grid, block, 0, s>>>(a); break;
+    case 1: k_aggregate_update<false, false, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 2: k_aggregate_update<false, true, false, GT><<<grid, block, 0, s>>>(a); break;
+    case 3: k_aggregate_update<false, true, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 5: k_aggregate_update<true, false, true, GT><<<grid, block, 0, s>>>(a); break;
+    default: k_aggregate_update<true, true, true, GT><<<grid, block, 0, s>>>(a); break;
+    }
+}
 
 extern "C" {
 
@@ -600,14 +614,14 @@ osp_status osp_n_stage2(osp_ctx *ctx, int64_t *n_stage2)
     return OSP_OK;
 }
 
-osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
-                                   int64_t worker_stride, void *stream)
+static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, int64_t worker_stride,
+                                   void *stream, bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
     if (stage < 0 || stage > 2)
         return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 0, 1 or 2 (got %d)", stage);
-    osp_status st = check_grads(ctx, grads, worker_stride);
+    osp_status st = check_grads(ctx, grads, worker_stride, bf16);
     if (st != OSP_OK)
         return st;
     if (!ctx->bound)
@@ -647,7 +661,7 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         a.partial_other = ctx->d_partial(1);
     }
     const bool from_stash = masked && stage == 2 && ctx->stash_valid && ctx->stash_grads == grads &&
-                            ctx->stash_stride == (long long)worker_stride;
+                            ctx->stash_stride == (long long)worker_stride && ctx->stash_bf16 == bf16;
     a.n_workers = ctx->n_workers;
     a.stage = stage;
     a.inv_n = 1.0f / (float)ctx->n_workers;
@@ -668,16 +682,12 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         sa.mu = ctx->mu;
         k_update_from_stash<<<grid, block, 0, s>>>(sa);
     } else if (n_groups > 0) {        // an empty stage launches nothing
-    switch (variant) {
-    case 0: k_aggregate_update<false, false, false><<<grid, block, 0, s>>>(a); break;
-    case 1: k_aggregate_update<false, false, true><<<grid, block, 0, s>>>(a); break;
-    case 2: k_aggregate_update<false, true, false><<<grid, block, 0, s>>>(a); break;
-    case 3: k_aggregate_update<false, true, true><<<grid, block, 0, s>>>(a); break;
-    case 5: k_aggregate_update<true, false, true><<<grid, block, 0, s>>>(a); break;
-    case 7: k_aggregate_update<true, true, true><<<grid, block, 0, s>>>(a); break;
-    default:
-        return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
-    }
+        if (variant == 4 || variant == 6)
+            return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
+        if (bf16)
+            launch_aggregate<bf16_t>(variant, grid, block, s, a);
+        else
+            launch_aggregate<float>(variant, grid, block, s, a);
     }
     st = launch_check(ctx, "k_aggregate_update");
     if (st != OSP_OK)
@@ -688,6 +698,7 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
         ctx->stash_valid = masked && stage == 1;
         ctx->stash_grads = grads;
         ctx->stash_stride = (long long)worker_stride;
+        ctx->stash_bf16 = bf16;
     }
     if (stage == 1) {
         ctx->agg1 = true;
@@ -701,11 +712,24 @@ osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
     return OSP_OK;
 }
 
-osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
+                                   int64_t worker_stride, void *stream)
+{
+    return aggregate_update(ctx, stage, grads, worker_stride, stream, false);
+}
+
+osp_status osp_ps_aggregate_update_bf16(osp_ctx *ctx, int stage, const uint16_t *grads,
+                                        int64_t worker_stride, void *stream)
+{
+    return aggregate_update(ctx, stage, grads, worker_stride, stream, true);
+}
+
+static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_stride, void *stream,
+                              bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
-    osp_status st = check_grads(ctx, grads, worker_stride);
+    osp_status st = check_grads(ctx, grads, worker_stride, bf16);
     if (st != OSP_OK)
         return st;
     if (!ctx->bound)
@@ -756,10 +780,17 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
                         n_groups);
         const dim3 grid((unsigned)n_groups), block(kApplyBlock);
         if (n_groups > 0) {
-            if (masked)
-                k_lgp_sweep<true><<<grid, block, 0, s>>>(a);
-            else
-                k_lgp_sweep<false><<<grid, block, 0, s>>>(a);
+            if (bf16) {
+                if (masked)
+                    k_lgp_sweep<true, bf16_t><<<grid, block, 0, s>>>(a);
+                else
+                    k_lgp_sweep<false, bf16_t><<<grid, block, 0, s>>>(a);
+            } else {
+                if (masked)
+                    k_lgp_sweep<true><<<grid, block, 0, s>>>(a);
+                else
+                    k_lgp_sweep<false><<<grid, block, 0, s>>>(a);
+            }
         }
     } else {
         LgpArgs a;
@@ -778,12 +809,20 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
                 const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
                 LgpArgs b = a;
                 b.Pw = a.Pw + (long long)w0 * a.param_stride;
-                b.grads = a.grads + (long long)w0 * a.worker_stride;
+                b.grads = static_cast<const char *>(a.grads) +
+                          (long long)w0 * a.worker_stride * (bf16 ? 2 : 4);
                 const dim3 grid(n_groups, (unsigned)nw), block(kBlock);
-                if (masked)
-                    k_lgp_correct<true><<<grid, block, 0, s>>>(b);
-                else
-                    k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+                if (bf16) {
+                    if (masked)
+                        k_lgp_correct<true, bf16_t><<<grid, block, 0, s>>>(b);
+                    else
+                        k_lgp_correct<false, bf16_t><<<grid, block, 0, s>>>(b);
+                } else {
+                    if (masked)
+                        k_lgp_correct<true><<<grid, block, 0, s>>>(b);
+                    else
+                        k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+                }
             }
         }
     }
@@ -792,6 +831,17 @@ osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stri
         return st;
     ctx->lgp_done = true;
     return OSP_OK;
+}
+
+osp_status osp_lgp_correct(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+{
+    return lgp_correct(ctx, grads, worker_stride, stream, false);
+}
+
+osp_status osp_lgp_correct_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                                void *stream)
+{
+    return lgp_correct(ctx, grads, worker_stride, stream, true);
 }
 
 osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
@@ -1006,6 +1056,7 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
     ctx->stash_valid = element;
     ctx->stash_grads = grads;
     ctx->stash_stride = (long long)worker_stride;
+    ctx->stash_bf16 = false;
     ctx->agg1 = ctx->applied1 = ctx->lgp_done = ctx->last_lgp_shared = true;
     ctx->agg2 = ctx->single_pass = ctx->applied2 = false;
     return OSP_OK;
@@ -1048,7 +1099,7 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
     } else {
         if (element) {
             const bool from_stash = ctx->stash_valid && ctx->stash_grads == grads &&
-                                    ctx->stash_stride == (long long)worker_stride;
+                                    ctx->stash_stride == (long long)worker_stride && !ctx->stash_bf16;
             IcsElementArgs a;
             a.spans = ctx->d_spans();
             a.chunk_elems = ctx->chunk_elems;

@@ -72,6 +72,34 @@ __device__ __forceinline__ f4 ld_stream(const float *p)
 {   // read-once data: keep it from displacing reusable lines
     return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
 }
+// Gradient arenas hold fp32 or bfloat16 values.  A bfloat16 is the upper half of
+// the fp32 with the same value, so widening is exact and the arithmetic that
+// follows is the fp32 arithmetic on those values; a lane's 4 elements are one
+// 8-byte load.
+using bf16_t = unsigned short;
+using u2 = __attribute__((ext_vector_type(2))) unsigned int;
+
+template <typename GT>
+__device__ __forceinline__ f4 ld_grad(const GT *p);
+
+template <>
+__device__ __forceinline__ f4 ld_grad<float>(const float *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
+}
+
+template <>
+__device__ __forceinline__ f4 ld_grad<bf16_t>(const bf16_t *p)
+{
+    const u2 r = __builtin_nontemporal_load(reinterpret_cast<const u2 *>(p));
+    f4 f;
+    f.x = __uint_as_float(r.x << 16);
+    f.y = __uint_as_float(r.x & 0xFFFF0000u);
+    f.z = __uint_as_float(r.y << 16);
+    f.w = __uint_as_float(r.y & 0xFFFF0000u);
+    return f;
+}
+
 __device__ __forceinline__ f4 ld_keep(const float *p)
 {
     return *reinterpret_cast<const f4 *>(p);
@@ -183,7 +211,7 @@ struct AggArgs {
     const uint32_t *bitmap;            // bit per element (element-granular GIB), when MASKED
     float *P;
     float *V;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
     const float *weights;              // [N] device, used when WEIGHTED
     double *partial;                   // [n_chunks] importance partial of this stage
@@ -198,15 +226,15 @@ struct AggArgs {
 // Add B consecutive workers' gradients (w0 .. w0+B-1) to the running sum, in
 // ascending worker order; with w0 == 0 worker 0 starts the sum.  All B loads
 // are issued before the first add.
-template <int B, bool WEIGHTED>
-__device__ __forceinline__ void add_workers(f4 &acc, int w0, const float *__restrict__ g0,
+template <int B, bool WEIGHTED, typename GT = float>
+__device__ __forceinline__ void add_workers(f4 &acc, int w0, const GT *__restrict__ g0,
                                             long long worker_stride, unsigned i,
                                             const float *__restrict__ weights)
 {
     f4 g[B];
 #pragma unroll
     for (int j = 0; j < B; ++j)
-        g[j] = ld_stream(g0 + (long long)(w0 + j) * worker_stride + i);
+        g[j] = ld_grad<GT>(g0 + (long long)(w0 + j) * worker_stride + i);
     if (WEIGHTED) {
 #pragma unroll
         for (int j = 0; j < B; ++j)
@@ -223,7 +251,7 @@ __device__ __forceinline__ void add_workers(f4 &acc, int w0, const float *__rest
 
 constexpr int kWorkerBlock = 16;       // most gradient streams in flight per lane
 
-template <bool MASKED, bool WEIGHTED, bool KEYS>
+template <bool MASKED, bool WEIGHTED, bool KEYS, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 {
     Piece c;
@@ -233,7 +261,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
     // uniform bases of this chunk in every stream
     float *Pc = a.P + c.start;
     float *Vc = a.V + c.start;
-    const float *Gc = a.grads + c.start;
+    const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
     double imp = 0.0, imp_other = 0.0;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         // (masked: the data loads do not wait for the bitmap word; a group with no
@@ -246,12 +274,12 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         f4 acc;
         int w = 0;
         for (; w + kWorkerBlock <= N; w += kWorkerBlock)
-            add_workers<kWorkerBlock, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights);
+            add_workers<kWorkerBlock, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights);
         const int rest = N - w;
-        if (rest & 8) { add_workers<8, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
-        if (rest & 4) { add_workers<4, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
-        if (rest & 2) { add_workers<2, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
-        if (rest & 1) { add_workers<1, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); }
+        if (rest & 8) { add_workers<8, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
+        if (rest & 4) { add_workers<4, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
+        if (rest & 2) { add_workers<2, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
+        if (rest & 1) { add_workers<1, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); }
         const f4 gbar = WEIGHTED ? acc : acc * a.inv_n;
         const f4 prod = gbar * p;
         f4 q;
@@ -489,14 +517,14 @@ struct LgpArgs {
     const uint32_t *bitmap;
     float *Pw;
     long long param_stride;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
     float lr;
 };
 
 // grid = (chunks of stage 2, workers): one workgroup moves one chunk of ONE
 // replica, so the whole GPU sweeps one worker's arena at a time (three streams).
-template <bool MASKED>
+template <bool MASKED, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
 {
     Piece c;
@@ -504,11 +532,11 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
         return;
     const long long w = blockIdx.y;
     float *pw = a.Pw + w * a.param_stride + c.start;
-    const float *gw = a.grads + w * a.worker_stride + c.start;
+    const GT *gw = static_cast<const GT *>(a.grads) + w * a.worker_stride + c.start;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         const unsigned m = lane_mask<MASKED>(c.len - (int)i, c.start + i, 2, a.bitmap);
         const f4 p = ld_stream(pw + i);
-        const f4 g = ld_stream(gw + i);
+        const f4 g = ld_grad<GT>(gw + i);
         const f4 step = g * a.lr;
         const f4 pn = p - step;
         if (!MASKED && m == 0xFu) {
@@ -556,7 +584,7 @@ struct LgpSweepArgs {
     const float *P;
     float *Pw;
     long long param_stride;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
     unsigned n_spans;
     unsigned pieces_per_span;
@@ -565,7 +593,7 @@ struct LgpSweepArgs {
     float lr;
 };
 
-template <bool MASKED>
+template <bool MASKED, typename GT = float>
 __global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
 {
     const unsigned per_worker = a.spans_per_block * a.pieces_per_span;
@@ -584,7 +612,7 @@ __global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
     float *dst = a.Pw + (long long)w * a.param_stride + e;
     const unsigned m = lane_mask<MASKED>(rem, e, 2, a.bitmap);
     const f4 p = ld_keep(a.P + e);             // kept in cache for the other replicas' sweeps
-    const f4 g = ld_stream(a.grads + (long long)w * a.worker_stride + e);
+    const f4 g = ld_grad<GT>(static_cast<const GT *>(a.grads) + (long long)w * a.worker_stride + e);
     const f4 step = g * a.lr;
     const f4 pn = p - step;
     if (!MASKED && m == 0xFu) {

@@ -44,6 +44,20 @@ class DeviceJob:
         assert grads_host.dtype == np.float32 and grads_host.ndim == 2
         return torch.from_numpy(grads_host).to(self.dev)
 
+    def upload_grads_bf16(self, grads_bf16_host: np.ndarray) -> torch.Tensor:
+        """bfloat16 bit patterns (uint16, [N, stride]) as a device tensor of int16."""
+        assert grads_bf16_host.dtype == np.uint16 and grads_bf16_host.ndim == 2
+        return torch.from_numpy(grads_bf16_host.view(np.int16)).to(self.dev)
+
+    def sync_step_bf16(self, grads: torch.Tensor, granularity: int, budget_elems: int) -> None:
+        c, s = self.ctx, grads.shape[1]
+        c.osp_ps_aggregate_update_bf16(1, grads, s)
+        c.osp_apply_stage(1)
+        c.osp_lgp_correct_bf16(grads, s)
+        c.osp_ps_aggregate_update_bf16(2, grads, s)
+        c.osp_apply_stage(2)
+        c.osp_split(granularity, budget_elems)
+
     # the six calls of one synchronization step, in the paper's order
     def sync_step(self, grads: torch.Tensor, granularity: int, budget_elems: int) -> None:
         c, s = self.ctx, grads.shape[1]

@@ -133,6 +133,25 @@ def _grad_outliers(rng: np.random.Generator, out: np.ndarray, tensor_scale: floa
         out[a:b][hit] *= np.float32(100.0)
 
 
+# ----------------------------------------------------------------------------
+# bfloat16 storage of gradients (input preparation only)
+# ----------------------------------------------------------------------------
+
+def to_bf16(a: np.ndarray) -> np.ndarray:
+    """fp32 -> bfloat16 bit patterns (uint16), round to nearest even; NaN stays NaN."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32).astype(np.uint64)
+    r = (u + 0x7FFF + ((u >> 16) & 1)) >> 16
+    nan = np.isnan(a)
+    if nan.any():
+        r[nan] = (u[nan] >> 16) | 0x40
+    return r.astype(np.uint16)
+
+
+def from_bf16(h: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns -> the fp32 with the same value (exact)."""
+    return (np.ascontiguousarray(h, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
+
+
 @dataclasses.dataclass(frozen=True)
 class Workload:
     name: str

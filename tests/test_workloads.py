@@ -25,3 +25,17 @@ def test_seeded_and_distinct():
     assert np.array_equal(a, t)
     assert abs(float(a.std()) - 1e-3) < 1e-4
     assert abs(float(wl.make_params(0).std()) - 0.05) < 5e-3
+
+
+def test_bf16_storage_rounds_like_torch_and_widens_exactly():
+    import torch
+    from paper_2306_16926_amd.workloads import from_bf16, to_bf16
+    rng = np.random.default_rng(0)
+    a = (rng.standard_normal(200_000) * 10.0 ** rng.uniform(-8, 3, 200_000)).astype(np.float32)
+    a[:6] = [np.inf, -np.inf, 0.0, -0.0, 3.3895314e38, 1e-40]      # overflow to inf, subnormal
+    h = to_bf16(a)
+    t = torch.from_numpy(a).to(torch.bfloat16)
+    assert np.array_equal(h, t.view(torch.int16).numpy().view(np.uint16))
+    assert np.array_equal(from_bf16(h), t.float().numpy())
+    assert np.array_equal(to_bf16(from_bf16(h)), h)               # representable values are fixed points
+    assert np.isnan(from_bf16(to_bf16(np.array([np.nan], np.float32))))[0]
