@@ -453,6 +453,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         OSP_HIP(hipHostMalloc((void **)&ctx->pinned_counts, sizeof(StageCounts), hipHostMallocMapped));
         OSP_HIP(hipHostGetDevicePointer((void **)&ctx->pinned_counts_dev, ctx->pinned_counts, 0));
         ctx->pinned_counts->n[0] = ctx->pinned_counts->n[1] = 0;
+        ctx->pinned_counts->n_stage2 = 0;
         ctx->pinned_counts->seq = 0;
         ctx->split_seq = 0;
     }
@@ -496,6 +497,8 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     ctx->replicas_synced = buf->replicas_in_sync != 0;
     ctx->iter_synced = false;
     ctx->stash_valid = false;
+    ctx->pack_index_valid = false;
+    ctx->windows_fused = 0;
     ctx->have_gib = false;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     ctx->have_layer_importance = false;
