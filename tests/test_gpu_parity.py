@@ -598,6 +598,123 @@ def test_bf16_gradients_cnn_shaped():
 
 
 # --------------------------------------------------------------------------
+# random legal call sequences over every entry point that touches the state
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_call_sequences(seed):
+    """Iterations assembled at random from the single-stage calls (fp32, bfloat16 and dense
+    gradient inputs), the two windows, optional installs and LGP in any legal order, splits of
+    either granularity or an injected GIB: the state is compared with the oracle after every
+    call.  Gradients are bfloat16-representable so that every input form carries the same values."""
+    import torch
+    say("random sequences", seed)
+    rng = np.random.default_rng(1000 + seed)
+    n_workers = int(rng.choice([2, 5, 8, 11]))
+    wl = W.custom([5000, 3, 1029, 64, 2048, 30000, 2], n_workers, 0.5, align=4, config_id=300 + seed)
+    arena = wl.arena_elems()
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    wts = None
+    if seed % 2:
+        wts = rng.random(n_workers).astype(F); wts /= wts.sum()
+    o = make_oracle(wl, weights=wts)
+    job = device_job(wl, weights=wts, element_keys=True, declare_in_sync=bool(seed % 3))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    M = wl.n_params
+    dense_i = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
+    dense_u = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
+    log = []
+
+    def check(what):
+        log.append(what)
+        try:
+            compare_state(job, o, what)
+        except AssertionError:
+            print("[case] calls so far:", " | ".join(log), flush=True)
+            raise
+
+    for it in range(10):
+        h = W.to_bf16(wl.make_grads(seed, it)); g = W.from_bf16(h)
+        gd = job.upload_grads(g); hd = job.upload_grads_bf16(h); s_ = g.shape[1]
+        packed = None
+
+        def get_packed():
+            og_i, og_u = o.split_gradients(g)
+            c.osp_split_gradients(gd, s_, dense_i, M + 4, dense_u, M + 4)
+            return og_i, og_u
+
+        def agg(stage):
+            nonlocal packed
+            form = rng.choice(["f32", "bf16", "packed"])
+            if form == "packed":
+                if packed is None:
+                    packed = get_packed()
+                part = packed[stage - 1]
+                if part.shape[1]:
+                    o.ps_aggregate_update_packed(stage, part)
+                else:
+                    o.ps_aggregate_update(stage, g)
+                c.osp_ps_aggregate_update_packed(stage, dense_i if stage == 1 else dense_u, M + 4)
+            elif form == "bf16":
+                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update_bf16(stage, hd, s_)
+            else:
+                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update(stage, gd, s_)
+            check(f"it{it} agg{stage}:{form}")
+
+        def lgp():
+            if rng.random() < 0.5:
+                o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+            else:
+                o.lgp_correct(g); c.osp_lgp_correct_bf16(hd, s_)
+            check(f"it{it} lgp")
+
+        lgp_done = False
+        if rng.random() < 0.4:
+            o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+            c.osp_rs_window(gd, s_)
+            lgp_done = True
+            check(f"it{it} rs_window")
+        else:
+            agg(1)
+            todo = []
+            if rng.random() < 0.8:
+                todo.append("apply1")
+            if rng.random() < 0.7:
+                todo.append("lgp")
+            rng.shuffle(todo)
+            for t in todo:
+                if t == "apply1":
+                    o.apply_stage(1); c.osp_apply_stage(1); check(f"it{it} apply1")
+                else:
+                    lgp(); lgp_done = True
+        split_gran = int(rng.choice([GRAN_LAYER, GRAN_ELEMENT]))
+        budget = int(rng.choice([0, wl.budget // 3, wl.budget, M]))
+        if rng.random() < 0.4:
+            o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(split_gran, budget)
+            c.osp_ics_window(gd, s_, split_gran, budget)
+            check(f"it{it} ics_window gran{split_gran} budget{budget}")
+        else:
+            agg(2)
+            if not lgp_done and rng.random() < 0.3:
+                lgp()
+            if rng.random() < 0.85:
+                o.apply_stage(2); c.osp_apply_stage(2); check(f"it{it} apply2")
+            r = rng.random()
+            if r < 0.6:
+                o.split(split_gran, budget); c.osp_split(split_gran, budget)
+                log.append(f"it{it} split gran{split_gran} budget{budget}")
+            elif r < 0.8:
+                gib = (random_layer_gib(rng, wl.n_tensors) if split_gran == GRAN_LAYER
+                       else random_bits(rng, arena, real))
+                o.set_gib(split_gran, gib); c.osp_set_gib(split_gran, gib)
+                log.append(f"it{it} set_gib gran{split_gran}")
+        compare_gib(job, o, f"it{it} gib")
+        assert c.osp_n_stage2() == o.n_stage2
+
+
+# --------------------------------------------------------------------------
 # each call on its own, with an injected GIB
 # --------------------------------------------------------------------------
 
