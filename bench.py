@@ -96,7 +96,7 @@ BRACKETED = {"six": ("agg1", "agg2"), "windows": ("rs_window",), "packed": ("spl
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=50)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="vgg16",
                     choices=["tiny", "resnet18", "resnet50", "resnet152", "vgg16", "bert_base"])

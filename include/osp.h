@@ -15,7 +15,9 @@
  *   every tensor are padding and are never written by any call.
  *   All pointers in osp_buffers and every `grads` argument are DEVICE
  *   pointers owned by the caller and only borrowed: the library never
- *   allocates or frees device memory.  All pointers in osp_config and the
+ *   allocates or frees device memory (osp_bind allocates a few bytes of
+ *   pinned host memory, freed by osp_destroy).  Every call of a context is
+ *   made with the device current that owns these buffers.  All pointers in osp_config and the
  *   gib/out arguments of osp_set_gib / osp_get_* are HOST pointers.
  *   `stream` is a hipStream_t passed as void* (NULL = the default stream).
  *   Kernels are enqueued on it and the call returns without waiting, except

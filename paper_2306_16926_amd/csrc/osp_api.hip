@@ -236,7 +236,8 @@ osp_status stage_counts(osp_ctx *ctx)
         // Poll the sequence number instead of waiting for the whole split to retire: the
         // lengths are published by the ranking kernel, so the next launch can be enqueued
         // while the table-filling kernel behind it still runs.  Bounded: after 2 s fall back
-        // to the event (which also surfaces a device error instead of spinning on it).
+        // to synchronizing the split's stream (which also surfaces a device error instead of
+        // spinning on it).
         const volatile unsigned *seq = &ctx->pinned_counts->seq;
         const auto t0 = std::chrono::steady_clock::now();
         unsigned spins = 0;
