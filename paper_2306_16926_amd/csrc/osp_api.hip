@@ -955,6 +955,9 @@ static void launch_window_layer(osp_ctx *ctx, const WindowLayerArgs &a, unsigned
     }
 }
 
+// Up to this many spans the ranking workgroup fills the stage tables itself (one launch less).
+constexpr int kRankFillMaxSpans = 16384;
+
 // Largest N for which the element-granular RS window keeps all gradients of a group in registers.
 constexpr int kRsElementMaxWorkers = 16;
 // Layer-granular windows run fused up to this many gradient elements (N x parameters): measured
@@ -1345,15 +1348,34 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
         k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
             ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
-        k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
-                                              ctx->d_big(), (int)ctx->big_layers.size(),
-                                              ctx->d_imp(), ctx->d_numel(),
-                                              ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
-                                              ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
-                                              ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
-        osp_status ls = enqueue_stage_lists(ctx, s);
-        if (ls != OSP_OK)
-            return ls;
+        const int ns = (int)ctx->spans.size();
+        if (ctx->n_tensors <= kRankTile) {
+            // one workgroup ranks in LDS and, unless the tables are long, fills them as well
+            const bool fill = ns <= kRankFillMaxSpans;
+            k_layer_rank_lds<kRankBlock><<<1, kRankBlock, 0, s>>>(
+                ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(), ctx->d_big(), (int)ctx->big_layers.size(),
+                ctx->d_imp(), ctx->d_numel(), ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
+                ctx->d_order(), ctx->d_lbase(), ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq,
+                fill ? ns : 0, ctx->d_spans(), ctx->d_slayer(), ctx->d_list(1), ctx->d_list(2));
+            if (fill) {
+                ctx->counts_stream = s;
+                ctx->counts_pending = true;
+            } else {
+                osp_status ls = enqueue_stage_lists(ctx, s);
+                if (ls != OSP_OK)
+                    return ls;
+            }
+        } else {
+            k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
+                                                  ctx->d_big(), (int)ctx->big_layers.size(),
+                                                  ctx->d_imp(), ctx->d_numel(),
+                                                  ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
+                                                  ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
+                                                  ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
+            osp_status ls = enqueue_stage_lists(ctx, s);
+            if (ls != OSP_OK)
+                return ls;
+        }
         ctx->have_layer_importance = true;
     } else {
         const long long nv = ctx->n_vec;
