@@ -1,0 +1,42 @@
+"""Host-side checks of bench.py: the byte counts it credits and its refusal of more than one GPU."""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+sys.path.insert(0, ROOT)
+import bench  # noqa: E402
+
+SIX = ("agg1", "apply1", "lgp", "agg2", "apply2", "split")
+
+
+@pytest.mark.parametrize("N,M,E2", [(16, 138_357_544, 35_597_096), (8, 60_192_808, 41_957_416), (4, 100_000, 0)])
+def test_layer_step_bytes_are_the_stated_formula(N, M, E2):
+    b = bench.step_bytes(N, M, E2, element=False)
+    assert sum(b[n] for n in SIX) == 4 * M * (2 * N + 5) + 12 * N * E2
+    assert b["rs_window"] + b["ics_window"] == sum(b[n] for n in SIX)
+    assert b["split_gradients"] == 8 * N * M
+
+
+def test_element_step_bytes_add_keys_and_selection_floor():
+    N, M, E2 = 16, 138_357_544, 69_178_772
+    layer = bench.step_bytes(N, M, E2, element=False)
+    elem = bench.step_bytes(N, M, E2, element=True)
+    extra = sum(elem[n] - layer[n] for n in SIX)
+    assert extra == 4 * M + (4 * M + M // 8)            # key write per element, then one key read + bitmap
+
+
+def test_bf16_gradients_halve_only_the_gradient_reads():
+    N, M, E2 = 8, 1000, 400
+    f32 = bench.step_bytes(N, M, E2, element=False, gb=4)
+    b16 = bench.step_bytes(N, M, E2, element=False, gb=2)
+    assert sum(f32[n] - b16[n] for n in SIX) == 2 * N * M + 2 * N * E2
+
+
+def test_more_than_one_gpu_is_refused_with_a_message():
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
