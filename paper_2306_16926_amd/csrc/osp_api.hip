@@ -956,7 +956,7 @@ static void launch_window_layer(osp_ctx *ctx, const WindowLayerArgs &a, unsigned
 }
 
 // Up to this many spans the ranking workgroup fills the stage tables itself (one launch less).
-constexpr int kRankFillMaxSpans = 16384;
+constexpr int kRankFillMaxSpans = 4096;
 
 // Largest N for which the element-granular RS window keeps all gradients of a group in registers.
 constexpr int kRsElementMaxWorkers = 16;
