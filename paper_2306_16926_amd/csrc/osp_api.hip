@@ -1380,7 +1380,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     } else {
         const long long nv = ctx->n_vec;
         long long want = (nv + kSplitBlock - 1) / kSplitBlock;
-        const unsigned hgrid = (unsigned)(want < 2048 ? (want < 1 ? 1 : want) : 2048);
+        const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
         k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
                                          (long long)3 * kRadixBins * 2, 0u);
         k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));

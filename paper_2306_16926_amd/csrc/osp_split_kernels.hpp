@@ -485,14 +485,40 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
     const unsigned prefix = PASS == 0 ? 0u : st->prefix;
     const int hi = shift + radix_bits(PASS);          // bits above this pass's digit
     const u4 *kv = reinterpret_cast<const u4 *>(key);
-    for (long long v = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v < n_vec;
-         v += (long long)gridDim.x * kSplitBlock) {
-        const u4 k = kv[v];
+    // four 16-byte loads in flight per thread; keys of one group that fall into one bin
+    // (the rule in the first pass, whose digit is mostly exponent) cost one LDS atomic
+    constexpr int kUnroll = 4;
+    const long long stride = (long long)gridDim.x * kSplitBlock;
+    for (long long v0 = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v0 < n_vec;
+         v0 += kUnroll * stride) {
+        u4 k[kUnroll];
 #pragma unroll
-        for (int j = 0; j < kVec; ++j) {
-            const unsigned x = k[j];
-            if (PASS == 0 || (x >> hi) == prefix)
-                atomicAdd(&h[(x >> shift) & mask], 1u);
+        for (int u = 0; u < kUnroll; ++u) {
+            const long long v = v0 + u * stride;
+            if (v < n_vec)
+                k[u] = __builtin_nontemporal_load(kv + v);
+        }
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) {
+            if (v0 + u * stride >= n_vec)
+                continue;
+            unsigned bin[kVec];
+            bool in[kVec];
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const unsigned x = k[u][j];
+                in[j] = PASS == 0 || (x >> hi) == prefix;
+                bin[j] = (x >> shift) & mask;
+            }
+            if (in[0] && in[1] && in[2] && in[3] && bin[0] == bin[1] && bin[0] == bin[2] &&
+                bin[0] == bin[3]) {
+                atomicAdd(&h[bin[0]], 4u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    if (in[j])
+                        atomicAdd(&h[bin[j]], 1u);
+            }
         }
     }
     __syncthreads();
