@@ -715,6 +715,59 @@ def test_random_call_sequences(seed):
 
 
 # --------------------------------------------------------------------------
+# the caller's stream schedule: RS on one stream, ICS on another, ordered by events
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_two_streams_with_events(gran):
+    """What OSP overlaps is the ICS window with the next iteration's compute: the RS calls go to
+    one stream, the ICS calls to a second one behind an event, while the first stream carries
+    other work (here a copy standing in for the forward/backward pass); the next RS waits for
+    the ICS through another event.  Default priorities, no host synchronization in the loop."""
+    import torch
+    say("two streams", gran)
+    wl = W.get("resnet18")
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=(gran == GRAN_ELEMENT))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    rs, ics = torch.cuda.Stream(), torch.cuda.Stream()
+    busy_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    busy_dst = torch.empty_like(busy_src)
+    grads = [wl.make_grads(0, step, threads=8) for step in range(3)]
+    dev = [job.upload_grads(g) for g in grads]
+    torch.cuda.synchronize()
+    ics_done = torch.cuda.Event()
+    ics_done.record(ics)
+    for step in range(3):
+        gd = dev[step]; s_ = gd.shape[1]
+        rs.wait_event(ics_done)                         # stage 2 of the previous iteration is complete
+        if step % 2 == 0:
+            c.osp_rs_window(gd, s_, stream=rs)
+        else:
+            c.osp_ps_aggregate_update(1, gd, s_, stream=rs)
+            c.osp_apply_stage(1, stream=rs)
+            c.osp_lgp_correct(gd, s_, stream=rs)
+        rs_done = torch.cuda.Event(); rs_done.record(rs)
+        with torch.cuda.stream(rs):                     # "compute" of the next iteration
+            busy_dst.copy_(busy_src, non_blocking=True)
+        ics.wait_event(rs_done)
+        if step % 2 == 0:
+            c.osp_ics_window(gd, s_, gran, wl.budget, stream=ics)
+        else:
+            c.osp_ps_aggregate_update(2, gd, s_, stream=ics)
+            c.osp_apply_stage(2, stream=ics)
+            c.osp_split(gran, wl.budget, stream=ics)
+        ics_done = torch.cuda.Event(); ics_done.record(ics)
+        o.sync_step(grads[step], gran, wl.budget)
+    torch.cuda.synchronize()
+    compare_state(job, o, "two streams")
+    compare_gib(job, o, "two streams")
+    assert bool((busy_dst[:1024] == 1.0).all())
+
+
+# --------------------------------------------------------------------------
 # each call on its own, with an injected GIB
 # --------------------------------------------------------------------------
 
