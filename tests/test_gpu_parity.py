@@ -1,103 +1,17 @@
-"""Parity of the HIP library against the CPU oracle, through the C ABI.
-
-Bar: the stage-1/stage-2 partition bit-exact; fp32 parameters within a relative
-error of 1e-5 (they are in fact bit-identical, which is asserted too, because
-both sides evaluate the same sequence of separately rounded fp32 operations);
-fp64 layer importances within 1e-12 relative (different summation order)."""
-import sys
-
+"""Parity of the HIP library against the CPU oracle, through the C ABI: chained sync steps,
+full sizes in the benchmark's launch configuration, each call on its own, the splits, the
+order-of-calls state machine."""
 import numpy as np
 import pytest
 
 from oracle.osp_oracle import GRAN_ELEMENT, GRAN_LAYER, OracleOSP
 from paper_2306_16926_amd import workloads as W
 from tests import brute
+from tests.gpu_common import (F, close_enough, compare_gib, compare_state, device_job, run_steps,
+                              say)
 from tests.helpers import make_oracle, random_bits, random_layer_gib
 
 pytestmark = pytest.mark.gpu
-F = np.float32
-REL_TOL = 1e-5           # tolerance of record for fp32 parameters
-
-
-def say(*a):
-    print("[case]", *a, flush=True)
-    sys.stdout.flush()
-
-
-def device_job(wl, seed=0, align=None, weights=None, element_keys=False, chunk_elems=0,
-               lr=None, mu=None, param_stride=None, pad_fill=None, params=None,
-               declare_in_sync=True):
-    from paper_2306_16926_amd.device import DeviceJob
-    p = wl.make_params(seed, align) if params is None else params
-    return DeviceJob(wl.numel, wl.offsets(align), wl.arena_elems(align), wl.n_workers,
-                     wl.lr if lr is None else lr, wl.momentum if mu is None else mu, p,
-                     worker_weight=weights, element_keys=element_keys, chunk_elems=chunk_elems,
-                     param_stride=param_stride, pad_fill=pad_fill,
-                     declare_in_sync=declare_in_sync)
-
-
-def close_enough(got, want, what):
-    """rel 1e-5 (the stated bar), then bit equality (what the design promises)."""
-    got = np.asarray(got); want = np.asarray(want)
-    assert got.shape == want.shape, what
-    both_nan = np.isnan(got) & np.isnan(want)
-    fin = ~both_nan
-    err = np.abs(got[fin].astype(np.float64) - want[fin].astype(np.float64))
-    bound = REL_TOL * np.abs(want[fin].astype(np.float64))
-    with np.errstate(invalid="ignore"):
-        bad = ~((err <= bound) | (got[fin] == want[fin]))
-    assert not bad.any(), f"{what}: {int(bad.sum())} elements outside rel {REL_TOL}"
-    assert np.array_equal(got, want, equal_nan=True), f"{what}: not bit-identical"
-
-
-def compare_state(job, o, what):
-    P, V, Pw = job.download()
-    close_enough(P, o.P, what + " P")
-    close_enough(V, o.V, what + " V")
-    close_enough(Pw[:, :o.arena], o.Pw[:, :o.arena], what + " Pw")
-
-
-def compare_gib(job, o, what):
-    layer, bits, n2 = job.ctx.osp_get_gib()
-    if o.granularity == GRAN_LAYER:
-        assert np.array_equal(layer, o.gib_layer), what + " layer GIB"
-    else:
-        assert np.array_equal(bits, o.gib_bits), what + " element bitmap"
-    assert n2 == o.n_stage2, what + " n_stage2"
-
-
-def run_steps(wl, gran, steps, seed=0, align=None, weights=None, chunk_elems=0, budget=None,
-              threads=4, windows=False):
-    budget = wl.budget if budget is None else budget
-    o = make_oracle(wl, seed, align, weights)
-    job = device_job(wl, seed, align, weights, element_keys=(gran == GRAN_ELEMENT),
-                     chunk_elems=chunk_elems)
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); job.ctx.osp_set_gib(GRAN_LAYER, all1)
-    sizes = []
-    for step in range(steps):
-        g = wl.make_grads(seed, step, align, threads=threads)
-        gd = job.upload_grads(g)
-        o.sync_step(g, gran, budget)
-        if windows:
-            job.sync_step_windows(gd, gran, budget)
-        else:
-            job.sync_step(gd, gran, budget)
-        compare_state(job, o, f"{wl.name} step {step}")
-        compare_gib(job, o, f"{wl.name} step {step}")
-        if gran == GRAN_LAYER:
-            imp = job.ctx.osp_get_importance()
-            rel = np.abs(imp - o.importance) / np.maximum(np.abs(o.importance), 1e-300)
-            assert rel.max() <= 1e-12, f"layer importance rel err {rel.max()}"
-        else:
-            real = brute.real_mask(wl.numel, wl.offsets(align), wl.arena_elems(align))
-            keys = job.ctx.osp_get_keys()
-            assert np.array_equal(keys[real], o.keys()[real]), "element keys"
-            assert (keys[~real] == 0xFFFFFFFF).all()
-        sizes.append(o.n_stage2)
-        del gd
-    return sizes
-
 
 # --------------------------------------------------------------------------
 # whole sync steps, chained
@@ -283,488 +197,6 @@ def test_full_size_resnet152_element_properties():
     assert np.array_equal(c.osp_get_keys()[real], o.keys()[real])
     _, bits, n2 = c.osp_get_gib()
     assert n2 == k
-
-
-# --------------------------------------------------------------------------
-# the two windows (one call each) against the oracle's six calls
-# --------------------------------------------------------------------------
-
-@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-@pytest.mark.parametrize("weighted", [False, True])
-def test_windows_tiny_three_chained_steps(gran, weighted):
-    say("windows tiny", gran, weighted)
-    wl = W.get("tiny")
-    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
-    sizes = run_steps(wl, gran, 3, weights=wts, windows=True)
-    assert sizes[0] > 0
-    run_steps(wl, gran, 2, align=64, chunk_elems=1024, windows=True)
-
-
-@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 8, 9, 16, 17])
-def test_windows_worker_counts(n_workers):
-    """Fused kernels up to 8 (layer) / 16 (element, RS) workers, single-stage kernels above."""
-    say("windows workers", n_workers)
-    wl = W.custom([5000, 3, 1029, 64, 2048, 1], n_workers, 0.4, align=4, config_id=140 + n_workers)
-    run_steps(wl, GRAN_LAYER, 3, windows=True)
-    run_steps(wl, GRAN_ELEMENT, 3, windows=True)
-    wts = np.random.default_rng(n_workers).random(n_workers).astype(F)
-    wts /= wts.sum()
-    run_steps(wl, GRAN_ELEMENT, 2, weights=wts, windows=True)
-    run_steps(wl, GRAN_LAYER, 2, weights=wts, windows=True)
-
-
-@pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT)])
-def test_windows_cnn_shaped(name, gran):
-    say("windows", name, gran)
-    sizes = run_steps(W.get(name), gran, 3, threads=8, windows=True)
-    assert sizes[-1] > 0
-
-
-@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-@pytest.mark.parametrize("in_sync", [True, False])
-def test_windows_mixed_with_single_calls(gran, in_sync):
-    """Windows and single calls in one run, starting from replicas that are or are not declared
-    equal to the PS, over iterations that do and do not restore consistency; stage 2 from
-    another gradient buffer on some steps."""
-    say("windows mixed", gran, in_sync)
-    wl = W.custom([5000, 3, 1029, 64, 2048, 70000, 2], 6, 0.5, align=4, config_id=170)
-    o = make_oracle(wl)
-    job = device_job(wl, element_keys=True, declare_in_sync=in_sync)
-    c = job.ctx
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-    plans = ["ww", "ws", "sw", "ww", "w-", "ww", "s-", "ww", "wW", "ww"]
-    for step, plan in enumerate(plans):
-        g = wl.make_grads(0, step); gd = job.upload_grads(g); s_ = g.shape[1]
-        g2, gd2 = g, gd
-        if plan[1] == "W":                      # ICS window from a different gradient buffer
-            g2 = wl.make_grads(3, step); gd2 = job.upload_grads(g2)
-        o.ps_aggregate_update(1, g)
-        if plan[0] == "w":
-            o.apply_stage(1); o.lgp_correct(g)
-            c.osp_rs_window(gd, s_)
-        else:                                   # single calls, stage 1 never installed
-            o.lgp_correct(g)
-            c.osp_ps_aggregate_update(1, gd, s_); c.osp_lgp_correct(gd, s_)
-        compare_state(job, o, f"step {step} {plan} RS")
-        o.ps_aggregate_update(2, g2)
-        if plan[1] in "wW":
-            o.apply_stage(2); o.split(gran, wl.budget)
-            c.osp_ics_window(gd2, s_, gran, wl.budget)
-        elif plan[1] == "s":
-            o.apply_stage(2); o.split(gran, wl.budget)
-            c.osp_ps_aggregate_update(2, gd2, s_); c.osp_apply_stage(2); c.osp_split(gran, wl.budget)
-        else:                                   # stage 2 aggregated but not installed, old GIB stays
-            c.osp_ps_aggregate_update(2, gd2, s_)
-        compare_state(job, o, f"step {step} {plan} ICS")
-        compare_gib(job, o, f"step {step} {plan}")
-
-
-def test_windows_reject_bad_arguments_before_launching():
-    say("windows errors")
-    from paper_2306_16926_amd.binding import OspError
-    wl = W.get("tiny")
-    o = make_oracle(wl)
-    job = device_job(wl)                        # no element keys
-    c = job.ctx
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s_ = g.shape[1]
-    with pytest.raises(OspError):
-        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)        # no stage 1 yet
-    c.osp_rs_window(gd, s_)
-    o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
-    with pytest.raises(OspError):
-        c.osp_rs_window(gd, s_)                                # stage 2 pending
-    with pytest.raises(OspError):
-        c.osp_ics_window(gd, s_, GRAN_ELEMENT, wl.budget)      # needs element keys
-    with pytest.raises(OspError):
-        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.n_params + 1)
-    compare_state(job, o, "after rejected calls")              # nothing was touched
-    c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)
-    o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(GRAN_LAYER, wl.budget)
-    compare_state(job, o, "after ICS")
-    compare_gib(job, o, "after ICS")
-
-
-# --------------------------------------------------------------------------
-# gradient splitter: dense G^i / G^u, and the PS fed by them
-# --------------------------------------------------------------------------
-
-def run_splitter_steps(wl, gran, steps, weights=None, chunk_elems=0, align=None, injected=False, seed=0):
-    """Each iteration: split every worker's gradients on both sides, compare the dense parts
-    bit for bit, then run the iteration with the PS fed by the dense parts on the GPU and by
-    the oracle's own dense parts on the CPU."""
-    import torch
-    o = make_oracle(wl, seed, align, weights)
-    job = device_job(wl, seed, align, weights, element_keys=True, chunk_elems=chunk_elems)
-    c = job.ctx
-    arena = wl.arena_elems(align)
-    real = brute.real_mask(wl.numel, wl.offsets(align), arena)
-    rng = np.random.default_rng(17)
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-    for step in range(steps):
-        if injected:
-            gib = random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER else random_bits(rng, arena, real)
-            o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
-        g = wl.make_grads(seed, step, align)
-        g[:, :arena][:, ~real] = 5.0                 # padding must not reach the dense parts
-        gd = job.upload_grads(g); s_ = g.shape[1]
-        og_i, og_u = o.split_gradients(g)
-        e1, e2 = og_i.shape[1], og_u.shape[1]
-        assert c.osp_n_stage2() == e2
-        st_i, st_u = e1 + 3, e2 + 1                  # strides beyond the parts, sentinel behind
-        dg_i = torch.full((wl.n_workers, st_i), -7.0, dtype=torch.float32, device="cuda")
-        dg_u = torch.full((wl.n_workers, st_u), -7.0, dtype=torch.float32, device="cuda")
-        c.osp_split_gradients(gd, s_, dg_i, st_i, dg_u, st_u)
-        hi, hu = dg_i.cpu().numpy(), dg_u.cpu().numpy()
-        assert np.array_equal(hi[:, :e1], og_i, equal_nan=True), f"G^i step {step}"
-        assert np.array_equal(hu[:, :e2], og_u, equal_nan=True), f"G^u step {step}"
-        assert (hi[:, e1:] == -7.0).all() and (hu[:, e2:] == -7.0).all()
-        # one part only
-        only_u = torch.full_like(dg_u, -7.0)
-        c.osp_split_gradients(gd, s_, None, 0, only_u, st_u)
-        assert torch.equal(only_u, dg_u)
-        o.ps_aggregate_update_packed(1, og_i); c.osp_ps_aggregate_update_packed(1, dg_i, st_i)
-        compare_state(job, o, f"packed agg1 step {step}")
-        o.apply_stage(1); c.osp_apply_stage(1)
-        o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
-        compare_state(job, o, f"lgp step {step}")
-        if e2 > 0:
-            o.ps_aggregate_update_packed(2, og_u)
-        else:
-            o.ps_aggregate_update(2, g)              # empty stage: nothing to read
-        c.osp_ps_aggregate_update_packed(2, dg_u, st_u)
-        compare_state(job, o, f"packed agg2 step {step}")
-        o.apply_stage(2); c.osp_apply_stage(2)
-        compare_state(job, o, f"apply2 step {step}")
-        keys = c.osp_get_keys()
-        assert np.array_equal(keys[real], o.keys()[real]), "element keys"
-        split_gran = gran if step % 2 == 0 else (GRAN_LAYER if gran == GRAN_ELEMENT else GRAN_ELEMENT)
-        o.split(split_gran, wl.budget); c.osp_split(split_gran, wl.budget)
-        compare_gib(job, o, f"split step {step}")
-        if split_gran == GRAN_LAYER:
-            assert np.allclose(c.osp_get_importance(), o.importance, rtol=1e-12, atol=0)
-
-
-@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-@pytest.mark.parametrize("weighted", [False, True])
-def test_splitter_tiny(gran, weighted):
-    say("splitter tiny", gran, weighted)
-    wl = W.get("tiny")
-    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
-    run_splitter_steps(wl, gran, 4, weights=wts)
-    run_splitter_steps(wl, gran, 3, weights=wts, injected=True)
-
-
-@pytest.mark.parametrize("chunk,align", [(256, 4), (1024, 64), (16384, 4), (131072, 4)])
-def test_splitter_chunk_sizes(chunk, align):
-    """Chunks that take several passes of a wavefront (running position inside the chunk),
-    up to chunks larger than a 16-bit count."""
-    say("splitter chunk", chunk, align)
-    wl = W.custom([70001, 3, 1029, 64, 2048, 200000, 1], 3, 0.5, align=align, config_id=180)
-    run_splitter_steps(wl, GRAN_ELEMENT, 2, chunk_elems=chunk, align=align, injected=True)
-    run_splitter_steps(wl, GRAN_LAYER, 2, chunk_elems=chunk, align=align, injected=True)
-
-
-def test_splitter_degenerate_gibs_and_errors():
-    say("splitter degenerate")
-    import torch
-    from paper_2306_16926_amd.binding import OspError
-    wl = W.custom([5000, 3, 1029], 2, 0.5, align=4, config_id=181)
-    o = make_oracle(wl)
-    job = device_job(wl, element_keys=True)
-    c = job.ctx
-    arena = wl.arena_elems()
-    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s_ = g.shape[1]
-    M = wl.n_params
-    buf_i = torch.zeros((2, M), dtype=torch.float32, device="cuda")
-    buf_u = torch.zeros((2, M), dtype=torch.float32, device="cuda")
-    with pytest.raises(OspError):
-        c.osp_split_gradients(gd, s_, buf_i, M, buf_u, M)       # no GIB yet
-    for gib, gran in ((np.ones(3, np.uint8), GRAN_LAYER), (np.zeros(3, np.uint8), GRAN_LAYER),
-                      (np.zeros((arena + 31) // 32, np.uint32), GRAN_ELEMENT)):
-        o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
-        og_i, og_u = o.split_gradients(g)
-        buf_i.fill_(-1.0); buf_u.fill_(-1.0)
-        c.osp_split_gradients(gd, s_, buf_i, M, buf_u, M)
-        e1, e2 = og_i.shape[1], og_u.shape[1]
-        assert e1 == 0 or e2 == 0
-        assert np.array_equal(buf_i.cpu().numpy()[:, :e1], og_i)
-        assert np.array_equal(buf_u.cpu().numpy()[:, :e2], og_u)
-        assert (buf_i.cpu().numpy()[:, e1:] == -1.0).all() and (buf_u.cpu().numpy()[:, e2:] == -1.0).all()
-        with pytest.raises(OspError):
-            c.osp_split_gradients(gd, s_, None, 0, None, 0)
-        if e1 > 0:
-            with pytest.raises(OspError):
-                c.osp_split_gradients(gd, s_, buf_i, e1 - 1, None, 0)
-        with pytest.raises(OspError):
-            c.osp_ps_aggregate_update_packed(2, buf_u, M)       # stage 1 first
-        with pytest.raises(OspError):
-            c.osp_ps_aggregate_update_packed(0, buf_u, M)
-        # a full iteration through the dense parts, one of them empty
-        o.ps_aggregate_update(1, g); c.osp_ps_aggregate_update_packed(1, buf_i, M)
-        o.ps_aggregate_update(2, g); c.osp_ps_aggregate_update_packed(2, buf_u, M)
-        o.apply_stage(0); c.osp_apply_stage(0)
-        compare_state(job, o, "degenerate GIB")
-
-
-def test_splitter_cnn_shaped():
-    say("splitter resnet18")
-    run_splitter_steps(W.get("resnet18"), GRAN_ELEMENT, 2)
-    run_splitter_steps(W.get("resnet18"), GRAN_LAYER, 2)
-
-
-# --------------------------------------------------------------------------
-# bfloat16 gradient arenas: the oracle is fed the widened values (exact), so
-# the bar stays bit equality
-# --------------------------------------------------------------------------
-
-def run_steps_bf16(wl, gran, steps, weights=None, chunk_elems=0, align=None, seed=0, threads=4):
-    o = make_oracle(wl, seed, align, weights)
-    job = device_job(wl, seed, align, weights, element_keys=(gran == GRAN_ELEMENT),
-                     chunk_elems=chunk_elems)
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); job.ctx.osp_set_gib(GRAN_LAYER, all1)
-    sizes = []
-    for step in range(steps):
-        h = W.to_bf16(wl.make_grads(seed, step, align, threads=threads))
-        g = W.from_bf16(h)
-        gd = job.upload_grads_bf16(h)
-        o.sync_step(g, gran, wl.budget)
-        job.sync_step_bf16(gd, gran, wl.budget)
-        compare_state(job, o, f"bf16 {wl.name} step {step}")
-        compare_gib(job, o, f"bf16 {wl.name} step {step}")
-        sizes.append(o.n_stage2)
-    return sizes
-
-
-@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-@pytest.mark.parametrize("weighted", [False, True])
-def test_bf16_gradients_tiny(gran, weighted):
-    say("bf16 tiny", gran, weighted)
-    wl = W.get("tiny")
-    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
-    sizes = run_steps_bf16(wl, gran, 3, weights=wts)
-    assert sizes[0] > 0
-    run_steps_bf16(wl, gran, 2, align=64, chunk_elems=1024)
-
-
-@pytest.mark.parametrize("n_workers", [1, 3, 8, 9, 16, 17])
-def test_bf16_gradients_worker_counts(n_workers):
-    say("bf16 workers", n_workers)
-    wl = W.custom([5000, 3, 1029, 64, 2048, 1], n_workers, 0.4, align=4, config_id=240 + n_workers)
-    run_steps_bf16(wl, GRAN_LAYER, 2)
-    run_steps_bf16(wl, GRAN_ELEMENT, 2)
-
-
-def test_bf16_gradients_lgp_paths_nonfinite_and_errors():
-    """LGP per replica (replicas not declared in sync) and from the PS values; non-finite
-    gradients; misaligned arenas are refused."""
-    say("bf16 lgp paths")
-    from paper_2306_16926_amd.binding import OspError
-    wl = W.custom([5000, 3, 1029, 64, 70000], 5, 0.5, align=4, config_id=250)
-    for in_sync in (True, False):
-        o = make_oracle(wl)
-        job = device_job(wl, element_keys=True, declare_in_sync=in_sync)
-        c = job.ctx
-        all1 = np.ones(wl.n_tensors, np.uint8)
-        o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-        for step in range(3):
-            gf = wl.make_grads(0, step)
-            if step == 2:
-                gf[1, 7] = np.inf; gf[2, 5001] = np.nan; gf[0, 5010] = -np.inf
-            h = W.to_bf16(gf); g = W.from_bf16(h); gd = job.upload_grads_bf16(h); s_ = g.shape[1]
-            gran = GRAN_ELEMENT if step else GRAN_LAYER
-            with np.errstate(all="ignore"):
-                o.ps_aggregate_update(1, g); c.osp_ps_aggregate_update_bf16(1, gd, s_)
-                o.lgp_correct(g); c.osp_lgp_correct_bf16(gd, s_)       # before the install
-                compare_state(job, o, f"lgp in_sync={in_sync} step {step}")
-                o.apply_stage(1); c.osp_apply_stage(1)
-                o.ps_aggregate_update(2, g); c.osp_ps_aggregate_update_bf16(2, gd, s_)
-                o.apply_stage(2); c.osp_apply_stage(2)
-                compare_state(job, o, f"in_sync={in_sync} step {step}")
-                o.split(gran, wl.budget); c.osp_split(gran, wl.budget)
-            compare_gib(job, o, f"in_sync={in_sync} step {step}")
-        with pytest.raises(OspError):
-            c.osp_ps_aggregate_update_bf16(1, gd.data_ptr() + 2, s_)   # not 8-byte aligned
-
-
-def test_bf16_gradients_cnn_shaped():
-    say("bf16 resnet18")
-    run_steps_bf16(W.get("resnet18"), GRAN_LAYER, 2, threads=8)
-    run_steps_bf16(W.get("resnet18"), GRAN_ELEMENT, 2, threads=8)
-
-
-# --------------------------------------------------------------------------
-# random legal call sequences over every entry point that touches the state
-# --------------------------------------------------------------------------
-
-@pytest.mark.parametrize("seed", list(range(16)))
-def test_random_call_sequences(seed):
-    """Iterations assembled at random from the single-stage calls (fp32, bfloat16 and dense
-    gradient inputs), the two windows, optional installs and LGP in any legal order, splits of
-    either granularity or an injected GIB: the state is compared with the oracle after every
-    call.  Gradients are bfloat16-representable so that every input form carries the same values."""
-    import torch
-    say("random sequences", seed)
-    rng = np.random.default_rng(1000 + seed)
-    n_workers = int(rng.choice([2, 5, 8, 11]))
-    wl = W.custom([5000, 3, 1029, 64, 2048, 30000, 2], n_workers, 0.5, align=4, config_id=300 + seed)
-    arena = wl.arena_elems()
-    real = brute.real_mask(wl.numel, wl.offsets(), arena)
-    wts = None
-    if seed % 2:
-        wts = rng.random(n_workers).astype(F); wts /= wts.sum()
-    o = make_oracle(wl, weights=wts)
-    job = device_job(wl, weights=wts, element_keys=True, declare_in_sync=bool(seed % 3))
-    c = job.ctx
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-    M = wl.n_params
-    dense_i = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
-    dense_u = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
-    log = []
-
-    def check(what):
-        log.append(what)
-        try:
-            compare_state(job, o, what)
-        except AssertionError:
-            print("[case] calls so far:", " | ".join(log), flush=True)
-            raise
-
-    for it in range(10):
-        h = W.to_bf16(wl.make_grads(seed, it)); g = W.from_bf16(h)
-        gd = job.upload_grads(g); hd = job.upload_grads_bf16(h); s_ = g.shape[1]
-        packed = None
-
-        def get_packed():
-            og_i, og_u = o.split_gradients(g)
-            c.osp_split_gradients(gd, s_, dense_i, M + 4, dense_u, M + 4)
-            return og_i, og_u
-
-        def agg(stage):
-            nonlocal packed
-            form = rng.choice(["f32", "bf16", "packed"])
-            if form == "packed":
-                if packed is None:
-                    packed = get_packed()
-                part = packed[stage - 1]
-                if part.shape[1]:
-                    o.ps_aggregate_update_packed(stage, part)
-                else:
-                    o.ps_aggregate_update(stage, g)
-                c.osp_ps_aggregate_update_packed(stage, dense_i if stage == 1 else dense_u, M + 4)
-            elif form == "bf16":
-                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update_bf16(stage, hd, s_)
-            else:
-                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update(stage, gd, s_)
-            check(f"it{it} agg{stage}:{form}")
-
-        def lgp():
-            if rng.random() < 0.5:
-                o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
-            else:
-                o.lgp_correct(g); c.osp_lgp_correct_bf16(hd, s_)
-            check(f"it{it} lgp")
-
-        lgp_done = False
-        if rng.random() < 0.4:
-            o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
-            c.osp_rs_window(gd, s_)
-            lgp_done = True
-            check(f"it{it} rs_window")
-        else:
-            agg(1)
-            todo = []
-            if rng.random() < 0.8:
-                todo.append("apply1")
-            if rng.random() < 0.7:
-                todo.append("lgp")
-            rng.shuffle(todo)
-            for t in todo:
-                if t == "apply1":
-                    o.apply_stage(1); c.osp_apply_stage(1); check(f"it{it} apply1")
-                else:
-                    lgp(); lgp_done = True
-        split_gran = int(rng.choice([GRAN_LAYER, GRAN_ELEMENT]))
-        budget = int(rng.choice([0, wl.budget // 3, wl.budget, M]))
-        if rng.random() < 0.4:
-            o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(split_gran, budget)
-            c.osp_ics_window(gd, s_, split_gran, budget)
-            check(f"it{it} ics_window gran{split_gran} budget{budget}")
-        else:
-            agg(2)
-            if not lgp_done and rng.random() < 0.3:
-                lgp()
-            if rng.random() < 0.85:
-                o.apply_stage(2); c.osp_apply_stage(2); check(f"it{it} apply2")
-            r = rng.random()
-            if r < 0.6:
-                o.split(split_gran, budget); c.osp_split(split_gran, budget)
-                log.append(f"it{it} split gran{split_gran} budget{budget}")
-            elif r < 0.8:
-                gib = (random_layer_gib(rng, wl.n_tensors) if split_gran == GRAN_LAYER
-                       else random_bits(rng, arena, real))
-                o.set_gib(split_gran, gib); c.osp_set_gib(split_gran, gib)
-                log.append(f"it{it} set_gib gran{split_gran}")
-        compare_gib(job, o, f"it{it} gib")
-        assert c.osp_n_stage2() == o.n_stage2
-
-
-# --------------------------------------------------------------------------
-# the caller's stream schedule: RS on one stream, ICS on another, ordered by events
-# --------------------------------------------------------------------------
-
-@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-def test_two_streams_with_events(gran):
-    """What OSP overlaps is the ICS window with the next iteration's compute: the RS calls go to
-    one stream, the ICS calls to a second one behind an event, while the first stream carries
-    other work (here a copy standing in for the forward/backward pass); the next RS waits for
-    the ICS through another event.  Default priorities, no host synchronization in the loop."""
-    import torch
-    say("two streams", gran)
-    wl = W.get("resnet18")
-    o = make_oracle(wl)
-    job = device_job(wl, element_keys=(gran == GRAN_ELEMENT))
-    c = job.ctx
-    all1 = np.ones(wl.n_tensors, np.uint8)
-    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
-    rs, ics = torch.cuda.Stream(), torch.cuda.Stream()
-    busy_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
-    busy_dst = torch.empty_like(busy_src)
-    grads = [wl.make_grads(0, step, threads=8) for step in range(3)]
-    dev = [job.upload_grads(g) for g in grads]
-    torch.cuda.synchronize()
-    ics_done = torch.cuda.Event()
-    ics_done.record(ics)
-    for step in range(3):
-        gd = dev[step]; s_ = gd.shape[1]
-        rs.wait_event(ics_done)                         # stage 2 of the previous iteration is complete
-        if step % 2 == 0:
-            c.osp_rs_window(gd, s_, stream=rs)
-        else:
-            c.osp_ps_aggregate_update(1, gd, s_, stream=rs)
-            c.osp_apply_stage(1, stream=rs)
-            c.osp_lgp_correct(gd, s_, stream=rs)
-        rs_done = torch.cuda.Event(); rs_done.record(rs)
-        with torch.cuda.stream(rs):                     # "compute" of the next iteration
-            busy_dst.copy_(busy_src, non_blocking=True)
-        ics.wait_event(rs_done)
-        if step % 2 == 0:
-            c.osp_ics_window(gd, s_, gran, wl.budget, stream=ics)
-        else:
-            c.osp_ps_aggregate_update(2, gd, s_, stream=ics)
-            c.osp_apply_stage(2, stream=ics)
-            c.osp_split(gran, wl.budget, stream=ics)
-        ics_done = torch.cuda.Event(); ics_done.record(ics)
-        o.sync_step(grads[step], gran, wl.budget)
-    torch.cuda.synchronize()
-    compare_state(job, o, "two streams")
-    compare_gib(job, o, "two streams")
-    assert bool((busy_dst[:1024] == 1.0).all())
 
 
 # --------------------------------------------------------------------------

@@ -1,0 +1,139 @@
+"""The gradient splitter (dense G^i / G^u per worker) and the PS update fed by its output."""
+import numpy as np
+import pytest
+
+from oracle.osp_oracle import GRAN_ELEMENT, GRAN_LAYER
+from paper_2306_16926_amd import workloads as W
+from tests import brute
+from tests.gpu_common import F, compare_gib, compare_state, device_job, say
+from tests.helpers import make_oracle, random_bits, random_layer_gib
+
+pytestmark = pytest.mark.gpu
+
+# --------------------------------------------------------------------------
+# gradient splitter: dense G^i / G^u, and the PS fed by them
+# --------------------------------------------------------------------------
+
+def run_splitter_steps(wl, gran, steps, weights=None, chunk_elems=0, align=None, injected=False, seed=0):
+    """Each iteration: split every worker's gradients on both sides, compare the dense parts
+    bit for bit, then run the iteration with the PS fed by the dense parts on the GPU and by
+    the oracle's own dense parts on the CPU."""
+    import torch
+    o = make_oracle(wl, seed, align, weights)
+    job = device_job(wl, seed, align, weights, element_keys=True, chunk_elems=chunk_elems)
+    c = job.ctx
+    arena = wl.arena_elems(align)
+    real = brute.real_mask(wl.numel, wl.offsets(align), arena)
+    rng = np.random.default_rng(17)
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    for step in range(steps):
+        if injected:
+            gib = random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER else random_bits(rng, arena, real)
+            o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
+        g = wl.make_grads(seed, step, align)
+        g[:, :arena][:, ~real] = 5.0                 # padding must not reach the dense parts
+        gd = job.upload_grads(g); s_ = g.shape[1]
+        og_i, og_u = o.split_gradients(g)
+        e1, e2 = og_i.shape[1], og_u.shape[1]
+        assert c.osp_n_stage2() == e2
+        st_i, st_u = e1 + 3, e2 + 1                  # strides beyond the parts, sentinel behind
+        dg_i = torch.full((wl.n_workers, st_i), -7.0, dtype=torch.float32, device="cuda")
+        dg_u = torch.full((wl.n_workers, st_u), -7.0, dtype=torch.float32, device="cuda")
+        c.osp_split_gradients(gd, s_, dg_i, st_i, dg_u, st_u)
+        hi, hu = dg_i.cpu().numpy(), dg_u.cpu().numpy()
+        assert np.array_equal(hi[:, :e1], og_i, equal_nan=True), f"G^i step {step}"
+        assert np.array_equal(hu[:, :e2], og_u, equal_nan=True), f"G^u step {step}"
+        assert (hi[:, e1:] == -7.0).all() and (hu[:, e2:] == -7.0).all()
+        # one part only
+        only_u = torch.full_like(dg_u, -7.0)
+        c.osp_split_gradients(gd, s_, None, 0, only_u, st_u)
+        assert torch.equal(only_u, dg_u)
+        o.ps_aggregate_update_packed(1, og_i); c.osp_ps_aggregate_update_packed(1, dg_i, st_i)
+        compare_state(job, o, f"packed agg1 step {step}")
+        o.apply_stage(1); c.osp_apply_stage(1)
+        o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+        compare_state(job, o, f"lgp step {step}")
+        if e2 > 0:
+            o.ps_aggregate_update_packed(2, og_u)
+        else:
+            o.ps_aggregate_update(2, g)              # empty stage: nothing to read
+        c.osp_ps_aggregate_update_packed(2, dg_u, st_u)
+        compare_state(job, o, f"packed agg2 step {step}")
+        o.apply_stage(2); c.osp_apply_stage(2)
+        compare_state(job, o, f"apply2 step {step}")
+        keys = c.osp_get_keys()
+        assert np.array_equal(keys[real], o.keys()[real]), "element keys"
+        split_gran = gran if step % 2 == 0 else (GRAN_LAYER if gran == GRAN_ELEMENT else GRAN_ELEMENT)
+        o.split(split_gran, wl.budget); c.osp_split(split_gran, wl.budget)
+        compare_gib(job, o, f"split step {step}")
+        if split_gran == GRAN_LAYER:
+            assert np.allclose(c.osp_get_importance(), o.importance, rtol=1e-12, atol=0)
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_splitter_tiny(gran, weighted):
+    say("splitter tiny", gran, weighted)
+    wl = W.get("tiny")
+    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
+    run_splitter_steps(wl, gran, 4, weights=wts)
+    run_splitter_steps(wl, gran, 3, weights=wts, injected=True)
+
+
+@pytest.mark.parametrize("chunk,align", [(256, 4), (1024, 64), (16384, 4), (131072, 4)])
+def test_splitter_chunk_sizes(chunk, align):
+    """Chunks that take several passes of a wavefront (running position inside the chunk),
+    up to chunks larger than a 16-bit count."""
+    say("splitter chunk", chunk, align)
+    wl = W.custom([70001, 3, 1029, 64, 2048, 200000, 1], 3, 0.5, align=align, config_id=180)
+    run_splitter_steps(wl, GRAN_ELEMENT, 2, chunk_elems=chunk, align=align, injected=True)
+    run_splitter_steps(wl, GRAN_LAYER, 2, chunk_elems=chunk, align=align, injected=True)
+
+
+def test_splitter_degenerate_gibs_and_errors():
+    say("splitter degenerate")
+    import torch
+    from paper_2306_16926_amd.binding import OspError
+    wl = W.custom([5000, 3, 1029], 2, 0.5, align=4, config_id=181)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    arena = wl.arena_elems()
+    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s_ = g.shape[1]
+    M = wl.n_params
+    buf_i = torch.zeros((2, M), dtype=torch.float32, device="cuda")
+    buf_u = torch.zeros((2, M), dtype=torch.float32, device="cuda")
+    with pytest.raises(OspError):
+        c.osp_split_gradients(gd, s_, buf_i, M, buf_u, M)       # no GIB yet
+    for gib, gran in ((np.ones(3, np.uint8), GRAN_LAYER), (np.zeros(3, np.uint8), GRAN_LAYER),
+                      (np.zeros((arena + 31) // 32, np.uint32), GRAN_ELEMENT)):
+        o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
+        og_i, og_u = o.split_gradients(g)
+        buf_i.fill_(-1.0); buf_u.fill_(-1.0)
+        c.osp_split_gradients(gd, s_, buf_i, M, buf_u, M)
+        e1, e2 = og_i.shape[1], og_u.shape[1]
+        assert e1 == 0 or e2 == 0
+        assert np.array_equal(buf_i.cpu().numpy()[:, :e1], og_i)
+        assert np.array_equal(buf_u.cpu().numpy()[:, :e2], og_u)
+        assert (buf_i.cpu().numpy()[:, e1:] == -1.0).all() and (buf_u.cpu().numpy()[:, e2:] == -1.0).all()
+        with pytest.raises(OspError):
+            c.osp_split_gradients(gd, s_, None, 0, None, 0)
+        if e1 > 0:
+            with pytest.raises(OspError):
+                c.osp_split_gradients(gd, s_, buf_i, e1 - 1, None, 0)
+        with pytest.raises(OspError):
+            c.osp_ps_aggregate_update_packed(2, buf_u, M)       # stage 1 first
+        with pytest.raises(OspError):
+            c.osp_ps_aggregate_update_packed(0, buf_u, M)
+        # a full iteration through the dense parts, one of them empty
+        o.ps_aggregate_update(1, g); c.osp_ps_aggregate_update_packed(1, buf_i, M)
+        o.ps_aggregate_update(2, g); c.osp_ps_aggregate_update_packed(2, buf_u, M)
+        o.apply_stage(0); c.osp_apply_stage(0)
+        compare_state(job, o, "degenerate GIB")
+
+
+def test_splitter_cnn_shaped():
+    say("splitter resnet18")
+    run_splitter_steps(W.get("resnet18"), GRAN_ELEMENT, 2)
+    run_splitter_steps(W.get("resnet18"), GRAN_LAYER, 2)

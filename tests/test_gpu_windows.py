@@ -1,0 +1,283 @@
+"""The RS and ICS window calls against the oracle's six calls; the caller's stream schedule;
+random legal call sequences over every state-changing entry point."""
+import numpy as np
+import pytest
+
+from oracle.osp_oracle import GRAN_ELEMENT, GRAN_LAYER
+from paper_2306_16926_amd import workloads as W
+from tests import brute
+from tests.gpu_common import F, compare_gib, compare_state, device_job, run_steps, say
+from tests.helpers import make_oracle, random_bits, random_layer_gib
+
+pytestmark = pytest.mark.gpu
+
+# --------------------------------------------------------------------------
+# the two windows (one call each) against the oracle's six calls
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_windows_tiny_three_chained_steps(gran, weighted):
+    say("windows tiny", gran, weighted)
+    wl = W.get("tiny")
+    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
+    sizes = run_steps(wl, gran, 3, weights=wts, windows=True)
+    assert sizes[0] > 0
+    run_steps(wl, gran, 2, align=64, chunk_elems=1024, windows=True)
+
+
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 8, 9, 16, 17])
+def test_windows_worker_counts(n_workers):
+    """Fused kernels up to 8 (layer) / 16 (element, RS) workers, single-stage kernels above."""
+    say("windows workers", n_workers)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 1], n_workers, 0.4, align=4, config_id=140 + n_workers)
+    run_steps(wl, GRAN_LAYER, 3, windows=True)
+    run_steps(wl, GRAN_ELEMENT, 3, windows=True)
+    wts = np.random.default_rng(n_workers).random(n_workers).astype(F)
+    wts /= wts.sum()
+    run_steps(wl, GRAN_ELEMENT, 2, weights=wts, windows=True)
+    run_steps(wl, GRAN_LAYER, 2, weights=wts, windows=True)
+
+
+@pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT)])
+def test_windows_cnn_shaped(name, gran):
+    say("windows", name, gran)
+    sizes = run_steps(W.get(name), gran, 3, threads=8, windows=True)
+    assert sizes[-1] > 0
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("in_sync", [True, False])
+def test_windows_mixed_with_single_calls(gran, in_sync):
+    """Windows and single calls in one run, starting from replicas that are or are not declared
+    equal to the PS, over iterations that do and do not restore consistency; stage 2 from
+    another gradient buffer on some steps."""
+    say("windows mixed", gran, in_sync)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 70000, 2], 6, 0.5, align=4, config_id=170)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True, declare_in_sync=in_sync)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    plans = ["ww", "ws", "sw", "ww", "w-", "ww", "s-", "ww", "wW", "ww"]
+    for step, plan in enumerate(plans):
+        g = wl.make_grads(0, step); gd = job.upload_grads(g); s_ = g.shape[1]
+        g2, gd2 = g, gd
+        if plan[1] == "W":                      # ICS window from a different gradient buffer
+            g2 = wl.make_grads(3, step); gd2 = job.upload_grads(g2)
+        o.ps_aggregate_update(1, g)
+        if plan[0] == "w":
+            o.apply_stage(1); o.lgp_correct(g)
+            c.osp_rs_window(gd, s_)
+        else:                                   # single calls, stage 1 never installed
+            o.lgp_correct(g)
+            c.osp_ps_aggregate_update(1, gd, s_); c.osp_lgp_correct(gd, s_)
+        compare_state(job, o, f"step {step} {plan} RS")
+        o.ps_aggregate_update(2, g2)
+        if plan[1] in "wW":
+            o.apply_stage(2); o.split(gran, wl.budget)
+            c.osp_ics_window(gd2, s_, gran, wl.budget)
+        elif plan[1] == "s":
+            o.apply_stage(2); o.split(gran, wl.budget)
+            c.osp_ps_aggregate_update(2, gd2, s_); c.osp_apply_stage(2); c.osp_split(gran, wl.budget)
+        else:                                   # stage 2 aggregated but not installed, old GIB stays
+            c.osp_ps_aggregate_update(2, gd2, s_)
+        compare_state(job, o, f"step {step} {plan} ICS")
+        compare_gib(job, o, f"step {step} {plan}")
+
+
+def test_windows_reject_bad_arguments_before_launching():
+    say("windows errors")
+    from paper_2306_16926_amd.binding import OspError
+    wl = W.get("tiny")
+    o = make_oracle(wl)
+    job = device_job(wl)                        # no element keys
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    g = wl.make_grads(0, 0); gd = job.upload_grads(g); s_ = g.shape[1]
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)        # no stage 1 yet
+    c.osp_rs_window(gd, s_)
+    o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+    with pytest.raises(OspError):
+        c.osp_rs_window(gd, s_)                                # stage 2 pending
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_ELEMENT, wl.budget)      # needs element keys
+    with pytest.raises(OspError):
+        c.osp_ics_window(gd, s_, GRAN_LAYER, wl.n_params + 1)
+    compare_state(job, o, "after rejected calls")              # nothing was touched
+    c.osp_ics_window(gd, s_, GRAN_LAYER, wl.budget)
+    o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(GRAN_LAYER, wl.budget)
+    compare_state(job, o, "after ICS")
+    compare_gib(job, o, "after ICS")
+
+
+# --------------------------------------------------------------------------
+# the caller's stream schedule: RS on one stream, ICS on another, ordered by events
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_two_streams_with_events(gran):
+    """What OSP overlaps is the ICS window with the next iteration's compute: the RS calls go to
+    one stream, the ICS calls to a second one behind an event, while the first stream carries
+    other work (here a copy standing in for the forward/backward pass); the next RS waits for
+    the ICS through another event.  Default priorities, no host synchronization in the loop."""
+    import torch
+    say("two streams", gran)
+    wl = W.get("resnet18")
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=(gran == GRAN_ELEMENT))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    rs, ics = torch.cuda.Stream(), torch.cuda.Stream()
+    busy_src = torch.ones(64 << 20, dtype=torch.float32, device="cuda")
+    busy_dst = torch.empty_like(busy_src)
+    grads = [wl.make_grads(0, step, threads=8) for step in range(3)]
+    dev = [job.upload_grads(g) for g in grads]
+    torch.cuda.synchronize()
+    ics_done = torch.cuda.Event()
+    ics_done.record(ics)
+    for step in range(3):
+        gd = dev[step]; s_ = gd.shape[1]
+        rs.wait_event(ics_done)                         # stage 2 of the previous iteration is complete
+        if step % 2 == 0:
+            c.osp_rs_window(gd, s_, stream=rs)
+        else:
+            c.osp_ps_aggregate_update(1, gd, s_, stream=rs)
+            c.osp_apply_stage(1, stream=rs)
+            c.osp_lgp_correct(gd, s_, stream=rs)
+        rs_done = torch.cuda.Event(); rs_done.record(rs)
+        with torch.cuda.stream(rs):                     # "compute" of the next iteration
+            busy_dst.copy_(busy_src, non_blocking=True)
+        ics.wait_event(rs_done)
+        if step % 2 == 0:
+            c.osp_ics_window(gd, s_, gran, wl.budget, stream=ics)
+        else:
+            c.osp_ps_aggregate_update(2, gd, s_, stream=ics)
+            c.osp_apply_stage(2, stream=ics)
+            c.osp_split(gran, wl.budget, stream=ics)
+        ics_done = torch.cuda.Event(); ics_done.record(ics)
+        o.sync_step(grads[step], gran, wl.budget)
+    torch.cuda.synchronize()
+    compare_state(job, o, "two streams")
+    compare_gib(job, o, "two streams")
+    assert bool((busy_dst[:1024] == 1.0).all())
+
+
+# --------------------------------------------------------------------------
+# random legal call sequences over every entry point that touches the state
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", list(range(16)))
+def test_random_call_sequences(seed):
+    """Iterations assembled at random from the single-stage calls (fp32, bfloat16 and dense
+    gradient inputs), the two windows, optional installs and LGP in any legal order, splits of
+    either granularity or an injected GIB: the state is compared with the oracle after every
+    call.  Gradients are bfloat16-representable so that every input form carries the same values."""
+    import torch
+    say("random sequences", seed)
+    rng = np.random.default_rng(1000 + seed)
+    n_workers = int(rng.choice([2, 5, 8, 11]))
+    wl = W.custom([5000, 3, 1029, 64, 2048, 30000, 2], n_workers, 0.5, align=4, config_id=300 + seed)
+    arena = wl.arena_elems()
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    wts = None
+    if seed % 2:
+        wts = rng.random(n_workers).astype(F); wts /= wts.sum()
+    o = make_oracle(wl, weights=wts)
+    job = device_job(wl, weights=wts, element_keys=True, declare_in_sync=bool(seed % 3))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    M = wl.n_params
+    dense_i = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
+    dense_u = torch.zeros((n_workers, M + 4), dtype=torch.float32, device="cuda")
+    log = []
+
+    def check(what):
+        log.append(what)
+        try:
+            compare_state(job, o, what)
+        except AssertionError:
+            print("[case] calls so far:", " | ".join(log), flush=True)
+            raise
+
+    for it in range(10):
+        h = W.to_bf16(wl.make_grads(seed, it)); g = W.from_bf16(h)
+        gd = job.upload_grads(g); hd = job.upload_grads_bf16(h); s_ = g.shape[1]
+        packed = None
+
+        def get_packed():
+            og_i, og_u = o.split_gradients(g)
+            c.osp_split_gradients(gd, s_, dense_i, M + 4, dense_u, M + 4)
+            return og_i, og_u
+
+        def agg(stage):
+            nonlocal packed
+            form = rng.choice(["f32", "bf16", "packed"])
+            if form == "packed":
+                if packed is None:
+                    packed = get_packed()
+                part = packed[stage - 1]
+                if part.shape[1]:
+                    o.ps_aggregate_update_packed(stage, part)
+                else:
+                    o.ps_aggregate_update(stage, g)
+                c.osp_ps_aggregate_update_packed(stage, dense_i if stage == 1 else dense_u, M + 4)
+            elif form == "bf16":
+                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update_bf16(stage, hd, s_)
+            else:
+                o.ps_aggregate_update(stage, g); c.osp_ps_aggregate_update(stage, gd, s_)
+            check(f"it{it} agg{stage}:{form}")
+
+        def lgp():
+            if rng.random() < 0.5:
+                o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+            else:
+                o.lgp_correct(g); c.osp_lgp_correct_bf16(hd, s_)
+            check(f"it{it} lgp")
+
+        lgp_done = False
+        if rng.random() < 0.4:
+            o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
+            c.osp_rs_window(gd, s_)
+            lgp_done = True
+            check(f"it{it} rs_window")
+        else:
+            agg(1)
+            todo = []
+            if rng.random() < 0.8:
+                todo.append("apply1")
+            if rng.random() < 0.7:
+                todo.append("lgp")
+            rng.shuffle(todo)
+            for t in todo:
+                if t == "apply1":
+                    o.apply_stage(1); c.osp_apply_stage(1); check(f"it{it} apply1")
+                else:
+                    lgp(); lgp_done = True
+        split_gran = int(rng.choice([GRAN_LAYER, GRAN_ELEMENT]))
+        budget = int(rng.choice([0, wl.budget // 3, wl.budget, M]))
+        if rng.random() < 0.4:
+            o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(split_gran, budget)
+            c.osp_ics_window(gd, s_, split_gran, budget)
+            check(f"it{it} ics_window gran{split_gran} budget{budget}")
+        else:
+            agg(2)
+            if not lgp_done and rng.random() < 0.3:
+                lgp()
+            if rng.random() < 0.85:
+                o.apply_stage(2); c.osp_apply_stage(2); check(f"it{it} apply2")
+            r = rng.random()
+            if r < 0.6:
+                o.split(split_gran, budget); c.osp_split(split_gran, budget)
+                log.append(f"it{it} split gran{split_gran} budget{budget}")
+            elif r < 0.8:
+                gib = (random_layer_gib(rng, wl.n_tensors) if split_gran == GRAN_LAYER
+                       else random_bits(rng, arena, real))
+                o.set_gib(split_gran, gib); c.osp_set_gib(split_gran, gib)
+                log.append(f"it{it} set_gib gran{split_gran}")
+        compare_gib(job, o, f"it{it} gib")
+        assert c.osp_n_stage2() == o.n_stage2
