@@ -349,11 +349,14 @@ def test_single_pass_equals_two_stages():
 
 @pytest.mark.parametrize("frac", [0.0, 1.0, 0.999])
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
-def test_degenerate_budgets(gran, frac):
-    say("budget", gran, frac)
+@pytest.mark.parametrize("windows", [False, True])
+def test_degenerate_budgets(gran, frac, windows):
+    """Budget 0: every iteration is a BSP step; budget M: nothing is synchronized in the RS
+    window and every worker runs on its own estimate (Sec. 4.3); one stage is empty either way."""
+    say("budget", gran, frac, windows)
     wl = W.get("tiny")
     budget = int(frac * wl.n_params)
-    sizes = run_steps(wl, gran, 3, budget=budget)
+    sizes = run_steps(wl, gran, 3, budget=budget, windows=windows)
     if frac == 0.0:
         assert sizes == [0, 0, 0]
     if frac == 1.0:
