@@ -106,6 +106,9 @@ def main() -> int:
                          "gradient splitter followed by the six calls with the PS fed by its dense parts")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the gradient arenas (bf16: --calls six only)")
+    ap.add_argument("--graph", action="store_true",
+                    help="replay each step as a captured HIP graph (element granularity with "
+                         "--calls windows only: no call of such a step needs the host)")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--chunk-elems", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -180,10 +183,29 @@ def main() -> int:
     bracketed = BRACKETED[mode]
     ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for n in bracketed} if i % BRACKET_EVERY == 0 else None for i in range(K)]
+    graphs = None
+    if args.graph:
+        if not (element and windows) or Wm < 2:
+            print("bench.py: --graph needs --granularity element --calls windows --warmup >= 2",
+                  file=sys.stderr)
+            return 2
+        torch.cuda.synchronize()
+        graphs = []
+        for gset in gsets:                       # one graph per gradient set; capture runs nothing
+            gr = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(gr):
+                for _, call in calls_of_step:
+                    call(gset)
+            graphs.append(gr)
+        ev = [None] * K                          # events cannot sit between the nodes of a graph
     torch.cuda.synchronize()
 
     t_start = time.perf_counter()
     for i in range(K):
+        if graphs:
+            graphs[(Wm + i) % 2].replay()
+            n2_log[i] = wl.budget                # element split: exactly the budget
+            continue
         g = gsets[(Wm + i) % 2]
         e = ev[i]
         for j, (name, call) in enumerate(calls_of_step):
@@ -227,6 +249,9 @@ def main() -> int:
               "k_split_gradients" if mode == "packed" else
               ("k_rs_window_element" if element else "k_window_layer") if fused_rs else
               "osp_rs_window (three single-stage kernels)")
+    roofline_from_second_pass = agg_launches == 0
+    if roofline_from_second_pass:                # graph replay: filled in from the eager second pass
+        agg_ms_sum, agg_bytes_sum, agg_launches = 1.0, 0, 1
     agg_ms = agg_ms_sum / agg_launches
     agg_bytes = agg_bytes_sum / agg_launches
     agg_gbps = agg_bytes / (agg_ms * 1e-3) / 1e9 if agg_ms > 0 else 0.0
@@ -260,6 +285,14 @@ def main() -> int:
         for j, n in enumerate(names):
             call_ms[n] += ev2[i][j].elapsed_time(ev2[i][j + 1])
             call_bytes[n] += b[n]
+    if roofline_from_second_pass:
+        n0 = bracketed[0]
+        ms0 = call_ms[n0] / K2
+        roofline.update({"achieved": round(call_bytes[n0] / K2 / (ms0 * 1e-3) / 1e9, 1),
+                         "frac": round(call_bytes[n0] / K2 / (ms0 * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "launches": K2, "avg_launch_ms": round(ms0, 5),
+                         "bytes_per_launch": int(call_bytes[n0] / K2),
+                         "note": "events cannot sit inside a graph: taken from the eager second pass"})
     calls = {n: {"ms": round(call_ms[n] / K2, 5),
                  "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
              for n in names}
@@ -290,6 +323,7 @@ def main() -> int:
         "dtype": "f32" if not bf16 else "f32 (gradients stored as bf16)", "data": "synthetic",
         "config": {"workload": f"{wl.name}-shaped", "n_workers": N, "n_tensors": wl.n_tensors,
                    "n_params": M, "granularity": args.granularity, "calls": args.calls,
+                   "graph_replay": bool(args.graph),
                    "windows_fused": ({"rs": bool(c.osp_windows_fused() & 1),
                                       "ics": bool(c.osp_windows_fused() & 2)} if windows else None),
                    "stage2_fraction_nominal": wl.stage2_fraction,

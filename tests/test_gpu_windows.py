@@ -281,3 +281,48 @@ def test_random_call_sequences(seed):
                 log.append(f"it{it} set_gib gran{split_gran}")
         compare_gib(job, o, f"it{it} gib")
         assert c.osp_n_stage2() == o.n_stage2
+
+
+# --------------------------------------------------------------------------
+# an element-granular iteration as a captured graph
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("name", ["tiny", "resnet18"])
+def test_element_windows_replay_as_a_graph(name):
+    """With an element-granular GIB no call of the iteration needs anything from the host (no
+    table lengths), and the library clears its scratch with fill kernels, not memsets: the two
+    window calls can be captured once and replayed.  Each replay, with eager copies and a
+    synchronization in between, is compared with the oracle."""
+    import torch
+    say("graph replay", name)
+    wl = W.get(name)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    g = wl.make_grads(0, 0, threads=8)
+    static = job.upload_grads(g); s_ = static.shape[1]
+    for step in range(2):                               # eager: reach an element-granular GIB
+        g = wl.make_grads(0, step, threads=8)
+        static.copy_(torch.from_numpy(g))
+        o.sync_step(g, GRAN_ELEMENT, wl.budget)
+        job.sync_step_windows(static, GRAN_ELEMENT, wl.budget)
+    torch.cuda.synchronize()
+    compare_state(job, o, "before capture")
+    graph = torch.cuda.CUDAGraph()
+    g = wl.make_grads(0, 2, threads=8)
+    static.copy_(torch.from_numpy(g))
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph):                       # capture runs nothing
+        c.osp_rs_window(static, s_)
+        c.osp_ics_window(static, s_, GRAN_ELEMENT, wl.budget)
+    for step in range(2, 6):
+        g = wl.make_grads(0, step, threads=8)
+        static.copy_(torch.from_numpy(g))               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        o.sync_step(g, GRAN_ELEMENT, wl.budget)
+        compare_state(job, o, f"replay of step {step}")
+        compare_gib(job, o, f"replay of step {step}")
