@@ -311,6 +311,19 @@ def main() -> int:
     copy_gbps = 10 * 2 * src.numel() * 4 / (a.elapsed_time(b2) * 1e-3) / 1e9
     assert bool((dst[:1024] == 1.0).all()) and bool((dst[-1024:] == 1.0).all())
     del src, dst
+    # second reference line: the aggregate's traffic shape without its arithmetic (N gradient
+    # streams read, two streams read and written back), on this run's own gradient arenas
+    pattern_gbps = None
+    if not bf16:
+        from paper_2306_16926_amd.binding import osp_stream_pattern
+        rw = torch.zeros((2, stride), dtype=torch.float32, device="cuda")
+        osp_stream_pattern(gsets[0], N, stride, rw, 2, stride, arena)
+        torch.cuda.synchronize(); a.record()
+        for r in range(6):
+            osp_stream_pattern(gsets[r % 2], N, stride, rw, 2, stride, arena)
+        b2.record(); torch.cuda.synchronize()
+        pattern_gbps = 6 * 4 * (N + 4) * arena / (a.elapsed_time(b2) * 1e-3) / 1e9
+        del rw
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -337,6 +350,7 @@ def main() -> int:
         "GBps_on_bytes_moved": None if moved_bytes is None else round(moved_bytes / elapsed / 1e9, 1),
         "calls_second_pass": calls,
         "copy_GBps_same_box": round(copy_gbps, 1),
+        "aggregate_pattern_GBps_same_box": None if pattern_gbps is None else round(pattern_gbps, 1),
         "roofline": roofline,
         "cpu_baseline": cpu,
         "paper_context": "paper reports up to 50% end-to-end training throughput gain on 8xT4 "

@@ -281,6 +281,16 @@ osp_status osp_get_keys(osp_ctx *ctx, uint32_t *key_host, void *stream);
  * part of the synchronization step.  At most 2^31 KiB per call. */
 osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *stream);
 
+/* A second reference line: the traffic of osp_ps_aggregate_update's shape without
+ * its arithmetic.  n_read streams (reads + s*read_stride, s < n_read) are read
+ * and summed; n_rw streams (1 or 2; rw + s*rw_stride) are read and written back
+ * with the sum added; n_elems elements (multiple of 4) of every stream, strides
+ * in elements (multiples of 4, >= n_elems), all DEVICE and 16-byte aligned.
+ * What it sustains is the ceiling of that access pattern on the machine at
+ * hand.  Not part of the synchronization step. */
+osp_status osp_stream_pattern(const float *reads, int32_t n_read, int64_t read_stride, float *rw,
+                              int32_t n_rw, int64_t rw_stride, int64_t n_elems, void *stream);
+
 /*
  * S(G^u) tuning (Sec. 4.1.2).  Host-only scalar functions: no context, no GPU.
  *

@@ -100,6 +100,8 @@ def _load() -> C.CDLL:
     lib.osp_get_keys.restype = C.c_int
     lib.osp_stream_copy.argtypes = [vp, vp, C.c_size_t, vp]
     lib.osp_stream_copy.restype = C.c_int
+    lib.osp_stream_pattern.argtypes = [vp, C.c_int32, i64, vp, C.c_int32, i64, i64, vp]
+    lib.osp_stream_pattern.restype = C.c_int
     lib.osp_ics_upper_bound.argtypes = [C.c_double, C.c_double, C.c_double, C.c_int32]
     lib.osp_ics_upper_bound.restype = C.c_double
     lib.osp_tune_budget.argtypes = [C.c_int32, C.c_double, C.c_double, C.c_double, i64]
@@ -125,7 +127,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_ps_aggregate_update_bf16", "osp_lgp_correct_bf16",
            "osp_get_importance", "osp_get_keys",
-           "osp_stream_copy", "osp_ics_upper_bound", "osp_tune_budget",
+           "osp_stream_copy", "osp_stream_pattern", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
 
 
@@ -301,6 +303,14 @@ def osp_stream_copy(dst, src, nbytes: int, stream=None) -> None:
     st = lib.osp_stream_copy(_ptr(dst), _ptr(src), int(nbytes), _stream(stream))
     if st != OSP_OK:
         raise OspError(st, "osp_stream_copy")
+
+
+def osp_stream_pattern(reads, n_read: int, read_stride: int, rw, n_rw: int, rw_stride: int,
+                       n_elems: int, stream=None) -> None:
+    st = lib.osp_stream_pattern(_ptr(reads), int(n_read), int(read_stride), _ptr(rw), int(n_rw),
+                                int(rw_stride), int(n_elems), _stream(stream))
+    if st != OSP_OK:
+        raise OspError(st, "osp_stream_pattern")
 
 
 def osp_ics_upper_bound(bandwidth_elems_per_s, loss_rate, t_compute_s, n_workers) -> float:

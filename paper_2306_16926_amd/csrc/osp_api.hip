@@ -1423,6 +1423,29 @@ osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *strea
     return hipGetLastError() == hipSuccess ? OSP_OK : OSP_ERR_HIP;
 }
 
+osp_status osp_stream_pattern(const float *reads, int32_t n_read, int64_t read_stride, float *rw,
+                              int32_t n_rw, int64_t rw_stride, int64_t n_elems, void *stream)
+{
+    if (!reads || !rw || !aligned16(reads) || !aligned16(rw) || n_read < 1 || n_rw < 1 || n_rw > 2 ||
+        n_elems < 0 || n_elems % 4 != 0 || read_stride % 4 != 0 || rw_stride % 4 != 0 ||
+        read_stride < n_elems || rw_stride < n_elems)
+        return OSP_ERR_INVALID_ARG;
+    PatternArgs a;
+    a.reads = reads;
+    a.read_stride = read_stride;
+    a.rw = rw;
+    a.rw_stride = rw_stride;
+    a.n_vec = n_elems / 4;
+    a.n_read = n_read;
+    a.n_rw = n_rw;
+    const long long groups = (a.n_vec + kBlock - 1) / kBlock;
+    if (groups > 0x7FFFFFFFLL)
+        return OSP_ERR_INVALID_ARG;
+    if (groups > 0)
+        k_stream_pattern<<<(unsigned)groups, kBlock, 0, (hipStream_t)stream>>>(a);
+    return hipGetLastError() == hipSuccess ? OSP_OK : OSP_ERR_HIP;
+}
+
 double osp_ics_upper_bound(double bandwidth_elems_per_s, double loss_rate, double t_compute_s,
                            int32_t n_workers)
 {

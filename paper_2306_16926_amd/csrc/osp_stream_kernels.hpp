@@ -567,6 +567,48 @@ __global__ __launch_bounds__(kBlock) void k_stream_copy(float *__restrict__ dst,
 }
 
 // ---------------------------------------------------------------------------
+// Reference traffic of the aggregate's shape, without its arithmetic: n_read
+// streams are read and summed, n_rw streams (1 or 2) are read and written back
+// with the sum added, one wavefront per KiB of every stream.  What this reaches
+// is the ceiling of k_aggregate_update's access pattern on the machine at hand.
+// ---------------------------------------------------------------------------
+struct PatternArgs {
+    const float *reads;
+    long long read_stride;
+    float *rw;
+    long long rw_stride;
+    long long n_vec;
+    int n_read;
+    int n_rw;
+};
+
+__global__ __launch_bounds__(kBlock) void k_stream_pattern(const PatternArgs a)
+{
+    const long long v = (long long)blockIdx.x * kBlock + threadIdx.x;
+    if (v >= a.n_vec)
+        return;
+    const unsigned i = threadIdx.x * kVec;
+    const float *R = a.reads + (long long)blockIdx.x * kStride;
+    float *W = a.rw + (long long)blockIdx.x * kStride;
+    f4 old[2];
+    old[0] = ld_stream(W + i);
+    if (a.n_rw > 1)
+        old[1] = ld_stream(W + a.rw_stride + i);
+    f4 acc;
+    int w = 0;
+    for (; w + kWorkerBlock <= a.n_read; w += kWorkerBlock)
+        add_workers<kWorkerBlock, false>(acc, w, R, a.read_stride, i, nullptr);
+    const int rest = a.n_read - w;
+    if (rest & 8) { add_workers<8, false>(acc, w, R, a.read_stride, i, nullptr); w += 8; }
+    if (rest & 4) { add_workers<4, false>(acc, w, R, a.read_stride, i, nullptr); w += 4; }
+    if (rest & 2) { add_workers<2, false>(acc, w, R, a.read_stride, i, nullptr); w += 2; }
+    if (rest & 1) { add_workers<1, false>(acc, w, R, a.read_stride, i, nullptr); }
+    st_stream(W + i, old[0] + acc);
+    if (a.n_rw > 1)
+        st_stream(W + a.rw_stride + i, old[1] + acc);
+}
+
+// ---------------------------------------------------------------------------
 // LGP when every replica is known to equal the PS on the stage-2 elements (the
 // previous iteration installed both stages and nothing else writes replicas):
 // P_w = P - lr g_w then gives bit for bit what P_w = P_w - lr g_w gives, and the

@@ -553,3 +553,26 @@ def test_state_machine():
     layer, _, n2 = c.osp_get_gib()
     assert n2 == 0 and layer.all()
     assert not np.array_equal(before[0], after[0])
+
+
+def test_reference_traffic_kernels_move_what_they_say():
+    """osp_stream_copy and osp_stream_pattern are bandwidth reference lines, not part of the
+    step; they still have to do exactly the stated data movement."""
+    import torch
+    from paper_2306_16926_amd.binding import OspError, osp_stream_copy, osp_stream_pattern
+    say("reference kernels")
+    n, stride = 100_000, 100_064
+    for n_read in (1, 3, 8, 16, 19):
+        for n_rw in (1, 2):
+            reads = torch.randint(-8, 9, (n_read, stride), device="cuda").float()
+            rw = torch.randint(-8, 9, (n_rw, stride), device="cuda").float()
+            want = rw.clone()
+            want[:, :n] += reads[:, :n].sum(0)              # small integers: exact in any order
+            osp_stream_pattern(reads, n_read, stride, rw, n_rw, stride, n)
+            assert torch.equal(rw, want), (n_read, n_rw)
+    src = torch.arange(1 << 16, device="cuda", dtype=torch.float32)
+    dst = torch.zeros_like(src)
+    osp_stream_copy(dst, src, src.numel() * 4)
+    assert torch.equal(dst, src)
+    with pytest.raises(OspError):
+        osp_stream_pattern(reads, 3, n - 4, rw, 1, stride, n)   # stride below the stream length
