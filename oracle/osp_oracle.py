@@ -142,6 +142,12 @@ class OracleOSP:
         self.n_stage2 = 0
 
     # -- state -----------------------------------------------------------
+    def set_hyper(self, lr: float, momentum: float) -> None:
+        """New learning rate / momentum from the next call on (the schedule of Sec. 5.1.3
+        halves the learning rate every 10 epochs)."""
+        self.model.lr = lr
+        self.model.momentum = momentum
+
     def load_params(self, P: np.ndarray, V: Optional[np.ndarray] = None) -> None:
         self.P[:] = P
         self.V[:] = 0.0 if V is None else V

@@ -576,3 +576,37 @@ def test_reference_traffic_kernels_move_what_they_say():
     assert torch.equal(dst, src)
     with pytest.raises(OspError):
         osp_stream_pattern(reads, 3, n - 4, rw, 1, stride, n)   # stride below the stream length
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_learning_rate_schedule(gran):
+    """osp_set_hyper between iterations (the learning rate is halved every 10 epochs, Sec. 5.1.3);
+    refused between the two stages of one iteration."""
+    from paper_2306_16926_amd.binding import OspError
+    say("lr schedule", gran)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 30000], 4, 0.5, align=4, config_id=400)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    lr = wl.lr
+    for step in range(6):
+        if step in (2, 4):
+            lr *= 0.5
+            mu = wl.momentum if step == 2 else 0.5
+            o.set_hyper(lr, mu); c.osp_set_hyper(lr, mu)
+        g = wl.make_grads(0, step); gd = job.upload_grads(g); s_ = g.shape[1]
+        if step % 2:
+            o.sync_step(g, gran, wl.budget); job.sync_step_windows(gd, gran, wl.budget)
+        else:
+            o.ps_aggregate_update(1, g); c.osp_ps_aggregate_update(1, gd, s_)
+            with pytest.raises(OspError):
+                c.osp_set_hyper(0.01, 0.0)              # between the stages
+            o.apply_stage(1); c.osp_apply_stage(1)
+            o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+            o.ps_aggregate_update(2, g); c.osp_ps_aggregate_update(2, gd, s_)
+            o.apply_stage(2); c.osp_apply_stage(2)
+            o.split(gran, wl.budget); c.osp_split(gran, wl.budget)
+        compare_state(job, o, f"lr schedule step {step}")
+        compare_gib(job, o, f"lr schedule step {step}")

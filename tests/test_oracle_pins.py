@@ -512,6 +512,28 @@ def test_gib_is_under_1kb_below_1k_layers():
     assert np.ones(wl.n_tensors, np.uint8).nbytes < 1024
 
 
+def test_learning_rate_schedule_matches_torch_sgd():
+    """Halving the learning rate between iterations (Sec. 5.1.3): the momentum buffer carries
+    over, as in torch.optim.SGD whose param_group lr is changed."""
+    wl = small_wl(2)
+    o = make_oracle(wl, lr=0.1, mu=0.9)
+    o.set_gib(GRAN_LAYER, np.ones(wl.n_tensors, np.uint8))
+    p = torch.tensor(o.P.copy(), dtype=torch.float32, requires_grad=True)
+    opt = torch.optim.SGD([p], lr=0.1, momentum=0.9)
+    lr = 0.1
+    for step in range(4):
+        if step == 2:
+            lr = 0.05
+            o.set_hyper(lr, 0.9)
+            opt.param_groups[0]["lr"] = lr
+        g = wl.make_grads(0, step)
+        o.ps_aggregate_update(0, g)
+        p.grad = torch.tensor((g[0, :wl.arena_elems()] + g[1, :wl.arena_elems()]) * F(0.5))
+        opt.step()
+    real = brute.real_mask(wl.numel, wl.offsets(), wl.arena_elems())
+    assert np.allclose(o.P[real], p.detach().numpy()[real], rtol=2e-6, atol=1e-9)
+
+
 # --------------------------------------------------------------------------
 # gradient splitter (Sec. 4.5): dense G^i / G^u, and the PS update fed by them
 # --------------------------------------------------------------------------
