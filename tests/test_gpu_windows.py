@@ -326,3 +326,41 @@ def test_element_windows_replay_as_a_graph(name):
         o.sync_step(g, GRAN_ELEMENT, wl.budget)
         compare_state(job, o, f"replay of step {step}")
         compare_gib(job, o, f"replay of step {step}")
+
+
+# --------------------------------------------------------------------------
+# Algorithm 1 driving the budget of the split over several "epochs"
+# --------------------------------------------------------------------------
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_tuned_budget_over_epochs(gran):
+    """S(G^u) from Eq. 5 and Algorithm 1 (library) sets the budget of each epoch's splits:
+    0 in the first epoch (BSP), growing as the synthetic loss falls, capped at 80 % of the
+    model; the stage-2 sizes follow the oracle's."""
+    from oracle.osp_oracle import ics_upper_bound, tune_budget
+    from paper_2306_16926_amd.binding import osp_ics_upper_bound, osp_tune_budget
+    say("tuned budget", gran)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 30000, 700], 4, 0.5, align=4, config_id=410)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    M = wl.n_params
+    u_lib = osp_ics_upper_bound(2.0e5, 0.01, 0.9, wl.n_workers)      # elements per compute window
+    assert u_lib == ics_upper_bound(2.0e5, 0.01, 0.9, wl.n_workers)
+    losses = [2.3, 1.7, 1.1, 0.6, 0.2, 0.01]
+    sizes, step = [], 0
+    for epoch, loss in enumerate(losses, start=1):
+        budget = osp_tune_budget(epoch, loss, losses[0], u_lib, M)
+        assert budget == tune_budget(epoch, loss, losses[0], u_lib, M)
+        assert 0 <= budget <= int(0.8 * M)
+        for _ in range(2):                                   # two iterations per epoch
+            g = wl.make_grads(0, step); gd = job.upload_grads(g); step += 1
+            o.sync_step(g, gran, budget)
+            job.sync_step_windows(gd, gran, budget)
+            compare_state(job, o, f"epoch {epoch}")
+            compare_gib(job, o, f"epoch {epoch}")
+        sizes.append(o.n_stage2)
+    assert sizes[0] == 0 and sizes[-1] > 0
+    assert sizes == sorted(sizes)                            # the loss only falls here
