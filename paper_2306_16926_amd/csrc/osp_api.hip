@@ -23,7 +23,7 @@ namespace {
 
 constexpr int kDefaultChunkElems = kStride;     // one float4 per lane
 constexpr size_t kAlign = 256;
-constexpr int kFanoutMaxWorkers = 8;           // install: fan-out kernel up to here, sweep above
+constexpr int kFanoutMaxWorkers = 4;           // install: fan-out kernel up to here, sweep above
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -285,6 +285,28 @@ static void launch_aggregate(int variant, dim3 grid, dim3 block, hipStream_t s, 
     case 5: k_aggregate_update<true, false, true, GT><<<grid, block, 0, s>>>(a); break;
     default: k_aggregate_update<true, true, true, GT><<<grid, block, 0, s>>>(a); break;
     }
+}
+
+// Shape of a sweep launch (install or LGP over a span table): blocks of about 8 MB of
+// parameters, each swept replica after replica; grid = (pieces of a block, workers, blocks).
+constexpr int kSweepVec = 1;            // float4 per lane in the sweep kernels (2 measured slower)
+struct SweepShape {
+    unsigned pieces_per_span, spans_per_block, n_blocks;
+    int pieces_shift;
+};
+
+static SweepShape sweep_shape(const osp_ctx *ctx, unsigned n_spans)
+{
+    SweepShape sh;
+    sh.pieces_per_span = (unsigned)(kSpanChunks * ctx->chunk_elems / (kPiece * kSweepVec));
+    sh.pieces_shift = -1;
+    for (int b = 0; b < 31; ++b)
+        if (sh.pieces_per_span == (1u << b))
+            sh.pieces_shift = b;
+    const long long span_bytes = (long long)kSpanChunks * ctx->chunk_elems * 4;
+    sh.spans_per_block = (unsigned)((8LL << 20) / span_bytes > 0 ? (8LL << 20) / span_bytes : 1);
+    sh.n_blocks = (n_spans + sh.spans_per_block - 1) / sh.spans_per_block;
+    return sh;
 }
 
 extern "C" {
@@ -772,28 +794,27 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
         a.grads = grads;
         a.worker_stride = worker_stride;
         a.n_spans = n_spans;
-        a.pieces_per_span = (unsigned)(kSpanChunks * ctx->chunk_elems / kPiece);
-        const long long span_bytes = (long long)kSpanChunks * ctx->chunk_elems * 4;
-        a.spans_per_block = (unsigned)((8LL << 20) / span_bytes > 0 ? (8LL << 20) / span_bytes : 1);
-        a.n_workers = (unsigned)ctx->n_workers;
+        const SweepShape sh = sweep_shape(ctx, n_spans);
+        a.pieces_per_span = sh.pieces_per_span;
+        a.pieces_shift = sh.pieces_shift;
+        a.spans_per_block = sh.spans_per_block;
         a.lr = ctx->lr;
-        const long long n_blocks = (n_spans + a.spans_per_block - 1) / a.spans_per_block;
-        const long long n_groups = n_blocks * a.spans_per_block * a.pieces_per_span * a.n_workers;
-        if (n_groups > 0x7FFFFFFFLL)
-            return fail(ctx, OSP_ERR_UNSUPPORTED, "LGP launch of %lld workgroups exceeds the grid limit",
-                        n_groups);
-        const dim3 grid((unsigned)n_groups), block(kApplyBlock);
-        if (n_groups > 0) {
+        if (sh.n_blocks > 65535u || ctx->n_workers > 65535)
+            return fail(ctx, OSP_ERR_UNSUPPORTED, "LGP launch of %u blocks x %d workers exceeds the grid limit",
+                        sh.n_blocks, ctx->n_workers);
+        const dim3 grid(sh.spans_per_block * sh.pieces_per_span, (unsigned)ctx->n_workers, sh.n_blocks);
+        const dim3 block(kApplyBlock);
+        if (sh.n_blocks > 0) {
             if (bf16) {
                 if (masked)
-                    k_lgp_sweep<true, bf16_t><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<true, bf16_t, kSweepVec><<<grid, block, 0, s>>>(a);
                 else
-                    k_lgp_sweep<false, bf16_t><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<false, bf16_t, kSweepVec><<<grid, block, 0, s>>>(a);
             } else {
                 if (masked)
-                    k_lgp_sweep<true><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<true, float, kSweepVec><<<grid, block, 0, s>>>(a);
                 else
-                    k_lgp_sweep<false><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<false, float, kSweepVec><<<grid, block, 0, s>>>(a);
             }
         }
     } else {
@@ -893,23 +914,22 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
         a.Pw = ctx->Pw;
         a.param_stride = ctx->param_stride;
         a.n_spans = n_spans;
-        a.pieces_per_span = (unsigned)(kSpanChunks * ctx->chunk_elems / kPiece);
-        // blocks of about 8 MB of parameters (at least one span)
-        const long long span_bytes = (long long)kSpanChunks * ctx->chunk_elems * 4;
-        a.spans_per_block = (unsigned)((8LL << 20) / span_bytes > 0 ? (8LL << 20) / span_bytes : 1);
-        a.n_workers = (unsigned)ctx->n_workers;
+        const SweepShape sh = sweep_shape(ctx, n_spans);
+        a.pieces_per_span = sh.pieces_per_span;
+        a.pieces_shift = sh.pieces_shift;
+        a.spans_per_block = sh.spans_per_block;
         a.stage = stage;
-        const long long n_blocks = (n_spans + a.spans_per_block - 1) / a.spans_per_block;
-        const long long n_groups = n_blocks * a.spans_per_block * a.pieces_per_span * a.n_workers;
-        if (n_groups > 0x7FFFFFFFLL)
+        if (sh.n_blocks > 65535u || ctx->n_workers > 65535)
             return fail(ctx, OSP_ERR_UNSUPPORTED,
-                        "install launch of %lld workgroups exceeds the grid limit", n_groups);
-        const dim3 grid((unsigned)n_groups), block(kApplyBlock);
-        if (n_groups > 0) {
+                        "install launch of %u blocks x %d workers exceeds the grid limit", sh.n_blocks,
+                        ctx->n_workers);
+        const dim3 grid(sh.spans_per_block * sh.pieces_per_span, (unsigned)ctx->n_workers, sh.n_blocks);
+        const dim3 block(kApplyBlock);
+        if (sh.n_blocks > 0) {
             if (masked)
-                k_apply_stage_sweep<true><<<grid, block, 0, s>>>(a);
+                k_apply_stage_sweep<true, kSweepVec><<<grid, block, 0, s>>>(a);
             else
-                k_apply_stage_sweep<false><<<grid, block, 0, s>>>(a);
+                k_apply_stage_sweep<false, kSweepVec><<<grid, block, 0, s>>>(a);
         }
     } else {
         FanoutArgs a;

@@ -399,15 +399,14 @@ __global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
 // Install a stage's global parameters on every worker replica: one read
 // stream, N write streams.  Two shapes, chosen by N on the host:
 //
-//  * sweep (N > 8): writing all N from one workgroup keeps 16+ DRAM write
+//  * sweep (N > 4): writing all N from one workgroup keeps 16+ DRAM write
 //    streams open at once (measured 5.7 TB/s at N = 16).  Instead the table is
 //    cut into blocks of about 8 MB of parameters and, block after block, the GPU
 //    writes one replica at a time: the parameter block is read from HBM once and
 //    served from cache to the other N-1 sweeps, and the writes form a single
-//    stream (measured 6.3 TB/s).  Workgroups of 256 lanes, one float4 each
-//    (4 KiB): with one wavefront per KiB the launch rate of workgroups would be
-//    the limit here.
-//  * fan-out (N <= 8): one wavefront per chunk reads its float4 once and writes
+//    stream.  Workgroups of 256 lanes: with one wavefront per KiB the launch
+//    rate of workgroups would be the limit here.
+//  * fan-out (N <= 4): one wavefront per chunk reads its float4 once and writes
 //    it to all N replicas; with few replicas this is as fast and launches fewer
 //    workgroups.
 // ---------------------------------------------------------------------------
@@ -421,41 +420,65 @@ struct ApplyArgs {
     float *Pw;
     long long param_stride;
     unsigned n_spans;
-    unsigned pieces_per_span;          // 64 * chunk_elems / kPiece
+    unsigned pieces_per_span;          // 64 * chunk_elems / (T * kPiece)
+    int pieces_shift;                  // log2(pieces_per_span) if it is a power of two, else -1
     unsigned spans_per_block;
-    unsigned n_workers;
     int stage;
 };
 
-template <bool MASKED>
+// Sweep kernels: grid = (pieces of a block, workers, blocks), dispatched in that order (x
+// fastest), so the kernel needs no division to find its place.  A workgroup lives about as
+// long as two dependent cache hits (its span entry, then its parameters): each lane moves T
+// float4, T * 4 KiB per workgroup, to keep enough bytes in flight over that latency.
+template <int T>
+__device__ __forceinline__ bool sweep_piece(const Span *__restrict__ spans, unsigned n_spans,
+                                            unsigned spans_per_block, unsigned pieces_per_span,
+                                            int pieces_shift, Span &s, int &off0)
+{
+    const unsigned q = blockIdx.x;
+    const unsigned sp = pieces_shift >= 0 ? q >> pieces_shift : q / pieces_per_span;
+    const unsigned si = blockIdx.z * spans_per_block + sp;
+    if (si >= n_spans)
+        return false;
+    s = spans[si];
+    off0 = (int)(q - sp * pieces_per_span) * (kPiece * T) + (int)threadIdx.x * kVec;
+    return off0 < s.n_elems;
+}
+
+template <bool MASKED, int T>
 __global__ __launch_bounds__(kApplyBlock) void k_apply_stage_sweep(const ApplyArgs a)
 {
-    // workgroup -> (block of spans, worker, span in block, piece of span), worker-major in a block
-    const unsigned per_worker = a.spans_per_block * a.pieces_per_span;
-    const unsigned per_block = per_worker * a.n_workers;
-    const unsigned blk = blockIdx.x / per_block, r = blockIdx.x % per_block;
-    const unsigned w = r / per_worker, q = r % per_worker;
-    const unsigned si = blk * a.spans_per_block + q / a.pieces_per_span;
-    if (si >= a.n_spans)
+    Span s;
+    int off0;
+    if (!sweep_piece<T>(a.spans, a.n_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift,
+                        s, off0))
         return;
-    const Span s = a.spans[si];
-    const int off = (int)(q % a.pieces_per_span) * kPiece + (int)threadIdx.x * kVec;
-    if (off >= s.n_elems)
-        return;
-    const int rem = s.n_elems - off;
-    const float *src = a.P + s.start + off;
-    float *dst = a.Pw + (long long)w * a.param_stride + s.start + off;
-    const unsigned m = lane_mask<MASKED>(rem, s.start + off, a.stage, a.bitmap);
-    const f4 p = ld_keep(src);                 // kept in cache for the other replicas' sweeps
-    if (!MASKED && m == 0xFu) {
-        st_stream(dst, p);
-    } else if (MASKED && rem >= kVec) {
-        st_stream(dst, blend(m, p, ld_stream(dst)));
-    } else {
+    const float *src = a.P + s.start;
+    float *dst = a.Pw + (long long)blockIdx.y * a.param_stride + s.start;
+    f4 p[T];
 #pragma unroll
-        for (int j = 0; j < kVec; ++j)
-            if (m & (1u << j))
-                dst[j] = p[j];
+    for (int t = 0; t < T; ++t) {
+        const int off = off0 + t * kPiece;
+        if (off < s.n_elems)
+            p[t] = ld_keep(src + off);         // kept in cache for the other replicas' sweeps
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int off = off0 + t * kPiece;
+        if (off >= s.n_elems)
+            continue;
+        const int rem = s.n_elems - off;
+        const unsigned m = lane_mask<MASKED>(rem, s.start + off, a.stage, a.bitmap);
+        if (!MASKED && m == 0xFu) {
+            st_stream(dst + off, p[t]);
+        } else if (MASKED && rem >= kVec) {
+            st_stream(dst + off, blend(m, p[t], ld_stream(dst + off)));
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j)
+                if (m & (1u << j))
+                    dst[off + j] = p[t][j];
+        }
     }
 }
 
@@ -630,42 +653,51 @@ struct LgpSweepArgs {
     long long worker_stride;
     unsigned n_spans;
     unsigned pieces_per_span;
+    int pieces_shift;
     unsigned spans_per_block;
-    unsigned n_workers;
     float lr;
 };
 
-template <bool MASKED, typename GT = float>
+template <bool MASKED, typename GT, int T>
 __global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
 {
-    const unsigned per_worker = a.spans_per_block * a.pieces_per_span;
-    const unsigned per_block = per_worker * a.n_workers;
-    const unsigned blk = blockIdx.x / per_block, r = blockIdx.x % per_block;
-    const unsigned w = r / per_worker, q = r % per_worker;
-    const unsigned si = blk * a.spans_per_block + q / a.pieces_per_span;
-    if (si >= a.n_spans)
+    Span s;
+    int off0;
+    if (!sweep_piece<T>(a.spans, a.n_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift,
+                        s, off0))
         return;
-    const Span s = a.spans[si];
-    const int off = (int)(q % a.pieces_per_span) * kPiece + (int)threadIdx.x * kVec;
-    if (off >= s.n_elems)
-        return;
-    const int rem = s.n_elems - off;
-    const long long e = s.start + off;
-    float *dst = a.Pw + (long long)w * a.param_stride + e;
-    const unsigned m = lane_mask<MASKED>(rem, e, 2, a.bitmap);
-    const f4 p = ld_keep(a.P + e);             // kept in cache for the other replicas' sweeps
-    const f4 g = ld_grad<GT>(static_cast<const GT *>(a.grads) + (long long)w * a.worker_stride + e);
-    const f4 step = g * a.lr;
-    const f4 pn = p - step;
-    if (!MASKED && m == 0xFu) {
-        st_stream(dst, pn);
-    } else if (MASKED && rem >= kVec) {
-        st_stream(dst, blend(m, pn, p));
-    } else {
+    const long long w = blockIdx.y;
+    const float *src = a.P + s.start;
+    const GT *grad = static_cast<const GT *>(a.grads) + w * a.worker_stride + s.start;
+    float *dst = a.Pw + w * a.param_stride + s.start;
+    f4 p[T], g[T];
 #pragma unroll
-        for (int j = 0; j < kVec; ++j)
-            if (m & (1u << j))
-                dst[j] = pn[j];
+    for (int t = 0; t < T; ++t) {
+        const int off = off0 + t * kPiece;
+        if (off < s.n_elems) {
+            p[t] = ld_keep(src + off);         // kept in cache for the other replicas' sweeps
+            g[t] = ld_grad<GT>(grad + off);
+        }
+    }
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        const int off = off0 + t * kPiece;
+        if (off >= s.n_elems)
+            continue;
+        const int rem = s.n_elems - off;
+        const unsigned m = lane_mask<MASKED>(rem, s.start + off, 2, a.bitmap);
+        const f4 step = g[t] * a.lr;
+        const f4 pn = p[t] - step;
+        if (!MASKED && m == 0xFu) {
+            st_stream(dst + off, pn);
+        } else if (MASKED && rem >= kVec) {
+            st_stream(dst + off, blend(m, pn, p[t]));
+        } else {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j)
+                if (m & (1u << j))
+                    dst[off + j] = pn[j];
+        }
     }
 }
 
