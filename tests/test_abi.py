@@ -129,3 +129,46 @@ def test_null_context_is_harmless():
     assert B.lib.osp_workspace_bytes(None) == 0
     B.lib.osp_destroy(None)
     assert B.lib.osp_apply_stage(None, 1, None) == B.OSP_ERR_INVALID_ARG
+
+
+def test_newer_entry_points_validate_before_touching_anything():
+    """Windows, gradient splitter, packed and bfloat16 inputs, reference traffic kernels:
+    NULL context, bad arguments and an unbound context are answered on the host."""
+    L = B.lib
+    assert L.osp_rs_window(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_ics_window(None, 16, 20, 0, 1, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_split_gradients(None, 16, 20, 16, 20, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_ps_aggregate_update_packed(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_ps_aggregate_update_bf16(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_lgp_correct_bf16(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_n_stage2(None, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_windows_fused(None) == 0
+    c = mk()
+    cases = [
+        (lambda: c.osp_rs_window(0, 20, stream=0), B.OSP_ERR_INVALID_ARG),            # NULL grads
+        (lambda: c.osp_rs_window(16, 20, stream=0), B.OSP_ERR_BAD_STATE),             # not bound
+        (lambda: c.osp_ics_window(16, 20, 9, 5, stream=0), B.OSP_ERR_INVALID_ARG),    # granularity
+        (lambda: c.osp_ics_window(16, 20, 0, 18, stream=0), B.OSP_ERR_INVALID_ARG),   # budget > 17
+        (lambda: c.osp_ics_window(16, 20, 1, 5, stream=0), B.OSP_ERR_UNSUPPORTED),    # element keys off
+        (lambda: c.osp_ics_window(16, 20, 0, 5, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_split_gradients(16, 20, 0, 0, 0, 0, stream=0), B.OSP_ERR_INVALID_ARG),
+        (lambda: c.osp_split_gradients(16, 20, 16, 20, 16, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_ps_aggregate_update_packed(0, 16, 20, stream=0), B.OSP_ERR_INVALID_ARG),
+        (lambda: c.osp_ps_aggregate_update_packed(1, 18, 20, stream=0), B.OSP_ERR_INVALID_ARG),
+        (lambda: c.osp_ps_aggregate_update_packed(1, 16, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_ps_aggregate_update_bf16(1, 12, 20, stream=0), B.OSP_ERR_INVALID_ARG),  # 8-byte alignment
+        (lambda: c.osp_ps_aggregate_update_bf16(1, 8, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_lgp_correct_bf16(8, 16, stream=0), B.OSP_ERR_INVALID_ARG),      # stride < arena
+        (lambda: c.osp_lgp_correct_bf16(8, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_n_stage2(), B.OSP_ERR_BAD_STATE),                               # no GIB
+    ]
+    for i, (call, want) in enumerate(cases):
+        with pytest.raises(B.OspError) as e:
+            call()
+        assert e.value.status == want, i
+    # reference kernels: argument checks only (no launch for bad shapes)
+    assert L.osp_stream_pattern(0, 1, 16, 16, 1, 16, 16, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_stream_pattern(16, 0, 16, 16, 1, 16, 16, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_stream_pattern(16, 1, 16, 16, 3, 16, 16, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_stream_pattern(16, 1, 12, 16, 1, 16, 16, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_stream_pattern(16, 1, 16, 16, 1, 16, 18, None) == B.OSP_ERR_INVALID_ARG
