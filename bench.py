@@ -38,13 +38,13 @@ BRACKET_EVERY = 4               # steps between two event-bracketed steps of the
 # HBM bytes per launch of k_aggregate_update on the default workload (VGG-16-shaped, layer
 # granularity, chunk 256), average over the stage-1 and stage-2 launch of a step, from the two
 # rocprofv3 --pmc runs summarised in profiles/sync_step_traffic_vgg16_layer.txt:
-# ((7226989 + 815437) + (2503511 + 282450)) / 2 KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
+# ((7226989 + 815367) + (2503511 + 282449)) / 2 KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
 # 1.0 (what each reads for the 2 GiB k_stream_copy).  Algorithmic: 5534301760.
-AGG_TRAFFIC_VGG16_LAYER = 5544134144
+AGG_TRAFFIC_VGG16_LAYER = 5544097792
 # HBM bytes per launch of k_rs_window_element on VGG-16-shaped, element granularity, --calls windows,
-# from profiles/window_kernels_vgg16_element.txt: (9814932 + 10846454) KiB.  The launch does the work the
+# from profiles/window_kernels_vgg16_element.txt: (9798016 + 10844915) KiB.  The launch does the work the
 # metric counts as stage-1 aggregate + install + LGP (30.4 GB) in one pass over 21.2 GB.
-RS_TRAFFIC_VGG16_ELEMENT = 21157259264
+RS_TRAFFIC_VGG16_ELEMENT = 21138361344
 
 
 def step_bytes(N, M, E2, element, gb=4):
