@@ -12,7 +12,9 @@
  * Memory model
  *   Every buffer is a flat fp32 "arena" of arena_elems elements; tensor
  *   ("layer") l occupies [offset[l], offset[l]+numel[l]).  Elements outside
- *   every tensor are padding and are never written by any call.
+ *   every tensor are padding and are never written by any call.  Offsets need
+ *   to be multiples of 4 elements only; multiples of 1024 (4 KiB) measure 1.5-2 %
+ *   faster per step on MI355X than multiples of 64.
  *   All pointers in osp_buffers and every `grads` argument are DEVICE
  *   pointers owned by the caller and only borrowed: the library never
  *   allocates or frees device memory (osp_bind allocates a few bytes of
