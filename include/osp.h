@@ -269,6 +269,12 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
 osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_stride,
                           int granularity, int64_t budget_elems, void *stream);
 
+/* Both windows back to back on one stream: a whole iteration's synchronization
+ * without overlap (what a benchmark of the arithmetic times; a training loop
+ * puts the next iteration's compute between the two windows instead). */
+osp_status osp_sync_step(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,
+                         int64_t budget_elems, void *stream);
+
 /* Inspection (each synchronizes `stream`): the fp64 layer importances I^l of
  * the last osp_split(LAYER) into imp_host[L]; the element keys (bit pattern of
  * I_k, NaN canonicalised to 0x7FC00000, padding 0xFFFFFFFF) into

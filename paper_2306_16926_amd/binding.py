@@ -94,6 +94,8 @@ def _load() -> C.CDLL:
     lib.osp_rs_window.restype = C.c_int
     lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
     lib.osp_ics_window.restype = C.c_int
+    lib.osp_sync_step.argtypes = [vp, vp, i64, C.c_int, i64, vp]
+    lib.osp_sync_step.restype = C.c_int
     lib.osp_get_importance.argtypes = [vp, vp, vp]
     lib.osp_get_importance.restype = C.c_int
     lib.osp_get_keys.argtypes = [vp, vp, vp]
@@ -123,7 +125,7 @@ lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
-           "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window",
+           "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window", "osp_sync_step",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_ps_aggregate_update_bf16", "osp_lgp_correct_bf16",
            "osp_get_importance", "osp_get_keys",
@@ -288,6 +290,11 @@ class Context:
         self._check(lib.osp_ics_window(self._h, _ptr(grads), int(worker_stride), int(granularity),
                                        int(budget_elems), _stream(stream)))
 
+    def osp_sync_step(self, grads, worker_stride: int, granularity: int, budget_elems: int,
+                      stream=None) -> None:
+        self._check(lib.osp_sync_step(self._h, _ptr(grads), int(worker_stride), int(granularity),
+                                      int(budget_elems), _stream(stream)))
+
     def osp_get_importance(self, stream=None) -> np.ndarray:
         imp = np.zeros(self.n_tensors, np.float64)
         self._check(lib.osp_get_importance(self._h, imp.ctypes.data, _stream(stream)))
@@ -362,3 +369,7 @@ def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):
 
 def osp_ics_window(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
     return ctx.osp_ics_window(grads, worker_stride, granularity, budget_elems, stream)
+
+
+def osp_sync_step(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
+    return ctx.osp_sync_step(grads, worker_stride, granularity, budget_elems, stream)

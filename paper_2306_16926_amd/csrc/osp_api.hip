@@ -1187,6 +1187,25 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
     return osp_split(ctx, granularity, budget_elems, stream);
 }
 
+osp_status osp_sync_step(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,
+                         int64_t budget_elems, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    // the split's arguments are checked before the RS window changes anything
+    if (granularity != OSP_GRAN_LAYER && granularity != OSP_GRAN_ELEMENT)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "unknown granularity %d", granularity);
+    if (budget_elems < 0 || budget_elems > ctx->n_params)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "budget %lld outside [0, %lld]",
+                    (long long)budget_elems, ctx->n_params);
+    if (granularity == OSP_GRAN_ELEMENT && !ctx->element_keys)
+        return fail(ctx, OSP_ERR_UNSUPPORTED, "element granularity needs cfg.element_keys");
+    osp_status st = osp_rs_window(ctx, grads, worker_stride, stream);
+    if (st != OSP_OK)
+        return st;
+    return osp_ics_window(ctx, grads, worker_stride, granularity, budget_elems, stream);
+}
+
 // Build the pack index of the current GIB if it is not there yet (four small launches).
 static osp_status ensure_pack_index(osp_ctx *ctx, hipStream_t s)
 {

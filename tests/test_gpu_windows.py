@@ -364,3 +364,24 @@ def test_tuned_budget_over_epochs(gran):
         sizes.append(o.n_stage2)
     assert sizes[0] == 0 and sizes[-1] > 0
     assert sizes == sorted(sizes)                            # the loss only falls here
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_sync_step_is_both_windows(gran):
+    from paper_2306_16926_amd.binding import OspError
+    say("osp_sync_step", gran)
+    wl = W.custom([5000, 3, 1029, 64, 2048, 30000], 6, 0.5, align=4, config_id=420)
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    for step in range(3):
+        g = wl.make_grads(0, step); gd = job.upload_grads(g)
+        with pytest.raises(OspError):
+            c.osp_sync_step(gd, g.shape[1], gran, wl.n_params + 1)     # nothing may have run
+        compare_state(job, o, f"after a refused call, step {step}")
+        o.sync_step(g, gran, wl.budget)
+        c.osp_sync_step(gd, g.shape[1], gran, wl.budget)
+        compare_state(job, o, f"step {step}")
+        compare_gib(job, o, f"step {step}")
