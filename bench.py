@@ -66,6 +66,9 @@ def step_bytes(N, M, E2, element, gb=4):
 
 def step_calls(mode, c, stride, gran, budget, dense, bf16=False):
     """One sync step as a list of (name, call(g)); names index step_bytes()."""
+    if bf16 and mode == "windows":
+        return [("rs_window", lambda g: c.osp_rs_window_bf16(g, stride)),
+                ("ics_window", lambda g: c.osp_ics_window_bf16(g, stride, gran, budget))]
     if bf16:
         return [("agg1", lambda g: c.osp_ps_aggregate_update_bf16(1, g, stride)),
                 ("apply1", lambda g: c.osp_apply_stage(1)),
@@ -105,7 +108,7 @@ def main() -> int:
                     help="six single-stage calls per step, the RS and ICS window calls, or the "
                          "gradient splitter followed by the six calls with the PS fed by its dense parts")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"],
-                    help="storage type of the gradient arenas (bf16: --calls six only)")
+                    help="storage type of the gradient arenas (bf16: not with --calls packed)")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step as a captured HIP graph (element granularity with "
                          "--calls windows only: no call of such a step needs the host)")
@@ -142,8 +145,8 @@ def main() -> int:
     # two gradient sets, alternated, so a step never re-reads what the last one left in cache
     host_g0 = wl.make_grads(args.seed, 0, stride=stride, threads=args.gen_threads)
     bf16 = args.grad_dtype == "bf16"
-    if bf16 and args.calls != "six":
-        print("bench.py: --grad-dtype bf16 goes with --calls six", file=sys.stderr)
+    if bf16 and args.calls == "packed":
+        print("bench.py: --grad-dtype bf16 goes with --calls six or windows", file=sys.stderr)
         return 2
     gb = 2 if bf16 else 4
     if bf16:                                    # rounded once, on the host; the oracle leg gets the widened values

@@ -237,6 +237,10 @@ osp_status osp_ps_aggregate_update_bf16(osp_ctx *ctx, int stage, const uint16_t 
                                         int64_t worker_stride, void *stream);
 osp_status osp_lgp_correct_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
                                 void *stream);
+/* The two windows (below) for bfloat16 gradient arenas. */
+osp_status osp_rs_window_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride, void *stream);
+osp_status osp_ics_window_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                               int granularity, int64_t budget_elems, void *stream);
 
 /* Workers receive the global parameters of a stage (Sec. 2.1.1); for stage 2
  * this is the correction of Eq. 7, which replaces the local LGP estimate by the

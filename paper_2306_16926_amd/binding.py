@@ -94,6 +94,10 @@ def _load() -> C.CDLL:
     lib.osp_rs_window.restype = C.c_int
     lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
     lib.osp_ics_window.restype = C.c_int
+    lib.osp_rs_window_bf16.argtypes = [vp, vp, i64, vp]
+    lib.osp_rs_window_bf16.restype = C.c_int
+    lib.osp_ics_window_bf16.argtypes = [vp, vp, i64, C.c_int, i64, vp]
+    lib.osp_ics_window_bf16.restype = C.c_int
     lib.osp_sync_step.argtypes = [vp, vp, i64, C.c_int, i64, vp]
     lib.osp_sync_step.restype = C.c_int
     lib.osp_get_importance.argtypes = [vp, vp, vp]
@@ -128,6 +132,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window", "osp_sync_step",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_ps_aggregate_update_bf16", "osp_lgp_correct_bf16",
+           "osp_rs_window_bf16", "osp_ics_window_bf16",
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_stream_pattern", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
@@ -290,6 +295,14 @@ class Context:
         self._check(lib.osp_ics_window(self._h, _ptr(grads), int(worker_stride), int(granularity),
                                        int(budget_elems), _stream(stream)))
 
+    def osp_rs_window_bf16(self, grads, worker_stride: int, stream=None) -> None:
+        self._check(lib.osp_rs_window_bf16(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
+
+    def osp_ics_window_bf16(self, grads, worker_stride: int, granularity: int, budget_elems: int,
+                            stream=None) -> None:
+        self._check(lib.osp_ics_window_bf16(self._h, _ptr(grads), int(worker_stride),
+                                            int(granularity), int(budget_elems), _stream(stream)))
+
     def osp_sync_step(self, grads, worker_stride: int, granularity: int, budget_elems: int,
                       stream=None) -> None:
         self._check(lib.osp_sync_step(self._h, _ptr(grads), int(worker_stride), int(granularity),
@@ -369,6 +382,14 @@ def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):
 
 def osp_ics_window(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
     return ctx.osp_ics_window(grads, worker_stride, granularity, budget_elems, stream)
+
+
+def osp_rs_window_bf16(ctx: Context, grads, worker_stride, stream=None):
+    return ctx.osp_rs_window_bf16(grads, worker_stride, stream)
+
+
+def osp_ics_window_bf16(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
+    return ctx.osp_ics_window_bf16(grads, worker_stride, granularity, budget_elems, stream)
 
 
 def osp_sync_step(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):

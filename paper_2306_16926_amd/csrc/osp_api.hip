@@ -309,6 +309,48 @@ static SweepShape sweep_shape(const osp_ctx *ctx, unsigned n_spans)
     return sh;
 }
 
+template <typename GT>
+static void launch_window_layer_t(const osp_ctx *ctx, const WindowLayerArgs &a, unsigned n_groups,
+                                  hipStream_t s)
+{
+    const dim3 grid(n_groups), block(kBlock);
+    const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    switch (variant) {
+    case 0: k_window_layer<false, false, GT><<<grid, block, 0, s>>>(a); break;
+    case 1: k_window_layer<false, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 2: k_window_layer<true, false, GT><<<grid, block, 0, s>>>(a); break;
+    default: k_window_layer<true, true, GT><<<grid, block, 0, s>>>(a); break;
+    }
+}
+
+static void launch_window_layer(const osp_ctx *ctx, const WindowLayerArgs &a, unsigned n_groups,
+                                hipStream_t s, bool bf16)
+{
+    if (n_groups == 0)
+        return;
+    if (bf16)
+        launch_window_layer_t<bf16_t>(ctx, a, n_groups, s);
+    else
+        launch_window_layer_t<float>(ctx, a, n_groups, s);
+}
+
+template <typename GT>
+static void launch_rs_window_element(const osp_ctx *ctx, const RsElementArgs &a, dim3 grid, hipStream_t s)
+{
+    const dim3 block(kBlock);
+    const int N = ctx->n_workers;
+    const int cap = N <= 4 ? 4 : (N <= 8 ? 8 : 16);
+    if (ctx->weighted) {
+        if (cap == 4) k_rs_window_element<4, true, GT><<<grid, block, 0, s>>>(a);
+        else if (cap == 8) k_rs_window_element<8, true, GT><<<grid, block, 0, s>>>(a);
+        else k_rs_window_element<16, true, GT><<<grid, block, 0, s>>>(a);
+    } else {
+        if (cap == 4) k_rs_window_element<4, false, GT><<<grid, block, 0, s>>>(a);
+        else if (cap == 8) k_rs_window_element<8, false, GT><<<grid, block, 0, s>>>(a);
+        else k_rs_window_element<16, false, GT><<<grid, block, 0, s>>>(a);
+    }
+}
+
 extern "C" {
 
 osp_status osp_create(const osp_config *cfg, osp_ctx **out)
@@ -961,20 +1003,6 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     return OSP_OK;
 }
 
-static void launch_window_layer(osp_ctx *ctx, const WindowLayerArgs &a, unsigned n_groups, hipStream_t s)
-{
-    if (n_groups == 0)
-        return;
-    const dim3 grid(n_groups), block(kBlock);
-    const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
-    switch (variant) {
-    case 0: k_window_layer<false, false><<<grid, block, 0, s>>>(a); break;
-    case 1: k_window_layer<false, true><<<grid, block, 0, s>>>(a); break;
-    case 2: k_window_layer<true, false><<<grid, block, 0, s>>>(a); break;
-    default: k_window_layer<true, true><<<grid, block, 0, s>>>(a); break;
-    }
-}
-
 // Up to this many spans the ranking workgroup fills the stage tables itself (one launch less).
 constexpr int kRankFillMaxSpans = 4096;
 
@@ -990,11 +1018,12 @@ static bool layer_window_fused(const osp_ctx *ctx)
            (long long)ctx->n_workers * ctx->n_params <= kWindowLayerMaxGradElems;
 }
 
-osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+static osp_status rs_window(osp_ctx *ctx, const void *grads, int64_t worker_stride, void *stream,
+                            bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
-    osp_status st = check_grads(ctx, grads, worker_stride);
+    osp_status st = check_grads(ctx, grads, worker_stride, bf16);
     if (st != OSP_OK)
         return st;
     if (!ctx->bound)
@@ -1011,11 +1040,11 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
                        (element ? N <= kRsElementMaxWorkers : layer_window_fused(ctx));
     ctx->windows_fused = fused ? 1 : 0;
     if (!fused) {
-        st = osp_ps_aggregate_update(ctx, 1, grads, worker_stride, stream);
+        st = aggregate_update(ctx, 1, grads, worker_stride, stream, bf16);
         if (st == OSP_OK)
             st = osp_apply_stage(ctx, 1, stream);
         if (st == OSP_OK)
-            st = osp_lgp_correct(ctx, grads, worker_stride, stream);
+            st = lgp_correct(ctx, grads, worker_stride, stream, bf16);
         return st;
     }
     hipStream_t s = (hipStream_t)stream;
@@ -1039,17 +1068,11 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
         a.inv_n = 1.0f / (float)N;
         a.lr = ctx->lr;
         a.mu = ctx->mu;
-        const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
-        const int cap = N <= 4 ? 4 : (N <= 8 ? 8 : 16);
-        if (ctx->weighted) {
-            if (cap == 4) k_rs_window_element<4, true><<<grid, block, 0, s>>>(a);
-            else if (cap == 8) k_rs_window_element<8, true><<<grid, block, 0, s>>>(a);
-            else k_rs_window_element<16, true><<<grid, block, 0, s>>>(a);
-        } else {
-            if (cap == 4) k_rs_window_element<4, false><<<grid, block, 0, s>>>(a);
-            else if (cap == 8) k_rs_window_element<8, false><<<grid, block, 0, s>>>(a);
-            else k_rs_window_element<16, false><<<grid, block, 0, s>>>(a);
-        }
+        const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks);
+        if (bf16)
+            launch_rs_window_element<bf16_t>(ctx, a, grid, s);
+        else
+            launch_rs_window_element<float>(ctx, a, grid, s);
     } else {
         // No wait for the table lengths of a split that may still be running: the launch covers
         // both tables (all spans), and the kernel reads where the first one ends.
@@ -1073,7 +1096,7 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
         a.lr = ctx->lr;
         a.mu = ctx->mu;
         const unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
-        launch_window_layer(ctx, a, n_groups, s);
+        launch_window_layer(ctx, a, n_groups, s, bf16);
     }
     st = launch_check(ctx, "osp_rs_window");
     if (st != OSP_OK)
@@ -1083,18 +1106,28 @@ osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride
     ctx->stash_valid = element;
     ctx->stash_grads = grads;
     ctx->stash_stride = (long long)worker_stride;
-    ctx->stash_bf16 = false;
+    ctx->stash_bf16 = bf16;
     ctx->agg1 = ctx->applied1 = ctx->lgp_done = ctx->last_lgp_shared = true;
     ctx->agg2 = ctx->single_pass = ctx->applied2 = false;
     return OSP_OK;
 }
 
-osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,
-                          int64_t budget_elems, void *stream)
+osp_status osp_rs_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, void *stream)
+{
+    return rs_window(ctx, grads, worker_stride, stream, false);
+}
+
+osp_status osp_rs_window_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride, void *stream)
+{
+    return rs_window(ctx, grads, worker_stride, stream, true);
+}
+
+static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_stride, int granularity,
+                             int64_t budget_elems, void *stream, bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
-    osp_status st = check_grads(ctx, grads, worker_stride);
+    osp_status st = check_grads(ctx, grads, worker_stride, bf16);
     if (st != OSP_OK)
         return st;
     // the split's arguments are checked before anything is launched
@@ -1118,7 +1151,7 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
     ctx->windows_fused = (ctx->windows_fused & 1) | (fused ? 2 : 0);
     hipStream_t s = (hipStream_t)stream;
     if (!fused) {
-        st = osp_ps_aggregate_update(ctx, 2, grads, worker_stride, stream);
+        st = aggregate_update(ctx, 2, grads, worker_stride, stream, bf16);
         if (st == OSP_OK)
             st = osp_apply_stage(ctx, 2, stream);
         if (st != OSP_OK)
@@ -1126,7 +1159,7 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
     } else {
         if (element) {
             const bool from_stash = ctx->stash_valid && ctx->stash_grads == grads &&
-                                    ctx->stash_stride == (long long)worker_stride && !ctx->stash_bf16;
+                                    ctx->stash_stride == (long long)worker_stride && ctx->stash_bf16 == bf16;
             IcsElementArgs a;
             a.spans = ctx->d_spans();
             a.chunk_elems = ctx->chunk_elems;
@@ -1148,6 +1181,10 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
             const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
             if (from_stash)
                 k_ics_window_element<true, false><<<grid, block, 0, s>>>(a);
+            else if (bf16 && ctx->weighted)
+                k_ics_window_element<false, true, bf16_t><<<grid, block, 0, s>>>(a);
+            else if (bf16)
+                k_ics_window_element<false, false, bf16_t><<<grid, block, 0, s>>>(a);
             else if (ctx->weighted)
                 k_ics_window_element<false, true><<<grid, block, 0, s>>>(a);
             else
@@ -1175,7 +1212,7 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
             a.inv_n = 1.0f / (float)N;
             a.lr = ctx->lr;
             a.mu = ctx->mu;
-            launch_window_layer(ctx, a, a.n_agg_groups, s);
+            launch_window_layer(ctx, a, a.n_agg_groups, s, bf16);
         }
         st = launch_check(ctx, "osp_ics_window");
         if (st != OSP_OK)
@@ -1185,6 +1222,18 @@ osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_strid
             ctx->replicas_synced = true;
     }
     return osp_split(ctx, granularity, budget_elems, stream);
+}
+
+osp_status osp_ics_window(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,
+                          int64_t budget_elems, void *stream)
+{
+    return ics_window(ctx, grads, worker_stride, granularity, budget_elems, stream, false);
+}
+
+osp_status osp_ics_window_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                               int granularity, int64_t budget_elems, void *stream)
+{
+    return ics_window(ctx, grads, worker_stride, granularity, budget_elems, stream, true);
 }
 
 osp_status osp_sync_step(osp_ctx *ctx, const float *grads, int64_t worker_stride, int granularity,

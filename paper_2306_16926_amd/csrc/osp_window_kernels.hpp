@@ -34,7 +34,7 @@ struct RsElementArgs {
     const uint32_t *bitmap;
     float *P;
     float *V;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
     const float *weights;
     double *partial1;                  // [n_chunks] importance of stage-1 elements
@@ -47,7 +47,7 @@ struct RsElementArgs {
     float inv_n, lr, mu;
 };
 
-template <int NB, bool WEIGHTED>
+template <int NB, bool WEIGHTED, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_rs_window_element(const RsElementArgs a)
 {
     Piece c;
@@ -56,7 +56,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_window_element(const RsElementArg
     const int N = a.n_workers;
     float *Pc = a.P + c.start;
     float *Vc = a.V + c.start;
-    const float *Gc = a.grads + c.start;
+    const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
     float *Wc = a.Pw + c.start;
     double imp1 = 0.0, imp2 = 0.0;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kBlock) void k_rs_window_element(const RsElementArg
 #pragma unroll
         for (int j = 0; j < NB; ++j)
             if (j < N)
-                g[j] = ld_stream(Gc + (long long)j * a.worker_stride + i);
+                g[j] = ld_grad<GT>(Gc + (long long)j * a.worker_stride + i);
         f4 acc = WEIGHTED ? g[0] * a.weights[0] : g[0];
 #pragma unroll
         for (int j = 1; j < NB; ++j)
@@ -143,7 +143,7 @@ struct IcsElementArgs {
     float *P;
     float *V;
     const float *stash;                // STASH
-    const float *grads;                // !STASH
+    const void *grads;                 // !STASH; fp32 or bfloat16 (GT)
     long long worker_stride;
     const float *weights;
     double *partial2;                  // !STASH
@@ -154,7 +154,7 @@ struct IcsElementArgs {
     float inv_n, lr, mu;
 };
 
-template <bool STASH, bool WEIGHTED>
+template <bool STASH, bool WEIGHTED, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_ics_window_element(const IcsElementArgs a)
 {
     Piece c;
@@ -174,16 +174,16 @@ __global__ __launch_bounds__(kBlock) void k_ics_window_element(const IcsElementA
         if (STASH) {
             gbar = ld_stream(a.stash + c.start + i);
         } else {
-            const float *Gc = a.grads + c.start;
+            const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
             f4 acc;
             int w = 0;
             for (; w + kWorkerBlock <= N; w += kWorkerBlock)
-                add_workers<kWorkerBlock, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights);
+                add_workers<kWorkerBlock, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights);
             const int rest = N - w;
-            if (rest & 8) { add_workers<8, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
-            if (rest & 4) { add_workers<4, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
-            if (rest & 2) { add_workers<2, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
-            if (rest & 1) { add_workers<1, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); }
+            if (rest & 8) { add_workers<8, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
+            if (rest & 4) { add_workers<4, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
+            if (rest & 2) { add_workers<2, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
+            if (rest & 1) { add_workers<1, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); }
             gbar = WEIGHTED ? acc : acc * a.inv_n;
         }
         const f4 prod = gbar * p;
@@ -248,7 +248,7 @@ struct WindowLayerArgs {
     int chunk_elems;
     float *P;
     float *V;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
     const float *weights;
     double *partial;
@@ -275,7 +275,7 @@ __device__ __forceinline__ bool piece_at(const Span *__restrict__ spans, int chu
     return true;
 }
 
-template <bool WEIGHTED, bool KEYS>
+template <bool WEIGHTED, bool KEYS, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a)
 {
     const int N = a.n_workers;
@@ -287,7 +287,7 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
         float *Pc = a.P + c.start;
         float *Vc = a.V + c.start;
         float *Wc = a.Pw + c.start;
-        const float *Gc = a.grads + c.start;
+        const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
         double imp = 0.0;
         for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
             const int rem = (int)c.len - (int)i;
@@ -296,10 +296,10 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
             f4 acc;
             int w = 0;
             const int rest = N;        // N <= 8
-            if (rest & 8) { add_workers<8, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
-            if (rest & 4) { add_workers<4, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
-            if (rest & 2) { add_workers<2, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
-            if (rest & 1) { add_workers<1, WEIGHTED>(acc, w, Gc, a.worker_stride, i, a.weights); }
+            if (rest & 8) { add_workers<8, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 8; }
+            if (rest & 4) { add_workers<4, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 4; }
+            if (rest & 2) { add_workers<2, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); w += 2; }
+            if (rest & 1) { add_workers<1, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights); }
             const f4 gbar = WEIGHTED ? acc : acc * a.inv_n;
             const f4 prod = gbar * p;
             const f4 q = abs4(prod);
@@ -338,7 +338,7 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
             return;
         const float *Pc = a.P + c.start;
         float *Wc = a.Pw + c.start;
-        const float *Gc = a.grads + c.start;
+        const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
         for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
             const int rem = (int)c.len - (int)i;
             const f4 p = ld_stream(Pc + i);
@@ -346,7 +346,7 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
 #pragma unroll
             for (int j = 0; j < kWindowMaxWorkers; ++j)
                 if (j < N)
-                    g[j] = ld_stream(Gc + (long long)j * a.worker_stride + i);
+                    g[j] = ld_grad<GT>(Gc + (long long)j * a.worker_stride + i);
 #pragma unroll
             for (int j = 0; j < kWindowMaxWorkers; ++j)
                 if (j < N) {

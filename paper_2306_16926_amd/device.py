@@ -58,6 +58,11 @@ class DeviceJob:
         c.osp_apply_stage(2)
         c.osp_split(granularity, budget_elems)
 
+    def sync_step_windows_bf16(self, grads: torch.Tensor, granularity: int, budget_elems: int) -> None:
+        c, s = self.ctx, grads.shape[1]
+        c.osp_rs_window_bf16(grads, s)
+        c.osp_ics_window_bf16(grads, s, granularity, budget_elems)
+
     # the six calls of one synchronization step, in the paper's order
     def sync_step(self, grads: torch.Tensor, granularity: int, budget_elems: int) -> None:
         c, s = self.ctx, grads.shape[1]

@@ -141,6 +141,9 @@ def test_newer_entry_points_validate_before_touching_anything():
     assert L.osp_ps_aggregate_update_packed(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_ps_aggregate_update_bf16(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_lgp_correct_bf16(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_rs_window_bf16(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_ics_window_bf16(None, 16, 20, 0, 1, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_sync_step(None, 16, 20, 0, 1, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_n_stage2(None, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_windows_fused(None) == 0
     c = mk()
@@ -161,6 +164,11 @@ def test_newer_entry_points_validate_before_touching_anything():
         (lambda: c.osp_lgp_correct_bf16(8, 16, stream=0), B.OSP_ERR_INVALID_ARG),      # stride < arena
         (lambda: c.osp_lgp_correct_bf16(8, 20, stream=0), B.OSP_ERR_BAD_STATE),
         (lambda: c.osp_n_stage2(), B.OSP_ERR_BAD_STATE),                               # no GIB
+        (lambda: c.osp_rs_window_bf16(12, 20, stream=0), B.OSP_ERR_INVALID_ARG),       # 8-byte alignment
+        (lambda: c.osp_rs_window_bf16(8, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_ics_window_bf16(8, 20, 0, 5, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_sync_step(16, 20, 0, 18, stream=0), B.OSP_ERR_INVALID_ARG),
+        (lambda: c.osp_sync_step(16, 20, 0, 5, stream=0), B.OSP_ERR_BAD_STATE),
     ]
     for i, (call, want) in enumerate(cases):
         with pytest.raises(B.OspError) as e:

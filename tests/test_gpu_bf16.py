@@ -14,7 +14,8 @@ pytestmark = pytest.mark.gpu
 # the bar stays bit equality
 # --------------------------------------------------------------------------
 
-def run_steps_bf16(wl, gran, steps, weights=None, chunk_elems=0, align=None, seed=0, threads=4):
+def run_steps_bf16(wl, gran, steps, weights=None, chunk_elems=0, align=None, seed=0, threads=4,
+                   windows=False):
     o = make_oracle(wl, seed, align, weights)
     job = device_job(wl, seed, align, weights, element_keys=(gran == GRAN_ELEMENT),
                      chunk_elems=chunk_elems)
@@ -26,7 +27,10 @@ def run_steps_bf16(wl, gran, steps, weights=None, chunk_elems=0, align=None, see
         g = W.from_bf16(h)
         gd = job.upload_grads_bf16(h)
         o.sync_step(g, gran, wl.budget)
-        job.sync_step_bf16(gd, gran, wl.budget)
+        if windows:
+            job.sync_step_windows_bf16(gd, gran, wl.budget)
+        else:
+            job.sync_step_bf16(gd, gran, wl.budget)
         compare_state(job, o, f"bf16 {wl.name} step {step}")
         compare_gib(job, o, f"bf16 {wl.name} step {step}")
         sizes.append(o.n_stage2)
@@ -42,6 +46,7 @@ def test_bf16_gradients_tiny(gran, weighted):
     sizes = run_steps_bf16(wl, gran, 3, weights=wts)
     assert sizes[0] > 0
     run_steps_bf16(wl, gran, 2, align=64, chunk_elems=1024)
+    run_steps_bf16(wl, gran, 3, weights=wts, windows=True)
 
 
 @pytest.mark.parametrize("n_workers", [1, 3, 8, 9, 16, 17])
@@ -50,6 +55,8 @@ def test_bf16_gradients_worker_counts(n_workers):
     wl = W.custom([5000, 3, 1029, 64, 2048, 1], n_workers, 0.4, align=4, config_id=240 + n_workers)
     run_steps_bf16(wl, GRAN_LAYER, 2)
     run_steps_bf16(wl, GRAN_ELEMENT, 2)
+    run_steps_bf16(wl, GRAN_LAYER, 3, windows=True)
+    run_steps_bf16(wl, GRAN_ELEMENT, 3, windows=True)
 
 
 def test_bf16_gradients_lgp_paths_nonfinite_and_errors():
@@ -88,3 +95,5 @@ def test_bf16_gradients_cnn_shaped():
     say("bf16 resnet18")
     run_steps_bf16(W.get("resnet18"), GRAN_LAYER, 2, threads=8)
     run_steps_bf16(W.get("resnet18"), GRAN_ELEMENT, 2, threads=8)
+    run_steps_bf16(W.get("resnet18"), GRAN_LAYER, 2, threads=8, windows=True)
+    run_steps_bf16(W.get("resnet18"), GRAN_ELEMENT, 3, threads=8, windows=True)
