@@ -242,7 +242,10 @@ def test_random_call_sequences(seed):
         lgp_done = False
         if rng.random() < 0.4:
             o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
-            c.osp_rs_window(gd, s_)
+            if rng.random() < 0.5:
+                c.osp_rs_window(gd, s_)
+            else:
+                c.osp_rs_window_bf16(hd, s_)
             lgp_done = True
             check(f"it{it} rs_window")
         else:
@@ -262,7 +265,10 @@ def test_random_call_sequences(seed):
         budget = int(rng.choice([0, wl.budget // 3, wl.budget, M]))
         if rng.random() < 0.4:
             o.ps_aggregate_update(2, g); o.apply_stage(2); o.split(split_gran, budget)
-            c.osp_ics_window(gd, s_, split_gran, budget)
+            if rng.random() < 0.5:
+                c.osp_ics_window(gd, s_, split_gran, budget)
+            else:
+                c.osp_ics_window_bf16(hd, s_, split_gran, budget)
             check(f"it{it} ics_window gran{split_gran} budget{budget}")
         else:
             agg(2)
