@@ -51,9 +51,14 @@ def _load() -> C.CDLL:
     # torch first makes libosp.so bind to the runtime torch has already loaded.
     import torch  # noqa: F401
     if not os.path.exists(LIB_PATH):
-        raise ImportError(
-            f"{LIB_PATH} is not built; run `python -c 'import __graft_entry__ as g; g.build()'` "
-            "(there is no CPU fallback)")
+        # nothing built yet: build once (hipcc cross-compiles without a GPU); no CPU fallback
+        try:
+            from . import build as _build
+            _build.build(force=True)
+        except Exception as e:
+            raise ImportError(
+                f"{LIB_PATH} is not built and building it failed ({e}); run "
+                "`python -c 'import __graft_entry__ as g; g.build()'` (there is no CPU fallback)") from e
     lib = C.CDLL(LIB_PATH)
     vp, i64 = C.c_void_p, C.c_int64
     lib.osp_create.argtypes = [C.POINTER(osp_config), C.POINTER(vp)]

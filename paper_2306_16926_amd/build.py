@@ -8,9 +8,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libosp.so")
 SOURCES = [os.path.join(CSRC, "osp_api.hip")]
-HEADERS = [os.path.join(CSRC, "osp_stream_kernels.hpp"),
-           os.path.join(CSRC, "osp_split_kernels.hpp"),
-           os.path.join(os.path.dirname(HERE), "include", "osp.h")]
+HEADERS = [os.path.join(CSRC, h) for h in ("osp_stream_kernels.hpp", "osp_split_kernels.hpp",
+                                            "osp_window_kernels.hpp", "osp_pack_kernels.hpp")]
+HEADERS.append(os.path.join(os.path.dirname(HERE), "include", "osp.h"))
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
