@@ -42,7 +42,7 @@ def test_tiny_chunk_sizes_and_alignment(chunk, align):
     run_steps(W.get("tiny"), GRAN_ELEMENT, 2, align=align, chunk_elems=chunk)
 
 
-@pytest.mark.parametrize("n_workers", [1, 2, 3, 7, 8, 9, 16, 17])
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 7, 8, 9, 16, 17, 33, 40])
 def test_worker_counts(n_workers):
     """Crosses the kernel's blocks of 8 (aggregate) and 4 (LGP) worker streams."""
     say("workers", n_workers)

@@ -26,7 +26,7 @@ def test_windows_tiny_three_chained_steps(gran, weighted):
     run_steps(wl, gran, 2, align=64, chunk_elems=1024, windows=True)
 
 
-@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 8, 9, 16, 17])
+@pytest.mark.parametrize("n_workers", [1, 2, 3, 4, 5, 8, 9, 16, 17, 35])
 def test_windows_worker_counts(n_workers):
     """Fused kernels up to 8 (layer) / 16 (element, RS) workers, single-stage kernels above."""
     say("windows workers", n_workers)
