@@ -610,3 +610,67 @@ def test_learning_rate_schedule(gran):
             o.split(gran, wl.budget); c.osp_split(gran, wl.budget)
         compare_state(job, o, f"lr schedule step {step}")
         compare_gib(job, o, f"lr schedule step {step}")
+
+
+def test_arena_beyond_2_to_31_elements():
+    """A tensor of more than 2^31 elements: every index computation has to be 64-bit.  Too large
+    for the oracle to hold, so the check is the closed form of a BSP step with mu = 0 (P - lr *
+    mean gradient, V = mean gradient), evaluated by separately rounded torch operations on
+    the GPU and compared bit for bit over the whole arena; then the two-stage calls with the small
+    tensor in stage 2."""
+    import torch
+    from paper_2306_16926_amd.binding import Context
+    say("2^31+ elements")
+    big = (1 << 31) + 4096 + 36
+    numel = [big, 1000]
+    off = [0, -(-big // 1024) * 1024]
+    arena = off[1] + 1024
+    N, lr = 2, 0.25
+    stride = arena + 1024
+    dev = torch.device("cuda")
+    ctx = Context(numel, off, arena, N, lr, 0.0)
+    P = torch.empty(arena, dtype=torch.float32, device=dev)
+    step = 1 << 26
+    for a in range(0, arena, step):                       # a ramp that differs across 2^31
+        n = min(step, arena - a)
+        P[a:a + n] = torch.arange(a, a + n, device=dev, dtype=torch.float64).mul_(1e-9).float()
+    P0 = P.clone()
+    V = torch.zeros(arena, dtype=torch.float32, device=dev)
+    Pw = torch.zeros((N, stride), dtype=torch.float32, device=dev)
+    Pw[:, :arena] = P
+    ws = torch.empty(ctx.osp_workspace_bytes(), dtype=torch.uint8, device=dev)
+    ctx.osp_bind(P, V, Pw, stride, ws, replicas_in_sync=True)
+    g = torch.empty((N, stride), dtype=torch.float32, device=dev)
+    g[0].fill_(0.5); g[1].fill_(-0.25)
+    g[0, big - 7:big] = 3.0                                # the tail of the big tensor, beyond 2^31
+    g[1, 5] = 8.0
+    ctx.osp_set_gib(0, np.array([1, 0], np.uint8))         # small tensor in stage 2
+    gbar = (g[0, :arena] + g[1, :arena]) * 0.5             # sum, then times fl(1/2): exact here
+    want_P = P0 - gbar * lr                                # two separately rounded operations
+    want_P[big:off[1]] = P0[big:off[1]]; want_P[off[1] + 1000:] = P0[off[1] + 1000:]   # padding untouched
+    ctx.osp_ps_aggregate_update(1, g, stride)
+    ctx.osp_apply_stage(1)
+    ctx.osp_lgp_correct(g, stride)
+    torch.cuda.synchronize()
+    assert torch.equal(P[:big], want_P[:big])
+    assert torch.equal(P[big:], P0[big:])                  # stage 2 and padding not yet touched
+    assert torch.equal(Pw[0, :big], want_P[:big]) and torch.equal(Pw[1, :big], want_P[:big])
+    lgp1 = P0[off[1]:off[1] + 1000] - g[1, off[1]:off[1] + 1000] * lr
+    assert torch.equal(Pw[1, off[1]:off[1] + 1000], lgp1)
+    ctx.osp_ps_aggregate_update(2, g, stride)
+    ctx.osp_apply_stage(2)
+    torch.cuda.synchronize()
+    assert torch.equal(P, want_P)
+    assert torch.equal(V[:big], gbar[:big]) and torch.equal(V[off[1]:off[1] + 1000], gbar[off[1]:off[1] + 1000])
+    assert torch.equal(Pw[0, :arena], want_P) and torch.equal(Pw[1, :arena], want_P)
+    assert bool((Pw[:, arena:] == 0).all())
+    # the split sees the big tensor's importance as the larger one: budget of 1000 picks the small tensor
+    ctx.osp_split(0, 1000)
+    layer, _, n2 = ctx.osp_get_gib()
+    assert layer.tolist() == [1, 0] and n2 == 1000
+    imp = ctx.osp_get_importance()
+    want_imp = 0.0
+    for a in range(0, big, step):                          # |fl(gbar * P)| summed in fp64, in pieces
+        b = min(big, a + step)
+        want_imp += (gbar[a:b] * P0[a:b]).abs().double().sum().item()
+    assert abs(imp[0] - want_imp) <= 1e-9 * want_imp
