@@ -60,12 +60,21 @@ def step_bytes(N, M, E2, element, gb=4):
         b["split"] = 4 * M + M // 8
     b["rs_window"] = b["agg1"] + b["apply1"] + b["lgp"]
     b["ics_window"] = b["agg2"] + b["apply2"] + b["split"]
-    b["split_gradients"] = 8 * N * M        # every gradient read once, written once
+    b["split_gradients"] = 2 * gb * N * M   # every gradient read once, written once
     return b
 
 
 def step_calls(mode, c, stride, gran, budget, dense, bf16=False):
     """One sync step as a list of (name, call(g)); names index step_bytes()."""
+    if bf16 and mode == "packed":
+        gi, gu, ds = dense
+        return [("split_gradients", lambda g: c.osp_split_gradients_bf16(g, stride, gi, ds, gu, ds)),
+                ("agg1", lambda g: c.osp_ps_aggregate_update_packed_bf16(1, gi, ds)),
+                ("apply1", lambda g: c.osp_apply_stage(1)),
+                ("lgp", lambda g: c.osp_lgp_correct_bf16(g, stride)),
+                ("agg2", lambda g: c.osp_ps_aggregate_update_packed_bf16(2, gu, ds)),
+                ("apply2", lambda g: c.osp_apply_stage(2)),
+                ("split", lambda g: c.osp_split(gran, budget))]
     if bf16 and mode == "windows":
         return [("rs_window", lambda g: c.osp_rs_window_bf16(g, stride)),
                 ("ics_window", lambda g: c.osp_ics_window_bf16(g, stride, gran, budget))]
@@ -108,7 +117,7 @@ def main() -> int:
                     help="six single-stage calls per step, the RS and ICS window calls, or the "
                          "gradient splitter followed by the six calls with the PS fed by its dense parts")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"],
-                    help="storage type of the gradient arenas (bf16: not with --calls packed)")
+                    help="storage type of the gradient arenas (and of the splitter's dense parts)")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step as a captured HIP graph (element granularity with "
                          "--calls windows only: no call of such a step needs the host)")
@@ -145,9 +154,6 @@ def main() -> int:
     # two gradient sets, alternated, so a step never re-reads what the last one left in cache
     host_g0 = wl.make_grads(args.seed, 0, stride=stride, threads=args.gen_threads)
     bf16 = args.grad_dtype == "bf16"
-    if bf16 and args.calls == "packed":
-        print("bench.py: --grad-dtype bf16 goes with --calls six or windows", file=sys.stderr)
-        return 2
     gb = 2 if bf16 else 4
     if bf16:                                    # rounded once, on the host; the oracle leg gets the widened values
         h = W.to_bf16(host_g0)
@@ -172,8 +178,9 @@ def main() -> int:
     dense = None
     if mode == "packed":
         ds = -(-M // 64) * 64 + 64
-        dense = (torch.empty((N, ds), dtype=torch.float32, device="cuda"),
-                 torch.empty((N, ds), dtype=torch.float32, device="cuda"), ds)
+        dense_dtype = torch.int16 if bf16 else torch.float32
+        dense = (torch.empty((N, ds), dtype=dense_dtype, device="cuda"),
+                 torch.empty((N, ds), dtype=dense_dtype, device="cuda"), ds)
     calls_of_step = step_calls(mode, c, stride, gran, wl.budget, dense, bf16)
     for i in range(Wm):
         for _, call in calls_of_step:

@@ -215,6 +215,17 @@ osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_
 osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *packed,
                                           int64_t packed_stride, void *stream);
 
+/* The two calls above for bfloat16 gradient arenas (see the _bf16 calls below):
+ * the dense parts hold bfloat16 as well, the same 16 bits moved, 2-byte
+ * aligned; the packed aggregate widens them exactly and then is the fp32
+ * arithmetic, so results equal those of the fp32 calls on the widened values. */
+osp_status osp_split_gradients_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                                    uint16_t *g_important, int64_t important_stride,
+                                    uint16_t *g_unimportant, int64_t unimportant_stride,
+                                    void *stream);
+osp_status osp_ps_aggregate_update_packed_bf16(osp_ctx *ctx, int stage, const uint16_t *packed,
+                                               int64_t packed_stride, void *stream);
+
 /* LGP (Sec. 4.2, Eq. 6): for every stage-2 element and every worker,
  * P_{w,k} = P_{w,k} - lr g_{w,k}: the stale parameter advances by the worker's
  * own local gradient.  Stage-1 elements are not touched. */

@@ -95,6 +95,10 @@ def _load() -> C.CDLL:
     lib.osp_split_gradients.restype = C.c_int
     lib.osp_ps_aggregate_update_packed.argtypes = [vp, C.c_int, vp, i64, vp]
     lib.osp_ps_aggregate_update_packed.restype = C.c_int
+    lib.osp_split_gradients_bf16.argtypes = [vp, vp, i64, vp, i64, vp, i64, vp]
+    lib.osp_split_gradients_bf16.restype = C.c_int
+    lib.osp_ps_aggregate_update_packed_bf16.argtypes = [vp, C.c_int, vp, i64, vp]
+    lib.osp_ps_aggregate_update_packed_bf16.restype = C.c_int
     lib.osp_rs_window.argtypes = [vp, vp, i64, vp]
     lib.osp_rs_window.restype = C.c_int
     lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
@@ -136,6 +140,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window", "osp_sync_step",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
+           "osp_split_gradients_bf16", "osp_ps_aggregate_update_packed_bf16",
            "osp_ps_aggregate_update_bf16", "osp_lgp_correct_bf16",
            "osp_rs_window_bf16", "osp_ics_window_bf16",
            "osp_get_importance", "osp_get_keys",
@@ -292,6 +297,18 @@ class Context:
         self._check(lib.osp_ps_aggregate_update_packed(self._h, stage, _ptr(packed),
                                                        int(packed_stride), _stream(stream)))
 
+    def osp_split_gradients_bf16(self, grads, worker_stride: int, g_important, important_stride: int,
+                                 g_unimportant, unimportant_stride: int, stream=None) -> None:
+        self._check(lib.osp_split_gradients_bf16(self._h, _ptr(grads), int(worker_stride),
+                                                 _ptr(g_important), int(important_stride),
+                                                 _ptr(g_unimportant), int(unimportant_stride),
+                                                 _stream(stream)))
+
+    def osp_ps_aggregate_update_packed_bf16(self, stage: int, packed, packed_stride: int,
+                                            stream=None) -> None:
+        self._check(lib.osp_ps_aggregate_update_packed_bf16(self._h, stage, _ptr(packed),
+                                                            int(packed_stride), _stream(stream)))
+
     def osp_rs_window(self, grads, worker_stride: int, stream=None) -> None:
         self._check(lib.osp_rs_window(self._h, _ptr(grads), int(worker_stride), _stream(stream)))
 
@@ -379,6 +396,16 @@ def osp_split_gradients(ctx: Context, grads, worker_stride, g_important, importa
 
 def osp_ps_aggregate_update_packed(ctx: Context, stage, packed, packed_stride, stream=None):
     return ctx.osp_ps_aggregate_update_packed(stage, packed, packed_stride, stream)
+
+
+def osp_split_gradients_bf16(ctx: Context, grads, worker_stride, g_important, important_stride,
+                             g_unimportant, unimportant_stride, stream=None):
+    return ctx.osp_split_gradients_bf16(grads, worker_stride, g_important, important_stride,
+                                        g_unimportant, unimportant_stride, stream)
+
+
+def osp_ps_aggregate_update_packed_bf16(ctx: Context, stage, packed, packed_stride, stream=None):
+    return ctx.osp_ps_aggregate_update_packed_bf16(stage, packed, packed_stride, stream)
 
 
 def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):

@@ -351,6 +351,18 @@ static void launch_rs_window_element(const osp_ctx *ctx, const RsElementArgs &a,
     }
 }
 
+template <typename GT>
+static void launch_aggregate_packed(int variant, dim3 grid, dim3 block, hipStream_t s,
+                                    const PackedAggArgs &a)
+{
+    switch (variant) {
+    case 0: k_aggregate_update_packed<false, false, GT><<<grid, block, 0, s>>>(a); break;
+    case 1: k_aggregate_update_packed<false, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 2: k_aggregate_update_packed<true, false, GT><<<grid, block, 0, s>>>(a); break;
+    default: k_aggregate_update_packed<true, true, GT><<<grid, block, 0, s>>>(a); break;
+    }
+}
+
 extern "C" {
 
 osp_status osp_create(const osp_config *cfg, osp_ctx **out)
@@ -1003,9 +1015,6 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     return OSP_OK;
 }
 
-// Up to this many spans the ranking workgroup fills the stage tables itself (one launch less).
-constexpr int kRankFillMaxSpans = 4096;
-
 // Largest N for which the element-granular RS window keeps all gradients of a group in registers.
 constexpr int kRsElementMaxWorkers = 16;
 // Layer-granular windows run fused up to this many gradient elements (N x parameters): measured
@@ -1285,17 +1294,22 @@ static osp_status ensure_pack_index(osp_ctx *ctx, hipStream_t s)
     return OSP_OK;
 }
 
-osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_stride,
-                               float *g_important, int64_t important_stride,
-                               float *g_unimportant, int64_t unimportant_stride, void *stream)
+static osp_status split_gradients(osp_ctx *ctx, const void *grads, int64_t worker_stride,
+                                  void *g_important, int64_t important_stride,
+                                  void *g_unimportant, int64_t unimportant_stride, void *stream,
+                                  bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
-    osp_status st = check_grads(ctx, grads, worker_stride);
+    osp_status st = check_grads(ctx, grads, worker_stride, bf16);
     if (st != OSP_OK)
         return st;
     if (!g_important && !g_unimportant)
         return fail(ctx, OSP_ERR_INVALID_ARG, "both outputs are NULL");
+    const uintptr_t elem = bf16 ? 2 : 4;
+    if (reinterpret_cast<uintptr_t>(g_important) % elem != 0 ||
+        reinterpret_cast<uintptr_t>(g_unimportant) % elem != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "outputs must be %d-byte aligned", (int)elem);
     if (!ctx->bound)
         return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
     if (!ctx->have_gib)
@@ -1329,16 +1343,40 @@ osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_
     const unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
     for (int w0 = 0; w0 < ctx->n_workers; w0 += 65535) {   // grid.y is limited to 65535
         const int nw = ctx->n_workers - w0 < 65535 ? ctx->n_workers - w0 : 65535;
-        a.grads = grads + (long long)w0 * worker_stride;
-        a.g_i = g_important ? g_important + (long long)w0 * important_stride : nullptr;
-        a.g_u = g_unimportant ? g_unimportant + (long long)w0 * unimportant_stride : nullptr;
-        k_split_gradients<<<dim3(n_groups, (unsigned)nw), kBlock, 0, s>>>(a);
+        const long long esz = (long long)elem;
+        a.grads = static_cast<const char *>(grads) + (long long)w0 * worker_stride * esz;
+        a.g_i = g_important ? static_cast<char *>(g_important) + (long long)w0 * important_stride * esz
+                            : nullptr;
+        a.g_u = g_unimportant
+                    ? static_cast<char *>(g_unimportant) + (long long)w0 * unimportant_stride * esz
+                    : nullptr;
+        if (bf16)
+            k_split_gradients<bf16_t><<<dim3(n_groups, (unsigned)nw), kBlock, 0, s>>>(a);
+        else
+            k_split_gradients<float><<<dim3(n_groups, (unsigned)nw), kBlock, 0, s>>>(a);
     }
     return launch_check(ctx, "k_split_gradients");
 }
 
-osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *packed,
-                                          int64_t packed_stride, void *stream)
+osp_status osp_split_gradients(osp_ctx *ctx, const float *grads, int64_t worker_stride,
+                               float *g_important, int64_t important_stride,
+                               float *g_unimportant, int64_t unimportant_stride, void *stream)
+{
+    return split_gradients(ctx, grads, worker_stride, g_important, important_stride, g_unimportant,
+                           unimportant_stride, stream, false);
+}
+
+osp_status osp_split_gradients_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t worker_stride,
+                                    uint16_t *g_important, int64_t important_stride,
+                                    uint16_t *g_unimportant, int64_t unimportant_stride,
+                                    void *stream)
+{
+    return split_gradients(ctx, grads, worker_stride, g_important, important_stride, g_unimportant,
+                           unimportant_stride, stream, true);
+}
+
+static osp_status aggregate_update_packed(osp_ctx *ctx, int stage, const void *packed,
+                                          int64_t packed_stride, void *stream, bool bf16)
 {
     if (!ctx)
         return OSP_ERR_INVALID_ARG;
@@ -1346,8 +1384,8 @@ osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *
         return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 1 or 2 (got %d)", stage);
     if (!packed)
         return fail(ctx, OSP_ERR_INVALID_ARG, "packed is NULL");
-    if (reinterpret_cast<uintptr_t>(packed) % 4 != 0)
-        return fail(ctx, OSP_ERR_INVALID_ARG, "packed must be 4-byte aligned");
+    if (reinterpret_cast<uintptr_t>(packed) % (bf16 ? 2 : 4) != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "packed must be %d-byte aligned", bf16 ? 2 : 4);
     if (!ctx->bound)
         return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
     if (!ctx->have_gib)
@@ -1393,12 +1431,10 @@ osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *
     // both stages' importance partials of every chunk, so each call has to leave its own
     if (need > 0 || a.element) {
         const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
-        switch (variant) {
-        case 0: k_aggregate_update_packed<false, false><<<grid, block, 0, s>>>(a); break;
-        case 1: k_aggregate_update_packed<false, true><<<grid, block, 0, s>>>(a); break;
-        case 2: k_aggregate_update_packed<true, false><<<grid, block, 0, s>>>(a); break;
-        default: k_aggregate_update_packed<true, true><<<grid, block, 0, s>>>(a); break;
-        }
+        if (bf16)
+            launch_aggregate_packed<bf16_t>(variant, grid, block, s, a);
+        else
+            launch_aggregate_packed<float>(variant, grid, block, s, a);
     }
     st = launch_check(ctx, "k_aggregate_update_packed");
     if (st != OSP_OK)
@@ -1413,6 +1449,18 @@ osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *
         ctx->agg2 = true;
     }
     return OSP_OK;
+}
+
+osp_status osp_ps_aggregate_update_packed(osp_ctx *ctx, int stage, const float *packed,
+                                          int64_t packed_stride, void *stream)
+{
+    return aggregate_update_packed(ctx, stage, packed, packed_stride, stream, false);
+}
+
+osp_status osp_ps_aggregate_update_packed_bf16(osp_ctx *ctx, int stage, const uint16_t *packed,
+                                               int64_t packed_stride, void *stream)
+{
+    return aggregate_update_packed(ctx, stage, packed, packed_stride, stream, true);
 }
 
 osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream)

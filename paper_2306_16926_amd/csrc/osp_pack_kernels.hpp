@@ -195,40 +195,103 @@ struct SplitGradArgs {
     int element;
     const long long *base1;
     const long long *base2;
-    const float *grads;
+    const void *grads;                 // fp32 or bfloat16 arenas
     long long worker_stride;
-    float *g_i;                        // or null
+    void *g_i;                         // or null; same element type as grads
     long long stride_i;
-    float *g_u;                        // or null
+    void *g_u;                         // or null
     long long stride_u;
 };
 
+// The splitter moves values as they are stored: a lane's 4 consecutive elements are one
+// 16-byte (fp32) or 8-byte (bfloat16) group.
+template <typename GT> struct GroupOf;
+template <> struct GroupOf<float> { using type = f4; };
+template <> struct GroupOf<bf16_t> { using type = u2; };
+
+__device__ __forceinline__ f4 get_group(const float *src) { return ld_stream(src); }
+__device__ __forceinline__ void put_group(float *dst, f4 v) { st_stream(dst, v); }
+__device__ __forceinline__ float group_elem(f4 v, int j) { return v[j]; }
+__device__ __forceinline__ u2 get_group(const bf16_t *src)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u2 *>(src));
+}
+__device__ __forceinline__ void put_group(bf16_t *dst, u2 v)
+{
+    __builtin_nontemporal_store(v, reinterpret_cast<u2 *>(dst));
+}
+__device__ __forceinline__ bf16_t group_elem(u2 v, int j)
+{
+    return (bf16_t)(v[j >> 1] >> ((j & 1) * 16));
+}
+
+template <typename GT>
 __global__ __launch_bounds__(kBlock) void k_split_gradients(const SplitGradArgs a)
 {
-    Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
+    using group_t = typename GroupOf<GT>::type;
+    // A workgroup lives for one short chain of dependent loads, so the chain is kept flat:
+    // the span entry, then data, pack index and bitmap word together.
+    const int span_idx = blockIdx.x / kSpanChunks;
+    const Span sp = a.spans[span_idx];
+    const int jchunk = blockIdx.x % kSpanChunks;
+    const int off = jchunk * a.chunk_elems;
+    if (off >= sp.n_elems)
         return;
-    const bool important = a.element ? false : a.gib_layer[a.span_layer[blockIdx.x / kSpanChunks]] != 0;
+    const long long start = sp.start + off;
+    const unsigned len = (unsigned)(sp.n_elems - off < a.chunk_elems ? sp.n_elems - off : a.chunk_elems);
+    const int chunk = sp.chunk_base + jchunk;
     const long long w = blockIdx.y;
-    const float *G = a.grads + w * a.worker_stride + c.start;
-    float *out1 = a.g_i ? a.g_i + w * a.stride_i + a.base1[c.chunk] : nullptr;
-    float *out2 = a.g_u ? a.g_u + w * a.stride_u + a.base2[c.chunk] : nullptr;
-    // The 4 elements of a lane land at consecutive dense positions, but those are not 16-byte
-    // aligned in general, and four 4-byte stores per lane would each touch every line of the run
-    // a little.  So a pass (256 elements) is put in dense order in LDS first and written out with
-    // lane k storing element k, k+64, ...: every store instruction covers 256 consecutive bytes.
-    __shared__ float dense1[kStride], dense2[kStride];
+    const GT *G = static_cast<const GT *>(a.grads) + w * a.worker_stride + start;
+    const unsigned i_first = threadIdx.x * kVec;
+    // (a group that straddles the tensor's end is read whole: tensors start on multiples of
+    // 4 elements, so the bytes are inside the arena)
+    group_t next = {};
+    if (i_first < len)
+        next = get_group(G + i_first);
+    const long long b1 = a.base1[chunk], b1_next = a.base1[chunk + 1], b2 = a.base2[chunk];
+    asm volatile("" ::"s"(b2));        // (requested here, with the others, not where it is used)
+    // layer-granular GIB: a chunk lies in one stage, and the pack index says which
+    const bool layer_important = b1_next != b1;
+    GT *out1 = a.g_i ? static_cast<GT *>(a.g_i) + w * a.stride_i + b1 : nullptr;
+    GT *out2 = a.g_u ? static_cast<GT *>(a.g_u) + w * a.stride_u + b2 : nullptr;
+    if (!a.element) {
+        // Layer-granular GIB: the whole chunk goes to one part, at consecutive positions.  Where
+        // that run starts on a lane's 4-element boundary (tensor sizes that are multiples of 4:
+        // the usual case) this is a plain copy with full-width loads and stores.
+        GT *out = layer_important ? out1 : out2;
+        if (!out)
+            return;
+        if ((reinterpret_cast<uintptr_t>(out) & (4 * sizeof(GT) - 1)) == 0) {
+            for (unsigned i = i_first; i < len; i += kStride) {
+                const group_t cur = next;
+                if (i + kStride < len)
+                    next = get_group(G + i + kStride);
+                if (len - i >= (unsigned)kVec)
+                    put_group(out + i, cur);
+                else
+                    for (unsigned j = 0; j < len - i; ++j)
+                        out[i + j] = group_elem(cur, (int)j);
+            }
+            return;
+        }
+    }
+    // The 4 elements of a lane land at consecutive dense positions, but those are not aligned
+    // to the group in general, and four single-element stores per lane would each touch every
+    // line of the run a little.  So a pass (256 elements) is put in dense order in LDS first and
+    // written out with lane k storing element k, k+64, ...: every store instruction covers
+    // consecutive bytes.
+    __shared__ GT dense1[kStride], dense2[kStride];
     unsigned carry1 = 0, carry2 = 0;   // elements of each stage in earlier passes over the chunk
     // every lane takes every pass (inactive ones count nothing): the prefix sum is wave-wide
-    for (unsigned i0 = 0; i0 < (unsigned)c.len; i0 += kStride) {
-        const unsigned i = i0 + threadIdx.x * kVec;
-        const int rem = (int)c.len - (int)i;
+    for (unsigned i0 = 0; i0 < len; i0 += kStride) {
+        const unsigned i = i0 + i_first;
+        const int rem = (int)len - (int)i;
+        const group_t cur = next;
+        if (i + kStride < len)
+            next = get_group(G + i + kStride);
         unsigned first = 0, valid = 0;
-        f4 g = {0.f, 0.f, 0.f, 0.f};
-        if (rem > 0) {
-            group_stages(a.element != 0, important, rem, c.start + i, a.bitmap, first, valid);
-            g = ld_stream(G + i);
-        }
+        if (rem > 0)
+            group_stages(a.element != 0, layer_important, rem, start + i, a.bitmap, first, valid);
         const unsigned second = valid & ~first;
         const unsigned mine = (unsigned)__popc(first) | ((unsigned)__popc(second) << 16);
         const unsigned incl = wave_scan_pair(mine);
@@ -237,9 +300,9 @@ __global__ __launch_bounds__(kBlock) void k_split_gradients(const SplitGradArgs 
 #pragma unroll
         for (int j = 0; j < kVec; ++j) {
             if (first & (1u << j))
-                dense1[p1++] = g[j];
+                dense1[p1++] = group_elem(cur, j);
             else if (second & (1u << j))
-                dense2[p2++] = g[j];
+                dense2[p2++] = group_elem(cur, j);
         }
         const unsigned tot = __shfl(incl, 63, 64);
         const unsigned n1 = tot & 0xFFFFu, n2 = tot >> 16;
@@ -270,7 +333,7 @@ struct PackedAggArgs {
     const long long *base;             // pack index of this stage
     float *P;
     float *V;
-    const float *packed;
+    const void *packed;                // fp32 or bfloat16 dense arrays
     long long packed_stride;
     const float *weights;
     double *partial;
@@ -280,7 +343,20 @@ struct PackedAggArgs {
     float inv_n, lr, mu;
 };
 
-template <bool WEIGHTED, bool KEYS>
+template <typename GT>
+__device__ __forceinline__ float ld_packed(const GT *p);
+template <>
+__device__ __forceinline__ float ld_packed<float>(const float *p)
+{
+    return __builtin_nontemporal_load(p);
+}
+template <>
+__device__ __forceinline__ float ld_packed<bf16_t>(const bf16_t *p)
+{
+    return __uint_as_float((unsigned)__builtin_nontemporal_load(p) << 16);
+}
+
+template <bool WEIGHTED, bool KEYS, typename GT>
 __global__ __launch_bounds__(kBlock) void k_aggregate_update_packed(const PackedAggArgs a)
 {
     Piece c;
@@ -292,11 +368,18 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update_packed(const Packed
             a.partial[c.chunk] = 0.0;
         return;
     }
-    const bool important = a.element ? false : a.gib_layer[a.span_layer[blockIdx.x / kSpanChunks]] != 0;
+    // layer-granular GIB: a chunk lies in one stage, so one that has elements of this stage
+    // lies in it whole
+    const bool important = a.stage == 1;
     const int N = a.n_workers;
     float *Pc = a.P + c.start;
     float *Vc = a.V + c.start;
-    const float *src = a.packed + base;
+    const GT *src = static_cast<const GT *>(a.packed) + base;
+    // Layer-granular GIB: the chunk's elements sit at consecutive positions from src; if every
+    // worker's run starts on a lane's 4-element boundary they are read with full-width loads.
+    const bool dense_run = !a.element;
+    const bool wide = dense_run && (reinterpret_cast<uintptr_t>(src) & (4 * sizeof(GT) - 1)) == 0 &&
+                      (a.packed_stride & 3) == 0;
     double imp = 0.0;
     unsigned carry = 0;
     for (unsigned i0 = 0; i0 < (unsigned)c.len; i0 += kStride) {
@@ -306,10 +389,13 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update_packed(const Packed
         if (rem > 0)
             group_stages(a.element != 0, important, rem, c.start + i, a.bitmap, first, valid);
         const unsigned m = a.stage == 1 ? first : (valid & ~first);
-        const unsigned mine = (unsigned)__popc(m);
-        const unsigned incl = wave_scan_pair(mine);
-        const unsigned pos = carry + incl - mine;
-        carry += __shfl(incl, 63, 64);
+        unsigned pos = i;
+        if (!dense_run) {
+            const unsigned mine = (unsigned)__popc(m);
+            const unsigned incl = wave_scan_pair(mine);
+            pos = carry + incl - mine;
+            carry += __shfl(incl, 63, 64);
+        }
         if (rem <= 0)
             continue;                  // (this lane; the next pass's scan is still wave-wide)
         // slot of component j inside this lane's run of the dense array
@@ -318,12 +404,16 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update_packed(const Packed
         const f4 v = ld_stream(Vc + i);
         f4 acc = {0.f, 0.f, 0.f, 0.f};
         for (int w = 0; w < N; ++w) {
-            const float *s = src + (long long)w * a.packed_stride + pos;
+            const GT *s = src + (long long)w * a.packed_stride + pos;
             f4 g = {0.f, 0.f, 0.f, 0.f};
-            if (m & 1u) g.x = __builtin_nontemporal_load(s);
-            if (m & 2u) g.y = __builtin_nontemporal_load(s + r1);
-            if (m & 4u) g.z = __builtin_nontemporal_load(s + r2);
-            if (m & 8u) g.w = __builtin_nontemporal_load(s + r3);
+            if (wide && rem >= kVec) {
+                g = ld_grad<GT>(s);
+            } else {
+                if (m & 1u) g.x = ld_packed<GT>(s);
+                if (m & 2u) g.y = ld_packed<GT>(s + r1);
+                if (m & 4u) g.z = ld_packed<GT>(s + r2);
+                if (m & 8u) g.w = ld_packed<GT>(s + r3);
+            }
             if (WEIGHTED)
                 g = g * a.weights[w];
             acc = w == 0 ? g : acc + g;

@@ -116,6 +116,8 @@ __device__ __forceinline__ unsigned long long importance_rank_key(double x)
 }
 
 constexpr int kRankBlock = 1024;
+// Up to this many spans the ranking workgroup fills the stage tables itself (one launch less).
+constexpr int kRankFillMaxSpans = 4096;
 
 // Exclusive scan of one value per thread over a workgroup of BLOCK threads, in
 // thread order (shuffles inside a wavefront, wavefront totals through LDS).
@@ -293,15 +295,41 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
     Span *__restrict__ list_s1, Span *__restrict__ list_s2)
 {
     __shared__ __align__(16) unsigned long long key[kRankTile];
-    __shared__ long long size_by_rank[kRankTile];
+    __shared__ long long numel_of_layer[kRankTile];
     __shared__ int sorted_layer[kRankTile];
     __shared__ int base_of_layer[kRankTile];
+    __shared__ int first_span_of_layer[kRankTile];
     __shared__ uint8_t important_layer[kRankTile];
     __shared__ long long n_stage2_found;
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int n = 1;
     while (n < L)
         n <<= 1;
+
+    // Everything the later phases read from global memory that does not depend on the ranking
+    // is requested here, so that its latency passes behind the importance sums and the sort
+    // instead of adding one round trip per phase (the kernel is a chain of short phases).
+    constexpr int kLayersPer = kRankTile / BLOCK, kSpansPer = kRankFillMaxSpans / BLOCK;
+    static_assert(kRankTile % BLOCK == 0 && kRankFillMaxSpans % BLOCK == 0, "whole rounds per thread");
+    long long my_numel[kLayersPer];
+    int my_first[kLayersPer], my_end[kLayersPer];
+#pragma unroll
+    for (int rep = 0; rep < kLayersPer; ++rep) {
+        const int l = rep * BLOCK + (int)threadIdx.x;
+        my_numel[rep] = l < L ? numel[l] : 0;
+        my_first[rep] = l < L ? layer_span_begin[l] : 0;
+        my_end[rep] = l < L ? layer_span_begin[l + 1] : 0;
+    }
+    Span my_span[kSpansPer];
+    int my_span_layer[kSpansPer];
+#pragma unroll
+    for (int j = 0; j < kSpansPer; ++j) {
+        const int k = j * BLOCK + (int)threadIdx.x;
+        if (k < n_spans) {
+            my_span[j] = spans[k];
+            my_span_layer[j] = span_layer[k];
+        }
+    }
 
     // I^l (same two summation schemes as k_layer_rank), straight into the sort keys
     for (int l = threadIdx.x; l < n; l += BLOCK) {
@@ -352,19 +380,25 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
             __syncthreads();
         }
 
-    const int per = (L + BLOCK - 1) / BLOCK;
-    for (int r = threadIdx.x; r < L; r += BLOCK) {
-        const int l = sorted_layer[r];
-        order[r] = l;
-        size_by_rank[r] = numel[l];
+#pragma unroll
+    for (int rep = 0; rep < kLayersPer; ++rep) {
+        const int l = rep * BLOCK + (int)threadIdx.x;
+        if (l < L) {
+            numel_of_layer[l] = my_numel[rep];
+            first_span_of_layer[l] = my_first[rep];
+            order[l] = sorted_layer[l];     // (position l of the ranking)
+        }
     }
     __syncthreads();
 
     // running size along the ranking (sizes are positive: "fits" holds exactly on a prefix)
     long long carry = 0;
-    for (int rep = 0; rep < per; ++rep) {
+#pragma unroll
+    for (int rep = 0; rep < kLayersPer; ++rep) {
+        if (rep * BLOCK >= L)
+            break;
         const int r = rep * BLOCK + (int)threadIdx.x;
-        const long long mine = r < L ? size_by_rank[r] : 0;
+        const long long mine = r < L ? numel_of_layer[sorted_layer[r]] : 0;
         long long total;
         const long long incl = carry + block_scan_exclusive<BLOCK, long long>(mine, &total) + mine;
         if (r < L) {
@@ -372,7 +406,7 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
             const int l = sorted_layer[r];
             important_layer[l] = fits ? 0 : 1;
             gib_layer[l] = fits ? 0 : 1;
-            const bool last = r == L - 1 || incl + size_by_rank[r + 1] > budget;
+            const bool last = r == L - 1 || incl + numel_of_layer[sorted_layer[r + 1]] > budget;
             if (fits && last)
                 n_stage2_found = incl;
         }
@@ -382,12 +416,15 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
 
     // bases of the two stage tables: exclusive scans over the layers, in layer order
     int carry1 = 0, carry2 = 0;
-    for (int rep = 0; rep < per; ++rep) {
+#pragma unroll
+    for (int rep = 0; rep < kLayersPer; ++rep) {
+        if (rep * BLOCK >= L)
+            break;
         const int l = rep * BLOCK + (int)threadIdx.x;
         int ns = 0;
         bool important = true;
         if (l < L) {
-            ns = layer_span_begin[l + 1] - layer_span_begin[l];
+            ns = my_end[rep] - my_first[rep];
             important = important_layer[l] != 0;
         }
         int tot1, tot2;
@@ -408,10 +445,14 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
         publish_counts(counts_out, carry1, carry2, n_stage2_found, seq);
     }
     __syncthreads();
-    for (int k = threadIdx.x; k < n_spans; k += BLOCK) {
-        const int l = span_layer[k];
-        const int pos = base_of_layer[l] + (k - layer_span_begin[l]);
-        (important_layer[l] ? list_s1 : list_s2)[pos] = spans[k];
+#pragma unroll
+    for (int j = 0; j < kSpansPer; ++j) {
+        const int k = j * BLOCK + (int)threadIdx.x;
+        if (k < n_spans) {
+            const int l = my_span_layer[j];
+            const int pos = base_of_layer[l] + (k - first_span_of_layer[l]);
+            (important_layer[l] ? list_s1 : list_s2)[pos] = my_span[j];
+        }
     }
 }
 

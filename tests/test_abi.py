@@ -139,6 +139,8 @@ def test_newer_entry_points_validate_before_touching_anything():
     assert L.osp_ics_window(None, 16, 20, 0, 1, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_split_gradients(None, 16, 20, 16, 20, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_ps_aggregate_update_packed(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_split_gradients_bf16(None, 16, 20, 16, 20, 16, 20, None) == B.OSP_ERR_INVALID_ARG
+    assert L.osp_ps_aggregate_update_packed_bf16(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_ps_aggregate_update_bf16(None, 1, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_lgp_correct_bf16(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_rs_window_bf16(None, 16, 20, None) == B.OSP_ERR_INVALID_ARG
@@ -159,6 +161,11 @@ def test_newer_entry_points_validate_before_touching_anything():
         (lambda: c.osp_ps_aggregate_update_packed(0, 16, 20, stream=0), B.OSP_ERR_INVALID_ARG),
         (lambda: c.osp_ps_aggregate_update_packed(1, 18, 20, stream=0), B.OSP_ERR_INVALID_ARG),
         (lambda: c.osp_ps_aggregate_update_packed(1, 16, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_split_gradients_bf16(12, 20, 16, 20, 16, 20, stream=0), B.OSP_ERR_INVALID_ARG),  # arena alignment
+        (lambda: c.osp_split_gradients_bf16(8, 20, 17, 20, 16, 20, stream=0), B.OSP_ERR_INVALID_ARG),   # odd output
+        (lambda: c.osp_split_gradients_bf16(8, 20, 18, 20, 16, 20, stream=0), B.OSP_ERR_BAD_STATE),
+        (lambda: c.osp_ps_aggregate_update_packed_bf16(1, 17, 20, stream=0), B.OSP_ERR_INVALID_ARG),
+        (lambda: c.osp_ps_aggregate_update_packed_bf16(1, 18, 20, stream=0), B.OSP_ERR_BAD_STATE),
         (lambda: c.osp_ps_aggregate_update_bf16(1, 12, 20, stream=0), B.OSP_ERR_INVALID_ARG),  # 8-byte alignment
         (lambda: c.osp_ps_aggregate_update_bf16(1, 8, 20, stream=0), B.OSP_ERR_BAD_STATE),
         (lambda: c.osp_lgp_correct_bf16(8, 16, stream=0), B.OSP_ERR_INVALID_ARG),      # stride < arena

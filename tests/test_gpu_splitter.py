@@ -14,10 +14,15 @@ pytestmark = pytest.mark.gpu
 # gradient splitter: dense G^i / G^u, and the PS fed by them
 # --------------------------------------------------------------------------
 
-def run_splitter_steps(wl, gran, steps, weights=None, chunk_elems=0, align=None, injected=False, seed=0):
+def run_splitter_steps(wl, gran, steps, weights=None, chunk_elems=0, align=None, injected=False, seed=0,
+                       bf16=False, strides_of_4=False):
     """Each iteration: split every worker's gradients on both sides, compare the dense parts
     bit for bit, then run the iteration with the PS fed by the dense parts on the GPU and by
-    the oracle's own dense parts on the CPU."""
+    the oracle's own dense parts on the CPU.  bf16: the arenas and the dense parts hold
+    bfloat16 on the GPU; the oracle works on the widened values (exact), and the GPU's dense
+    parts are compared as 16-bit patterns with the oracle's rounded back (exact too).
+    strides_of_4: the dense parts' worker strides are multiples of 4 elements (full-width
+    loads and stores where the layer-granular runs allow them) instead of odd ones."""
     import torch
     o = make_oracle(wl, seed, align, weights)
     job = device_job(wl, seed, align, weights, element_keys=True, chunk_elems=chunk_elems)
@@ -33,32 +38,50 @@ def run_splitter_steps(wl, gran, steps, weights=None, chunk_elems=0, align=None,
             o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
         g = wl.make_grads(seed, step, align)
         g[:, :arena][:, ~real] = 5.0                 # padding must not reach the dense parts
-        gd = job.upload_grads(g); s_ = g.shape[1]
+        if bf16:
+            h = W.to_bf16(g); g = W.from_bf16(h)
+            gd = job.upload_grads_bf16(h)
+        else:
+            gd = job.upload_grads(g)
+        s_ = g.shape[1]
+        split_gradients = c.osp_split_gradients_bf16 if bf16 else c.osp_split_gradients
+        agg_packed = c.osp_ps_aggregate_update_packed_bf16 if bf16 else c.osp_ps_aggregate_update_packed
+        lgp = c.osp_lgp_correct_bf16 if bf16 else c.osp_lgp_correct
+        dense_dtype = torch.int16 if bf16 else torch.float32
+        sentinel = -7 if bf16 else -7.0
         og_i, og_u = o.split_gradients(g)
         e1, e2 = og_i.shape[1], og_u.shape[1]
         assert c.osp_n_stage2() == e2
         st_i, st_u = e1 + 3, e2 + 1                  # strides beyond the parts, sentinel behind
-        dg_i = torch.full((wl.n_workers, st_i), -7.0, dtype=torch.float32, device="cuda")
-        dg_u = torch.full((wl.n_workers, st_u), -7.0, dtype=torch.float32, device="cuda")
-        c.osp_split_gradients(gd, s_, dg_i, st_i, dg_u, st_u)
+        if strides_of_4:
+            st_i, st_u = (e1 + 3) // 4 * 4 + 4, (e2 + 3) // 4 * 4 + 8
+        dg_i = torch.full((wl.n_workers, st_i), sentinel, dtype=dense_dtype, device="cuda")
+        dg_u = torch.full((wl.n_workers, st_u), sentinel, dtype=dense_dtype, device="cuda")
+        split_gradients(gd, s_, dg_i, st_i, dg_u, st_u)
         hi, hu = dg_i.cpu().numpy(), dg_u.cpu().numpy()
-        assert np.array_equal(hi[:, :e1], og_i, equal_nan=True), f"G^i step {step}"
-        assert np.array_equal(hu[:, :e2], og_u, equal_nan=True), f"G^u step {step}"
-        assert (hi[:, e1:] == -7.0).all() and (hu[:, e2:] == -7.0).all()
+        if bf16:                                      # 16-bit patterns on both sides
+            want_i, want_u = (og_i.view(np.uint32) >> 16).astype(np.uint16), (og_u.view(np.uint32) >> 16).astype(np.uint16)
+            assert np.array_equal(W.from_bf16(want_i), og_i, equal_nan=True)      # nothing lost
+            assert np.array_equal(hi[:, :e1].view(np.uint16), want_i), f"G^i step {step}"
+            assert np.array_equal(hu[:, :e2].view(np.uint16), want_u), f"G^u step {step}"
+        else:
+            assert np.array_equal(hi[:, :e1], og_i, equal_nan=True), f"G^i step {step}"
+            assert np.array_equal(hu[:, :e2], og_u, equal_nan=True), f"G^u step {step}"
+        assert (hi[:, e1:] == sentinel).all() and (hu[:, e2:] == sentinel).all()
         # one part only
-        only_u = torch.full_like(dg_u, -7.0)
-        c.osp_split_gradients(gd, s_, None, 0, only_u, st_u)
+        only_u = torch.full_like(dg_u, sentinel)
+        split_gradients(gd, s_, None, 0, only_u, st_u)
         assert torch.equal(only_u, dg_u)
-        o.ps_aggregate_update_packed(1, og_i); c.osp_ps_aggregate_update_packed(1, dg_i, st_i)
+        o.ps_aggregate_update_packed(1, og_i); agg_packed(1, dg_i, st_i)
         compare_state(job, o, f"packed agg1 step {step}")
         o.apply_stage(1); c.osp_apply_stage(1)
-        o.lgp_correct(g); c.osp_lgp_correct(gd, s_)
+        o.lgp_correct(g); lgp(gd, s_)
         compare_state(job, o, f"lgp step {step}")
         if e2 > 0:
             o.ps_aggregate_update_packed(2, og_u)
         else:
             o.ps_aggregate_update(2, g)              # empty stage: nothing to read
-        c.osp_ps_aggregate_update_packed(2, dg_u, st_u)
+        agg_packed(2, dg_u, st_u)
         compare_state(job, o, f"packed agg2 step {step}")
         o.apply_stage(2); c.osp_apply_stage(2)
         compare_state(job, o, f"apply2 step {step}")
@@ -79,6 +102,39 @@ def test_splitter_tiny(gran, weighted):
     wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
     run_splitter_steps(wl, gran, 4, weights=wts)
     run_splitter_steps(wl, gran, 3, weights=wts, injected=True)
+    run_splitter_steps(wl, gran, 3, weights=wts, injected=True, strides_of_4=True)
+
+
+def test_splitter_layer_runs_aligned_and_not():
+    """Layer-granular parts are runs of whole tensors: tensor sizes that are multiples of 4
+    (full-width copies), odd ones (the general path), and both in one model."""
+    say("splitter layer runs")
+    for numel, cid in (([4096, 64, 1000, 8192, 256, 70000], 183), ([4097, 63, 1001, 8191], 184),
+                       ([4096, 64, 1001, 8192, 3, 256, 70000, 4], 185)):
+        wl = W.custom(numel, 5, 0.5, align=4, config_id=cid)
+        for bf16 in (False, True):
+            run_splitter_steps(wl, GRAN_LAYER, 3, injected=True, bf16=bf16, strides_of_4=True)
+            run_splitter_steps(wl, GRAN_LAYER, 2, injected=True, bf16=bf16)
+            run_splitter_steps(wl, GRAN_LAYER, 2, injected=True, bf16=bf16, chunk_elems=1024, strides_of_4=True)
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+@pytest.mark.parametrize("weighted", [False, True])
+def test_splitter_bf16_tiny(gran, weighted):
+    say("splitter bf16 tiny", gran, weighted)
+    wl = W.get("tiny")
+    wts = np.array([0.4, 0.1, 0.3, 0.2], F) if weighted else None
+    run_splitter_steps(wl, gran, 4, weights=wts, bf16=True)
+    run_splitter_steps(wl, gran, 3, weights=wts, injected=True, bf16=True)
+    run_splitter_steps(wl, gran, 3, weights=wts, injected=True, bf16=True, strides_of_4=True)
+
+
+@pytest.mark.parametrize("chunk,align", [(256, 4), (16384, 4), (131072, 64)])
+def test_splitter_bf16_chunk_sizes(chunk, align):
+    say("splitter bf16 chunk", chunk, align)
+    wl = W.custom([70001, 3, 1029, 64, 2048, 200000, 1], 3, 0.5, align=align, config_id=182)
+    run_splitter_steps(wl, GRAN_ELEMENT, 2, chunk_elems=chunk, align=align, injected=True, bf16=True)
+    run_splitter_steps(wl, GRAN_LAYER, 2, chunk_elems=chunk, align=align, injected=True, bf16=True)
 
 
 @pytest.mark.parametrize("chunk,align", [(256, 4), (1024, 64), (16384, 4), (131072, 4)])
