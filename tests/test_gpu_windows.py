@@ -391,3 +391,59 @@ def test_sync_step_is_both_windows(gran):
         c.osp_sync_step(gd, g.shape[1], gran, wl.budget)
         compare_state(job, o, f"step {step}")
         compare_gib(job, o, f"step {step}")
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_two_contexts_interleaved_and_rebind_resume(gran):
+    """Two jobs alive at once with their calls interleaved on one stream do not disturb each
+    other; and a job whose state is moved into new buffers mid-run (osp_bind again, the GIB read
+    back and installed again: a resume) continues exactly where the oracle does."""
+    import torch
+    say("two contexts / rebind", gran)
+    wl_a = W.custom([5000, 3, 1029, 64, 70000], 5, 0.5, align=4, config_id=260)
+    wl_b = W.custom([300, 40000, 17, 2048], 3, 0.3, align=64, config_id=261)
+    oa, ob = make_oracle(wl_a), make_oracle(wl_b, align=64)
+    ja = device_job(wl_a, element_keys=True)
+    jb = device_job(wl_b, align=64, element_keys=True, chunk_elems=1024)
+    for o, j, wl in ((oa, ja, wl_a), (ob, jb, wl_b)):
+        all1 = np.ones(wl.n_tensors, np.uint8)
+        o.set_gib(GRAN_LAYER, all1); j.ctx.osp_set_gib(GRAN_LAYER, all1)
+    for step in range(3):
+        ga, gb = wl_a.make_grads(0, step), wl_b.make_grads(0, step, 64)
+        da, db = ja.upload_grads(ga), jb.upload_grads(gb)
+        oa.sync_step(ga, gran, wl_a.budget); ob.sync_step(gb, gran, wl_b.budget)
+        ca, cb, sa, sb = ja.ctx, jb.ctx, ga.shape[1], gb.shape[1]
+        ca.osp_ps_aggregate_update(1, da, sa); cb.osp_rs_window(db, sb)
+        ca.osp_apply_stage(1); ca.osp_lgp_correct(da, sa)
+        cb.osp_ps_aggregate_update(2, db, sb)
+        ca.osp_ps_aggregate_update(2, da, sa); cb.osp_apply_stage(2)
+        ca.osp_apply_stage(2); cb.osp_split(gran, wl_b.budget); ca.osp_split(gran, wl_a.budget)
+        compare_state(ja, oa, f"job a step {step}"); compare_gib(ja, oa, f"job a step {step}")
+        compare_state(jb, ob, f"job b step {step}"); compare_gib(jb, ob, f"job b step {step}")
+
+    # resume job a in new buffers: same values, other addresses, a fresh workspace
+    layer, bits, n2 = ja.ctx.osp_get_gib()
+    P2, V2 = ja.P.clone(), ja.V.clone()
+    stride2 = ja.arena + 260
+    Pw2 = torch.full((ja.N, stride2), 9.0, dtype=torch.float32, device="cuda")
+    Pw2[:, :ja.arena] = ja.Pw[:, :ja.arena]
+    nbytes = ja.ctx.osp_workspace_bytes()
+    ws2 = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    ja.ctx.osp_bind(P2, V2, Pw2, stride2, ws2, nbytes, replicas_in_sync=True)
+    from paper_2306_16926_amd.binding import OspError
+    with pytest.raises(OspError):
+        ja.ctx.osp_rs_window(ja.upload_grads(wl_a.make_grads(0, 3)), wl_a.make_grads(0, 3).shape[1])  # no GIB after a bind
+    ja.ctx.osp_set_gib(gran, layer if gran == GRAN_LAYER else bits)
+    ja.P, ja.V, ja.Pw, ja.param_stride, ja.workspace = P2, V2, Pw2, stride2, ws2
+    assert ja.ctx.osp_n_stage2() == n2 == oa.n_stage2
+    for step in range(3, 6):
+        ga = wl_a.make_grads(0, step); da = ja.upload_grads(ga)
+        oa.sync_step(ga, gran, wl_a.budget)
+        if step % 2:
+            ja.sync_step_windows(da, gran, wl_a.budget)
+        else:
+            ja.sync_step(da, gran, wl_a.budget)
+        compare_state(ja, oa, f"resumed job a step {step}"); compare_gib(ja, oa, f"resumed step {step}")
+    assert (Pw2[:, ja.arena:] == 9.0).all()
+    # job b was not disturbed by any of it
+    compare_state(jb, ob, "job b at the end")
