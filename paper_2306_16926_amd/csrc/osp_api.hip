@@ -89,6 +89,7 @@ struct osp_ctx {
     // with sequence number split_seq has been enqueued and its lengths have not been
     // read yet.  counts_stream is the stream that split was enqueued on (fallback wait).
     int stage_spans[2] = {0, 0};
+    int tables = 0;                     // which of the two sets of stage tables is current
     bool counts_pending = false;
     unsigned split_seq = 0;
     StageCounts *pinned_counts = nullptr;      // hipHostMalloc (mapped)
@@ -112,7 +113,12 @@ struct osp_ctx {
     int *d_lsb() const { return at<int>(off_lsb); }
     int *d_big() const { return at<int>(off_big); }
     double *d_segsum() const { return at<double>(off_segsum); }
-    Span *d_list(int stage) const { return at<Span>(off_lists) + (size_t)(stage - 1) * spans.size(); }
+    // stage tables of the current GIB; there are two sets, written alternately, so that a split
+    // may be enqueued while a launch over the old tables is still to come
+    Span *d_list(int stage) const
+    {
+        return at<Span>(off_lists) + (size_t)(tables * 2 + stage - 1) * spans.size();
+    }
     uint8_t *d_gib() const { return at<uint8_t>(off_gib); }
     SplitState *d_state() const { return at<SplitState>(off_state); }
     float *d_weights() const { return at<float>(off_weights); }
@@ -177,7 +183,7 @@ void layout_workspace(osp_ctx *c)
     c->off_segs = take(c->segments.size() * sizeof(Segment));
     c->off_lsb = take((size_t)(c->n_tensors + 1) * sizeof(int));
     c->off_big = take((size_t)(c->big_layers.size() + 1) * sizeof(int));
-    c->off_lists = take(2 * ns * sizeof(Span));
+    c->off_lists = take(4 * ns * sizeof(Span));
     c->off_partial = take(2 * nc * sizeof(double));
     c->off_segsum = take(c->segments.size() * sizeof(double));
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
@@ -535,6 +541,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         ctx->split_seq = 0;
     }
     ctx->counts_pending = false;
+    ctx->tables = 0;
     ctx->ws = (char *)buf->workspace;
     OSP_HIP(hipMemcpyAsync(ctx->d_spans(), ctx->spans.data(), ctx->spans.size() * sizeof(Span),
                            hipMemcpyHostToDevice, s));
@@ -608,6 +615,7 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         }
         OSP_HIP(hipMemcpyAsync(ctx->d_gib(), norm.data(), norm.size(), hipMemcpyHostToDevice, s));
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
+        ctx->tables ^= 1;               // the new GIB's tables go into the other set
         k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
                                        ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
         osp_status st = enqueue_stage_lists(ctx, s);
@@ -923,42 +931,11 @@ osp_status osp_lgp_correct_bf16(osp_ctx *ctx, const uint16_t *grads, int64_t wor
     return lgp_correct(ctx, grads, worker_stride, stream, true);
 }
 
-osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
+// Install launch over a span table: every replica receives the PS values of the table's spans
+// (masked: of their elements in `stage` under the element-granular GIB).
+static osp_status launch_install(osp_ctx *ctx, const Span *table, unsigned n_spans, int stage,
+                                 bool masked, hipStream_t s)
 {
-    if (!ctx)
-        return OSP_ERR_INVALID_ARG;
-    if (stage < 0 || stage > 2)
-        return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 0, 1 or 2 (got %d)", stage);
-    if (!ctx->bound)
-        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
-    if (stage != 0 && !ctx->have_gib)
-        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB");
-    if (stage == 1 && !ctx->agg1)
-        return fail(ctx, OSP_ERR_BAD_STATE, "stage 1 has not been aggregated in this iteration");
-    if (stage != 1 && !(ctx->agg1 && ctx->agg2))
-        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
-    // Element-granular GIB: two situations in which writing ALL elements gives the same result
-    // as writing the stage's elements only, with full-width stores and no read of old values:
-    //  * stage 2 after this iteration's stage 1 was installed: the stage-1 elements of every
-    //    replica already equal the PS and have not changed since;
-    //  * stage 1 when the replicas were in sync as the iteration began and neither LGP nor the
-    //    stage-2 aggregate has run yet: the stage-2 elements of every replica still equal the
-    //    PS's (both hold the stale value).
-    const bool element = ctx->gib_gran == OSP_GRAN_ELEMENT;
-    const bool overwrite_all =
-        element && ((stage == 2 && ctx->applied1) ||
-                    (stage == 1 && ctx->iter_synced && !ctx->agg2 && !ctx->lgp_done));
-    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
-    const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
-    unsigned n_spans = (unsigned)ctx->spans.size();
-    if (listed) {
-        osp_status sc = stage_counts(ctx);
-        if (sc != OSP_OK)
-            return sc;
-        n_spans = (unsigned)ctx->stage_spans[stage - 1];
-    }
-    hipStream_t s = (hipStream_t)stream;
-    const Span *table = listed ? ctx->d_list(stage) : ctx->d_spans();
     const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     if (ctx->n_workers > kFanoutMaxWorkers) {
         ApplyArgs a;
@@ -1003,7 +980,45 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
                 k_apply_stage_fanout<false><<<grid, block, 0, s>>>(a);
         }
     }
-    osp_status st = launch_check(ctx, "k_apply_stage");
+    return launch_check(ctx, "k_apply_stage");
+}
+
+osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (stage < 0 || stage > 2)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "stage must be 0, 1 or 2 (got %d)", stage);
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    if (stage != 0 && !ctx->have_gib)
+        return fail(ctx, OSP_ERR_BAD_STATE, "a staged call needs a GIB");
+    if (stage == 1 && !ctx->agg1)
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 1 has not been aggregated in this iteration");
+    if (stage != 1 && !(ctx->agg1 && ctx->agg2))
+        return fail(ctx, OSP_ERR_BAD_STATE, "stage 2 has not been aggregated in this iteration");
+    // Element-granular GIB: two situations in which writing ALL elements gives the same result
+    // as writing the stage's elements only, with full-width stores and no read of old values:
+    //  * stage 2 after this iteration's stage 1 was installed: the stage-1 elements of every
+    //    replica already equal the PS and have not changed since;
+    //  * stage 1 when the replicas were in sync as the iteration began and neither LGP nor the
+    //    stage-2 aggregate has run yet: the stage-2 elements of every replica still equal the
+    //    PS's (both hold the stale value).
+    const bool element = ctx->gib_gran == OSP_GRAN_ELEMENT;
+    const bool overwrite_all =
+        element && ((stage == 2 && ctx->applied1) ||
+                    (stage == 1 && ctx->iter_synced && !ctx->agg2 && !ctx->lgp_done));
+    const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
+    const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
+    unsigned n_spans = (unsigned)ctx->spans.size();
+    if (listed) {
+        osp_status sc = stage_counts(ctx);
+        if (sc != OSP_OK)
+            return sc;
+        n_spans = (unsigned)ctx->stage_spans[stage - 1];
+    }
+    const Span *table = listed ? ctx->d_list(stage) : ctx->d_spans();
+    osp_status st = launch_install(ctx, table, n_spans, stage, masked, (hipStream_t)stream);
     if (st != OSP_OK)
         return st;
     if (stage != 1)
@@ -1159,6 +1174,27 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
     const bool fused = element ? (ctx->applied1 && N <= kWindowMaxWorkers) : layer_window_fused(ctx);
     ctx->windows_fused = (ctx->windows_fused & 1) | (fused ? 2 : 0);
     hipStream_t s = (hipStream_t)stream;
+    if (!fused && !element) {
+        // Layer-granular GIB: the split only needs the stage-2 aggregate, and it writes the new
+        // stage tables into the other set.  Enqueued ahead of the install, it publishes the new
+        // table lengths while the install still runs, and the next iteration's first launch
+        // (which is shaped by them) is enqueued without the GPU running dry in between.
+        st = aggregate_update(ctx, 2, grads, worker_stride, stream, bf16);
+        if (st != OSP_OK)
+            return st;
+        const Span *old_table = ctx->d_list(2);
+        const unsigned old_spans = (unsigned)ctx->stage_spans[1];   // (known: the aggregate waited)
+        const bool stage1_installed = ctx->applied1;
+        st = osp_split(ctx, granularity, budget_elems, stream);
+        if (st != OSP_OK)
+            return st;
+        st = launch_install(ctx, old_table, old_spans, 2, false, s);
+        if (st != OSP_OK)
+            return st;
+        if (stage1_installed)
+            ctx->replicas_synced = true;    // every element of every replica equals the PS again
+        return OSP_OK;
+    }
     if (!fused) {
         st = aggregate_update(ctx, 2, grads, worker_stride, stream, bf16);
         if (st == OSP_OK)
@@ -1485,6 +1521,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
             ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
         const int ns = (int)ctx->spans.size();
+        ctx->tables ^= 1;               // the new GIB's tables go into the other set
         if (ctx->n_tensors <= kRankTile) {
             // one workgroup ranks in LDS and, unless the tables are long, fills them as well
             const bool fill = ns <= kRankFillMaxSpans;
@@ -1536,8 +1573,11 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         ctx->n_stage2_host = budget_elems;
     }
     osp_status st = launch_check(ctx, "split kernels");
-    if (st != OSP_OK)
+    if (st != OSP_OK) {
+        if (granularity == OSP_GRAN_LAYER)
+            ctx->tables ^= 1;           // the old GIB and its tables stay current
         return st;
+    }
     ctx->have_gib = true;
     ctx->pack_index_valid = false;
     ctx->gib_gran = granularity;
