@@ -56,7 +56,7 @@ struct osp_ctx {
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
            off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_big = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0, off_pack = 0,
-           off_bitmap = 0, off_hist = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
+           off_bitmap = 0, off_hist = 0, off_cand = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
     bool bound = false;
@@ -133,6 +133,8 @@ struct osp_ctx {
     {
         return at<unsigned long long>(off_hist) + (size_t)pass * kRadixBins;
     }
+    unsigned int *d_n_cand() const { return reinterpret_cast<unsigned int *>(d_hist(3)); }
+    TieCandidate *d_cand() const { return at<TieCandidate>(off_cand); }
     unsigned int *d_tile_ties() const { return at<unsigned int>(off_tile_ties); }
     unsigned long long *d_tile_before() const { return at<unsigned long long>(off_tile_before); }
 };
@@ -198,7 +200,9 @@ void layout_workspace(osp_ctx *c)
         c->off_key = take((size_t)c->arena * sizeof(uint32_t));
         c->off_stash = take((size_t)c->arena * sizeof(float));
         c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
-        c->off_hist = take((size_t)3 * kRadixBins * sizeof(unsigned long long));
+        // three histograms, then the length of the tie-candidate list (cleared with them)
+        c->off_hist = take(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long));
+        c->off_cand = take((size_t)kTieCandidates * sizeof(TieCandidate));
         c->off_tile_ties = take((size_t)c->n_tiles * sizeof(unsigned int));
         c->off_tile_before = take((size_t)c->n_tiles * sizeof(unsigned long long));
     }
@@ -1555,13 +1559,15 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         long long want = (nv + kSplitBlock - 1) / kSplitBlock;
         const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
         k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
-                                         (long long)3 * kRadixBins * 2, 0u);
+                                         (long long)(3 * kRadixBins + 1) * 2, 0u);
         k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));
         k_select_pick<<<1, kSplitBlock, 0, s>>>(0, (long long)budget_elems, ctx->d_hist(0), ctx->d_state());
         k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(1));
         k_select_pick<<<1, kSplitBlock, 0, s>>>(1, (long long)budget_elems, ctx->d_hist(1), ctx->d_state());
-        k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2));
-        k_select_pick<<<1, kSplitBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state());
+        k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2),
+                                                           ctx->d_cand(), ctx->d_n_cand());
+        k_select_pick<<<1, kSplitBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state(),
+                                               ctx->d_cand(), ctx->d_n_cand());
         const unsigned tiles = (unsigned)ctx->n_tiles;
         k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
         k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_state(),

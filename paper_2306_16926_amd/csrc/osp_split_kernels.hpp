@@ -47,7 +47,21 @@ struct SplitState {                    // one per context, in the workspace
     unsigned int threshold;            // T
     unsigned int done;                 // 1: budget 0, nothing is selected
     unsigned int all_ties;             // 1: every key equal to T is taken (no per-tile counts needed)
+    unsigned int collect;              // 1: the last radix pass lists the keys of its bucket
+    unsigned int ties_by_limit;        // 1: a key equal to T is taken iff its index < tie_limit
+    unsigned long long tie_limit;
 };
+
+// Keys that share the threshold's upper 22 bits, listed by the last radix pass when there are
+// few of them (the usual case): the ties among them are then cut by arena index in one
+// workgroup instead of two more passes over all keys.
+struct TieCandidate {
+    unsigned long long index;          // arena index of the element
+    unsigned int key;
+    unsigned int pad;
+};
+constexpr unsigned kTieCandidates = 65536;    // capacity of the list
+constexpr int kTieSortMax = 2048;             // ties cut through LDS up to this many
 
 // ---------------------------------------------------------------------------
 // layer granularity
@@ -515,7 +529,8 @@ __global__ __launch_bounds__(kSplitBlock) void k_fill_u32(uint32_t *p, long long
 template <int PASS>
 __global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
-    unsigned long long *__restrict__ hist)
+    unsigned long long *__restrict__ hist, TieCandidate *__restrict__ cand = nullptr,
+    unsigned int *__restrict__ n_cand = nullptr)
 {
     __shared__ unsigned int h[kRadixBins];
     for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
@@ -524,6 +539,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
     const int shift = radix_shift(PASS);
     const unsigned mask = (1u << radix_bits(PASS)) - 1u;
     const unsigned prefix = PASS == 0 ? 0u : st->prefix;
+    const bool collect = PASS == 2 && st->collect != 0;
     const int hi = shift + radix_bits(PASS);          // bits above this pass's digit
     const u4 *kv = reinterpret_cast<const u4 *>(key);
     // four 16-byte loads in flight per thread; keys of one group that fall into one bin
@@ -550,6 +566,21 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
                 const unsigned x = k[u][j];
                 in[j] = PASS == 0 || (x >> hi) == prefix;
                 bin[j] = (x >> shift) & mask;
+            }
+            if (collect) {
+                // (the bucket holds at most kTieCandidates keys, so every slot exists)
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    if (in[j]) {
+                        const unsigned slot = atomicAdd(n_cand, 1u);
+                        if (slot < kTieCandidates) {
+                            TieCandidate tc;
+                            tc.index = (unsigned long long)(v0 + u * stride) * kVec + j;
+                            tc.key = k[u][j];
+                            tc.pad = 0;
+                            cand[slot] = tc;
+                        }
+                    }
             }
             if (in[0] && in[1] && in[2] && in[3] && bin[0] == bin[1] && bin[0] == bin[2] &&
                 bin[0] == bin[3]) {
@@ -597,8 +628,12 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
 // One workgroup: find the bucket of this pass that holds the k-th smallest key.
 __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long budget,
                                                         const unsigned long long *__restrict__ hist,
-                                                        SplitState *__restrict__ st)
+                                                        SplitState *__restrict__ st,
+                                                        const TieCandidate *__restrict__ cand = nullptr,
+                                                        const unsigned int *__restrict__ n_cand = nullptr)
 {
+    __shared__ unsigned long long tie_index[kTieSortMax];
+    __shared__ unsigned int n_ties;
     __shared__ int found_bin;
     __shared__ unsigned long long found_below, found_count;
     if (pass == 0 && threadIdx.x == 0) {
@@ -614,6 +649,8 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             st->prefix = 0;
             st->k_rem = 0;
             st->all_ties = 0;
+            st->collect = 0;
+            st->ties_by_limit = 0;
         }
         return;
     }
@@ -643,16 +680,23 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
     }
     __syncthreads();
     if (threadIdx.x == 0) {
+        if (pass == 0)
+            st->collect = 0;
+        if (pass != 2)
+            st->ties_by_limit = 0;
         if (found_bin < 0) {           // cannot happen for budget <= number of keys
             st->done = 1;
             st->threshold = 0;
             st->ties_to_take = 0;
             st->all_ties = 0;
+            st->collect = 0;
         } else {
             const unsigned prefix = pass == 0 ? 0u : st->prefix;
             const unsigned np = (prefix << radix_bits(pass)) | (unsigned)found_bin;
             st->prefix = np;
             st->k_rem = k - found_below;
+            if (pass == 1)             // few keys left: the last pass lists them
+                st->collect = found_count <= kTieCandidates ? 1u : 0u;
             if (pass == 2) {
                 st->threshold = np;
                 st->ties_to_take = k - found_below;
@@ -662,6 +706,42 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             }
         }
     }
+    if (pass != 2 || cand == nullptr)
+        return;
+    // Ties at the threshold that are not all taken: the first r of them in index order are.
+    // With the bucket's keys listed, gather the ties' indices, find the r-th smallest, and the
+    // bitmap pass only compares indices with it.  (All threads reach this point; what they
+    // read from st was written by thread 0 before the barrier below.)
+    __threadfence_block();
+    __syncthreads();
+    if (found_bin < 0 || st->collect == 0 || st->all_ties != 0)
+        return;
+    const unsigned T = st->threshold;
+    const unsigned long long r = st->ties_to_take;          // 1 <= r < number of ties
+    const unsigned n = *n_cand < kTieCandidates ? *n_cand : kTieCandidates;
+    if (threadIdx.x == 0)
+        n_ties = 0;
+    __syncthreads();
+    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock)
+        if (cand[c].key == T) {
+            const unsigned slot = atomicAdd(&n_ties, 1u);
+            if (slot < (unsigned)kTieSortMax)
+                tie_index[slot] = cand[c].index;
+        }
+    __syncthreads();
+    const unsigned t = n_ties;
+    if (t > (unsigned)kTieSortMax || (unsigned long long)t != found_count)
+        return;                        // too many for LDS (or the list is not complete): per-tile counts
+    for (unsigned i = threadIdx.x; i < t; i += kSplitBlock) {
+        const unsigned long long mine = tie_index[i];
+        unsigned long long smaller = 0;
+        for (unsigned j = 0; j < t; ++j)
+            smaller += tie_index[j] < mine ? 1u : 0u;
+        if (smaller == r)              // the first tie that is NOT taken
+            st->tie_limit = mine;
+    }
+    if (threadIdx.x == 0)
+        st->ties_by_limit = 1;
 }
 
 __device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key, long long v,
@@ -679,7 +759,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
     unsigned int *__restrict__ tile_ties)
 {
-    if (st->all_ties || st->done)      // uniform: the bitmap pass will not read the counts
+    if (st->all_ties || st->done || st->ties_by_limit)  // uniform: the bitmap pass will not read the counts
         return;
     const unsigned T = st->threshold;
     const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
@@ -699,7 +779,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_scan_tiles(
     const unsigned int *__restrict__ tile_ties, long long n_tiles,
     const SplitState *__restrict__ st, unsigned long long *__restrict__ tile_before)
 {
-    if (st->all_ties || st->done)
+    if (st->all_ties || st->done || st->ties_by_limit)
         return;
     const long long per = (n_tiles + kSplitBlock - 1) / kSplitBlock;
     const long long b = (long long)threadIdx.x * per;
@@ -725,12 +805,17 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
     const unsigned long long r = st->ties_to_take;
     const bool none = st->done != 0;
     const bool all = st->all_ties != 0;
-    const unsigned long long before = (none || all) ? 0 : tile_before[blockIdx.x];
-    const unsigned long long ties = (none || all) ? 0 : tile_ties[blockIdx.x];
-    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
+    const bool by_limit = st->ties_by_limit != 0;
+    const unsigned long long limit = st->tie_limit;
+    const unsigned long long before = (none || all || by_limit) ? 0 : tile_before[blockIdx.x];
+    const unsigned long long ties = (none || all || by_limit) ? 0 : tile_ties[blockIdx.x];
+    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside,
+    // 3: those with an arena index below `limit` are
     int tie_mode;
     if (all)
         tie_mode = 1;
+    else if (by_limit && !none)
+        tie_mode = 3;
     else if (none || ties == 0 || before >= r)
         tie_mode = 0;
     else if (before + ties <= r)
@@ -761,6 +846,8 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
                     else if (tie_mode == 2) {
                         s = my_before < r;
                         ++my_before;
+                    } else if (tie_mode == 3) {
+                        s = (unsigned long long)v * kVec + j < limit;
                     }
                 }
                 sel |= (s ? 1u : 0u) << j;

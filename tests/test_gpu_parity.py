@@ -389,13 +389,47 @@ def _split_from_keys(keys_f32, budget, numel=None):
 
 @pytest.mark.parametrize("case", ["all_equal", "all_zero", "inside_ties", "ties_across_tiles",
                                   "nan_inf", "neg_zero", "denormal", "two_values_multi_tensor",
-                                  "nan_payloads"])
+                                  "nan_payloads", "few_ties", "ties_2048", "ties_2049",
+                                  "ties_in_a_crowded_bucket", "big_bucket_few_ties", "all_equal_200k"])
 def test_split_element_adversarial(case):
     say("adversarial", case)
     rng = np.random.default_rng(4)
     n = 50_000                                  # several 8192-key tiles and a ragged tail
     numel = None
-    if case == "all_equal":
+    if case in ("few_ties", "ties_2048", "ties_2049"):
+        # distinct keys except for t copies of one value, scattered over the arena; the budget
+        # ends inside them (t <= 2048: cut through the listed candidates; above: per-tile counts)
+        t = {"few_ties": 7, "ties_2048": 2048, "ties_2049": 2049}[case]
+        keys = (1.0 + rng.permutation(n) / n).astype(F)          # distinct, one binade
+        keys[keys == F(1.5)] = F(1.99999)
+        where = np.sort(rng.choice(n, t, replace=False))
+        keys[where] = F(1.5)
+        assert int((keys == F(1.5)).sum()) == t
+        k = int((keys < F(1.5)).sum()) + t // 2 + 1
+    elif case == "ties_in_a_crowded_bucket":
+        # 30 000 keys share the threshold's upper 22 bits (all listed), 40 of them equal it
+        keys = (1.0 + rng.permutation(n) / n).astype(F)
+        base = np.float32(1.25).view(np.uint32)
+        low = rng.integers(0, 1024, 30_000).astype(np.uint32)
+        idx = rng.choice(n, 30_000, replace=False)
+        keys.view(np.uint32)[idx] = (base & np.uint32(0xFFFFFC00)) | low
+        ties = idx[:40]
+        keys.view(np.uint32)[ties] = (base & np.uint32(0xFFFFFC00)) | np.uint32(512)
+        T = keys[ties[0]]
+        k = int((keys < T).sum()) + 13
+    elif case == "big_bucket_few_ties":
+        # more keys in the threshold's bucket than the candidate list holds: not listed
+        n = 200_000
+        keys = (1.0 + rng.permutation(n) / n).astype(F)
+        base = np.float32(1.25).view(np.uint32)
+        idx = rng.choice(n, 90_000, replace=False)
+        keys.view(np.uint32)[idx] = (base & np.uint32(0xFFFFFC00)) | rng.integers(0, 1024, 90_000).astype(np.uint32)
+        T = keys[idx[0]]
+        k = int((keys < T).sum()) + max(1, int((keys == T).sum()) // 2)
+    elif case == "all_equal_200k":
+        n = 200_000
+        keys, k = np.full(n, 3.0, F), 123_457
+    elif case == "all_equal":
         keys, k = np.full(n, 3.0, F), 23_456
     elif case == "all_zero":
         keys, k = np.zeros(n, F), 8192 * 3      # boundary exactly on a tile edge
