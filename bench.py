@@ -42,9 +42,9 @@ BRACKET_EVERY = 4               # steps between two event-bracketed steps of the
 # 1.0 (what each reads for the 2 GiB k_stream_copy).  Algorithmic: 5534301760.
 AGG_TRAFFIC_VGG16_LAYER = 5544097792
 # HBM bytes per launch of k_rs_window_element on VGG-16-shaped, element granularity, --calls windows,
-# from profiles/window_kernels_vgg16_element.txt: (9798009 + 10844826) KiB.  The launch does the work the
+# from profiles/window_kernels_vgg16_element.txt: (9797972 + 10844502) KiB.  The launch does the work the
 # metric counts as stage-1 aggregate + install + LGP (30.4 GB) in one pass over 21.2 GB.
-RS_TRAFFIC_VGG16_ELEMENT = 21138263040
+RS_TRAFFIC_VGG16_ELEMENT = 21137893376
 
 
 def step_bytes(N, M, E2, element, gb=4):
