@@ -11,7 +11,9 @@ All inputs are resident in HBM before the timed region.  Prints ONE JSON line.
 (E1 + E2 = M parameters, E2 = stage-2 elements in effect during the step, N workers);
 `GBps_on_bytes_moved` uses the smaller byte count the step really needs when LGP
 reads the stale stage-2 values once from the PS instead of once per replica
-(4 (N-1) E2 bytes less):
+(4 (N-1) E2 bytes less) and, with a layer-granular GIB, keeps the aggregate of the stage-2
+gradients it reads anyway, so that the stage-2 call does not read the N arenas again
+((8 N - 12) E2 bytes less in all, see bytes_not_moved):
     aggregate+update  4 (N + 4) E_s     per stage  (N grads + P + V read, P + V written)
     apply_stage       4 (N + 1) E_s     per stage  (P read once, N replicas written)
     lgp_correct       12 N E2                      (P_w and g_w read, P_w written)
@@ -36,11 +38,11 @@ HBM_PEAK_GBPS = 8000.0          # MI355X HBM3E, published
 BRACKET_EVERY = 4               # steps between two event-bracketed steps of the timed region
 
 # HBM bytes per launch of k_aggregate_update on the default workload (VGG-16-shaped, layer
-# granularity, chunk 256), average over the stage-1 and stage-2 launch of a step, from the two
-# rocprofv3 --pmc runs summarised in profiles/sync_step_traffic_vgg16_layer.txt:
-# ((7226989 + 815367) + (2503511 + 282449)) / 2 KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by
-# 1.0 (what each reads for the 2 GiB k_stream_copy).  Algorithmic: 5534301760.
-AGG_TRAFFIC_VGG16_LAYER = 5544097792
+# granularity, chunk 256; one launch per step, on stage 1: LGP keeps the stage-2 aggregate), from
+# the two rocprofv3 --pmc runs summarised in profiles/sync_step_traffic_vgg16_layer.txt:
+# (7226993 + 815368) KiB, FETCH_SIZE scaled by 2.0 and WRITE_SIZE by 1.0 (what each reads for
+# the 2 GiB k_stream_copy).  Algorithmic: 4 (N + 4) E1 = 8220835840.
+AGG_TRAFFIC_VGG16_LAYER = (7226993 + 815368) * 1024
 # HBM bytes per launch of k_rs_window_element on VGG-16-shaped, element granularity, --calls windows,
 # from profiles/window_kernels_vgg16_element.txt: (9797972 + 10844502) KiB.  The launch does the work the
 # metric counts as stage-1 aggregate + install + LGP (30.4 GB) in one pass over 21.2 GB.
@@ -62,6 +64,19 @@ def step_bytes(N, M, E2, element, gb=4):
     b["ics_window"] = b["agg2"] + b["apply2"] + b["split"]
     b["split_gradients"] = 2 * gb * N * M   # every gradient read once, written once
     return b
+
+
+def bytes_not_moved(N, E2, gb, lgp_shared, lgp_kept):
+    """What a layer-granular step moves less than the metric's byte count credits it with.
+    LGP reading the stale values once from the PS arena instead of once per replica:
+    4 (N-1) E2.  LGP that also keeps the stage-2 aggregate (reads N gradients + P, writes N
+    replicas + the aggregate; the stage-2 call then reads P, V and the aggregate and writes P, V):
+    the metric's (8 + gb) N E2 + (gb N + 16) E2 against (gb N + 4 + 4 N + 4) E2 + 20 E2."""
+    if lgp_kept:
+        return ((8 + gb) * N + gb * N + 16) * E2 - ((gb + 4) * N + 8 + 20) * E2
+    if lgp_shared:
+        return 4 * (N - 1) * E2
+    return 0
 
 
 def step_calls(mode, c, stride, gran, budget, dense, bf16=False):
@@ -118,6 +133,9 @@ def main() -> int:
                          "gradient splitter followed by the six calls with the PS fed by its dense parts")
     ap.add_argument("--grad-dtype", default="f32", choices=["f32", "bf16"],
                     help="storage type of the gradient arenas (and of the splitter's dense parts)")
+    ap.add_argument("--keep-stage2-aggregate", default="on", choices=["on", "off"],
+                    help="layer granularity: LGP leaves the aggregate of the stage-2 gradients for "
+                         "the stage-2 call (library default) or every call reads what it needs")
     ap.add_argument("--graph", action="store_true",
                     help="replay each step as a captured HIP graph (element granularity with "
                          "--calls windows only: no call of such a step needs the host)")
@@ -171,6 +189,7 @@ def main() -> int:
           file=sys.stderr, flush=True)
 
     c = job.ctx
+    c.osp_set_keep_stage2_aggregate(args.keep_stage2_aggregate == "on")
     c.osp_set_gib(0, np.ones(wl.n_tensors, np.uint8))     # iteration 1 is BSP (Algorithm 1)
     n2_log = np.zeros(K, dtype=np.int64)
     windows = args.calls == "windows"
@@ -191,6 +210,12 @@ def main() -> int:
     # between two kernels costs about 5 us of idle GPU.  The per-call breakdown of the other calls
     # comes from a second pass after the timed region.
     bracketed = BRACKETED[mode]
+    # LGP over a layer-granular stage 2 keeps the stage-2 aggregate (the warm-up steps have shown
+    # whether it does): the stage-2 call is then a short pass over the kept values and the
+    # aggregate kernel is launched once per step, on stage 1
+    lgp_kept = mode == "six" and c.osp_lgp_kept_aggregate()
+    if lgp_kept:
+        bracketed = ("agg1",)
     ev = [{n: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
            for n in bracketed} if i % BRACKET_EVERY == 0 else None for i in range(K)]
     graphs = None
@@ -248,12 +273,14 @@ def main() -> int:
     ms_per_step = elapsed * 1e3 / K
     gbps = total_bytes / elapsed / 1e9
     lgp_shared = c.osp_lgp_read_shared()
-    moved_bytes = total_bytes - (sum(4 * (N - 1) * int(n2[i]) for i in range(K)) if lgp_shared
-                                 and not element else 0)
+    moved_bytes = total_bytes - sum(bytes_not_moved(N, int(n2[i]), gb, lgp_shared and not element,
+                                                    lgp_kept) for i in range(K))
     if (lgp_shared and element) or mode != "six":  # whole groups / fused passes: not itemised here
         moved_bytes = None
 
-    # dominant kernel: the aggregate+update kernel, launched twice per step
+    # dominant kernel: the aggregate+update kernel (the longest launch of a step and the one
+    # furthest from the roofline; the two install launches together take about as long, see
+    # roofline_other), launched once per step when LGP keeps the stage-2 aggregate, else twice
     fused_rs = windows and (c.osp_windows_fused() & 1) != 0
     kernel = ("k_aggregate_update" if mode == "six" else
               "k_split_gradients" if mode == "packed" else
@@ -268,7 +295,7 @@ def main() -> int:
     roofline = {"bound": "hbm", "kernel": kernel, "achieved": round(agg_gbps, 1),
                 "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(agg_gbps / HBM_PEAK_GBPS, 4),
                 "traffic": (None if wl.name != "vgg16" or c.osp_chunk_elems() != 256 else
-                            AGG_TRAFFIC_VGG16_LAYER if not element and mode == "six" and not bf16 else
+                            AGG_TRAFFIC_VGG16_LAYER if not element and lgp_kept and not bf16 else
                             RS_TRAFFIC_VGG16_ELEMENT if element and fused_rs else None),
                 "launches": agg_launches,
                 "avg_launch_ms": round(agg_ms, 5), "bytes_per_launch": int(agg_bytes)}
@@ -303,6 +330,22 @@ def main() -> int:
                          "launches": K2, "avg_launch_ms": round(ms0, 5),
                          "bytes_per_launch": int(call_bytes[n0] / K2),
                          "note": "events cannot sit inside a graph: taken from the eager second pass"})
+    # the other two kernels that share the step's time with the aggregate, on the bytes they move
+    roofline_other = None
+    if lgp_kept and not element:
+        e2 = [int(x) for x in n2b[:K2]]
+        inst_b = sum(4 * (N + 1) * M for _ in e2)                       # both installs of a step
+        inst_ms = call_ms["apply1"] + call_ms["apply2"]
+        keep_b = sum((gb * N + 4 + 4 * N + 4) * x for x in e2)
+        roofline_other = [
+            {"kernel": "k_apply_stage_sweep (two launches per step)",
+             "achieved": round(inst_b / (inst_ms * 1e-3) / 1e9, 1),
+             "frac": round(inst_b / (inst_ms * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+             "ms_per_step": round(inst_ms / K2, 5)},
+            {"kernel": "k_lgp_keep",
+             "achieved": round(keep_b / (call_ms["lgp"] * 1e-3) / 1e9, 1),
+             "frac": round(keep_b / (call_ms["lgp"] * 1e-3) / 1e9 / HBM_PEAK_GBPS, 4),
+             "ms_per_step": round(call_ms["lgp"] / K2, 5)}]
     calls = {n: {"ms": round(call_ms[n] / K2, 5),
                  "GBps": round(call_bytes[n] / (call_ms[n] * 1e-3) / 1e9, 1) if call_ms[n] > 0 else None}
              for n in names}
@@ -345,7 +388,7 @@ def main() -> int:
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32" if not bf16 else "f32 (gradients stored as bf16)", "data": "synthetic",
         "config": {"workload": f"{wl.name}-shaped", "n_workers": N, "n_tensors": wl.n_tensors,
-                   "n_params": M, "granularity": args.granularity, "calls": args.calls,
+                   "n_params": M, "granularity": args.granularity, "calls": args.calls, "keep_stage2_aggregate": args.keep_stage2_aggregate == "on",
                    "graph_replay": bool(args.graph),
                    "windows_fused": ({"rs": bool(c.osp_windows_fused() & 1),
                                       "ics": bool(c.osp_windows_fused() & 2)} if windows else None),
@@ -355,13 +398,13 @@ def main() -> int:
         "sync_steps_per_s": round(K / elapsed, 2),
         "pct_hbm_peak": round(100.0 * gbps / HBM_PEAK_GBPS, 2),
         "GB_per_step": round(total_bytes / K / 1e9, 4),
-        "lgp_reads_ps_once": bool(lgp_shared),
+        "lgp_reads_ps_once": bool(lgp_shared), "lgp_keeps_stage2_aggregate": bool(lgp_kept),
         "GB_moved_per_step": None if moved_bytes is None else round(moved_bytes / K / 1e9, 4),
         "GBps_on_bytes_moved": None if moved_bytes is None else round(moved_bytes / elapsed / 1e9, 1),
         "calls_second_pass": calls,
         "copy_GBps_same_box": round(copy_gbps, 1),
         "aggregate_pattern_GBps_same_box": None if pattern_gbps is None else round(pattern_gbps, 1),
-        "roofline": roofline,
+        "roofline": roofline, "roofline_other": roofline_other,
         "cpu_baseline": cpu,
         "paper_context": "paper reports up to 50% end-to-end training throughput gain on 8xT4 "
                          "workers + 1 PS over 10 Gbps Ethernet; it never times this arithmetic",

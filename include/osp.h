@@ -93,8 +93,9 @@ typedef struct {
                                       NULL for equal shares 1/N; copied */
     int32_t element_keys;          /* nonzero: osp_ps_aggregate_update also stores every
                                       element's importance key, which makes
-                                      osp_split(OSP_GRAN_ELEMENT) legal (costs 8 B/element of
-                                      workspace: the keys and the kept stage-2 aggregate) */
+                                      osp_split(OSP_GRAN_ELEMENT) legal (costs 4 B/element of
+                                      workspace for the keys, on top of the 4 B/element of
+                                      the kept stage-2 aggregate) */
     int32_t chunk_elems;           /* work-chunk size in elements, multiple of 256;
                                       0 = library default (256: one float4 per lane) */
 } osp_config;
@@ -183,11 +184,15 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
  * grads + w*worker_stride (elements, multiple of 4, >= arena_elems).
  *
  * Both stages of an iteration see one gradient per worker, cut in two by the
- * GIB (Sec. 3.1).  With an element-granular GIB the stage-1 call therefore
- * keeps the aggregate of the stage-2 elements in the workspace, and a stage-2
- * call that is handed the same `grads` pointer and stride reuses it instead of
- * reading the N arenas again: between the two calls these arenas must not
- * change.  A stage-2 call with any other pointer or stride aggregates afresh.
+ * GIB (Sec. 3.1), and LGP reads the stage-2 part as well.  The library reads
+ * that part once where it can: with an element-granular GIB the stage-1 call
+ * keeps the aggregate of the stage-2 elements in the workspace; with a
+ * layer-granular GIB osp_lgp_correct does (N >= 4, replicas in sync, see
+ * osp_set_keep_stage2_aggregate).  A stage-2 call that is handed the same
+ * `grads` pointer and stride reuses the kept aggregate instead of reading the
+ * N arenas again: between the two calls these arenas must not change.  A
+ * stage-2 call with any other pointer or stride aggregates afresh.  Results
+ * are the same bit for bit either way.
  */
 osp_status osp_ps_aggregate_update(osp_ctx *ctx, int stage, const float *grads,
                                    int64_t worker_stride, void *stream);
@@ -274,7 +279,7 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream);
  * stages) the windows run fused kernels: one launch per window (plus the
  * split's), no second read of data a lane already holds.  Otherwise, and
  * where the single-stage kernels are as fast (layer-granular GIB: N > 8 or
- * N x parameters > 2^27; element-granular GIB: RS window N > 16, ICS window
+ * N x parameters > 2^25; element-granular GIB: RS window N > 16, ICS window
  * N > 8), they enqueue the single-stage kernels.  The single calls and
  * the windows may be mixed freely within the order of calls above.
  * The rule on the gradient arenas between the two stages (see
@@ -342,6 +347,19 @@ const char *osp_last_error(const osp_ctx *ctx);
  * arena (replicas known to be in sync) instead of once per replica; 0 otherwise.
  * For callers that account for the bytes a step really moves. */
 int32_t osp_lgp_read_shared(const osp_ctx *ctx);
+
+/* Whether osp_lgp_correct (and the RS window built from it) keeps the aggregate
+ * of a layer-granular stage 2 for the stage-2 call (default: on).  On one GPU
+ * with nothing overlapping the ICS this moves fewer bytes per iteration; it
+ * also makes the RS window, the part inside the barrier (Sec. 3.1), a little
+ * longer (its workgroups write all N replicas instead of sweeping them one by
+ * one), which a caller who overlaps the ICS with compute may not want.
+ * OSP_ERR_BAD_STATE between the two stages of an iteration. */
+osp_status osp_set_keep_stage2_aggregate(osp_ctx *ctx, int32_t on);
+
+/* 1 if the last osp_lgp_correct kept the stage-2 aggregate; 0 otherwise.  For
+ * callers that account for the bytes a step really moves. */
+int32_t osp_lgp_kept_aggregate(const osp_ctx *ctx);
 
 /* Which of the last osp_rs_window (bit 0) and osp_ics_window (bit 1) ran as a
  * fused kernel rather than as the single-stage kernels.  For reports. */

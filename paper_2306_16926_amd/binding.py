@@ -99,6 +99,10 @@ def _load() -> C.CDLL:
     lib.osp_split_gradients_bf16.restype = C.c_int
     lib.osp_ps_aggregate_update_packed_bf16.argtypes = [vp, C.c_int, vp, i64, vp]
     lib.osp_ps_aggregate_update_packed_bf16.restype = C.c_int
+    lib.osp_set_keep_stage2_aggregate.argtypes = [vp, C.c_int32]
+    lib.osp_set_keep_stage2_aggregate.restype = C.c_int
+    lib.osp_lgp_kept_aggregate.argtypes = [vp]
+    lib.osp_lgp_kept_aggregate.restype = C.c_int32
     lib.osp_rs_window.argtypes = [vp, vp, i64, vp]
     lib.osp_rs_window.restype = C.c_int
     lib.osp_ics_window.argtypes = [vp, vp, i64, C.c_int, i64, vp]
@@ -145,7 +149,8 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_rs_window_bf16", "osp_ics_window_bf16",
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_stream_pattern", "osp_ics_upper_bound", "osp_tune_budget",
-           "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused"]
+           "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused",
+           "osp_set_keep_stage2_aggregate", "osp_lgp_kept_aggregate"]
 
 
 def _ptr(t) -> int:
@@ -224,6 +229,12 @@ class Context:
 
     def osp_windows_fused(self) -> int:
         return int(lib.osp_windows_fused(self._h))
+
+    def osp_set_keep_stage2_aggregate(self, on: bool) -> None:
+        self._check(lib.osp_set_keep_stage2_aggregate(self._h, 1 if on else 0))
+
+    def osp_lgp_kept_aggregate(self) -> bool:
+        return bool(lib.osp_lgp_kept_aggregate(self._h))
 
     def osp_n_chunks(self) -> int:
         return int(lib.osp_n_chunks(self._h))

@@ -24,6 +24,7 @@ namespace {
 constexpr int kDefaultChunkElems = kStride;     // one float4 per lane
 constexpr size_t kAlign = 256;
 constexpr int kFanoutMaxWorkers = 4;           // install: fan-out kernel up to here, sweep above
+constexpr int kLgpKeepMinWorkers = 4;          // LGP keeps the stage-2 aggregate from here up
 
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
@@ -73,12 +74,13 @@ struct osp_ctx {
     // replicas_synced: every replica equals the PS on every element (after an iteration that
     // installed both stages, or by the caller's word at bind).  iter_synced: that held when
     // the current iteration began, i.e. the stage-2 replica values are the PS's stale ones.
-    bool replicas_synced = false, iter_synced = false, last_lgp_shared = false;
+    bool replicas_synced = false, iter_synced = false, last_lgp_shared = false, last_lgp_kept = false;
     // element-granular stage 1 leaves the aggregate of the stage-2 elements in the stash;
     // valid for a stage-2 call on the same gradient arenas
     bool pack_index_valid = false;      // the pack index matches the current GIB
     int windows_fused = 0;              // bit 0: last RS window ran fused, bit 1: last ICS window
     bool stash_valid = false;
+    bool keep_stage2 = true;            // LGP over a layer-granular stage 2 keeps its aggregate
     const void *stash_grads = nullptr;
     long long stash_stride = 0;
     bool stash_bf16 = false;
@@ -196,9 +198,9 @@ void layout_workspace(osp_ctx *c)
     c->off_state = take(sizeof(SplitState));
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
     c->off_pack = take((2 * (nc + 1) + 2 * (size_t)c->n_pack_blocks()) * sizeof(long long));
+    c->off_stash = take((size_t)c->arena * sizeof(float));
     if (c->element_keys) {
         c->off_key = take((size_t)c->arena * sizeof(uint32_t));
-        c->off_stash = take((size_t)c->arena * sizeof(float));
         c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
         // three histograms, then the length of the tie-candidate list (cleared with them)
         c->off_hist = take(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long));
@@ -373,6 +375,19 @@ static void launch_aggregate_packed(int variant, dim3 grid, dim3 block, hipStrea
     }
 }
 
+template <typename GT>
+static void launch_lgp_keep(const osp_ctx *ctx, const LgpKeepArgs &a, unsigned n_groups, hipStream_t s)
+{
+    const dim3 grid(n_groups), block(kBlock);
+    const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    switch (variant) {
+    case 0: k_lgp_keep<false, false, GT><<<grid, block, 0, s>>>(a); break;
+    case 1: k_lgp_keep<false, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 2: k_lgp_keep<true, false, GT><<<grid, block, 0, s>>>(a); break;
+    default: k_lgp_keep<true, true, GT><<<grid, block, 0, s>>>(a); break;
+    }
+}
+
 extern "C" {
 
 osp_status osp_create(const osp_config *cfg, osp_ctx **out)
@@ -494,6 +509,18 @@ int32_t osp_lgp_read_shared(const osp_ctx *ctx) { return ctx && ctx->last_lgp_sh
 
 int32_t osp_windows_fused(const osp_ctx *ctx) { return ctx ? ctx->windows_fused : 0; }
 
+int32_t osp_lgp_kept_aggregate(const osp_ctx *ctx) { return ctx && ctx->last_lgp_kept ? 1 : 0; }
+
+osp_status osp_set_keep_stage2_aggregate(osp_ctx *ctx, int32_t on)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (stage2_pending(ctx))
+        return fail(ctx, OSP_ERR_BAD_STATE, "the option cannot change between the two stages");
+    ctx->keep_stage2 = on != 0;
+    return OSP_OK;
+}
+
 int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->n_chunks : 0; }
 
 const char *osp_last_error(const osp_ctx *ctx)
@@ -585,6 +612,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
     ctx->replicas_synced = buf->replicas_in_sync != 0;
     ctx->iter_synced = false;
     ctx->stash_valid = false;
+    ctx->last_lgp_kept = false;
     ctx->pack_index_valid = false;
     ctx->windows_fused = 0;
     ctx->have_gib = false;
@@ -752,7 +780,8 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
         a.stash = ctx->d_stash();
         a.partial_other = ctx->d_partial(1);
     }
-    const bool from_stash = masked && stage == 2 && ctx->stash_valid && ctx->stash_grads == grads &&
+    const bool from_stash = (masked || listed) && stage == 2 && ctx->stash_valid &&
+                            ctx->stash_grads == grads &&
                             ctx->stash_stride == (long long)worker_stride && ctx->stash_bf16 == bf16;
     a.n_workers = ctx->n_workers;
     a.stage = stage;
@@ -772,7 +801,10 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
         sa.stash = ctx->d_stash();
         sa.lr = ctx->lr;
         sa.mu = ctx->mu;
-        k_update_from_stash<<<grid, block, 0, s>>>(sa);
+        if (masked)
+            k_update_from_stash<true><<<grid, block, 0, s>>>(sa);
+        else if (n_groups > 0)
+            k_update_from_stash<false><<<grid, block, 0, s>>>(sa);
     } else if (n_groups > 0) {        // an empty stage launches nothing
         if (variant == 4 || variant == 6)
             return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
@@ -850,7 +882,39 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
     // element-granular GIB, this iteration's stage 1 already installed.
     const bool shared_read = ctx->iter_synced && !ctx->agg2 && (!masked || ctx->applied1);
     ctx->last_lgp_shared = shared_read;
-    if (shared_read) {
+    // Layer-granular stage 2, several workers: the pass that has every worker's stage-2
+    // gradients in hand also leaves their aggregate for the stage-2 call (one read of the N
+    // arenas' stage-2 part per iteration instead of two).
+    const bool keep = shared_read && !masked && ctx->keep_stage2 && ctx->n_workers >= kLgpKeepMinWorkers;
+    ctx->last_lgp_kept = keep;
+    if (keep) {
+        LgpKeepArgs a;
+        a.spans = table;
+        a.chunk_elems = ctx->chunk_elems;
+        a.P = ctx->P;
+        a.Pw = ctx->Pw;
+        a.param_stride = ctx->param_stride;
+        a.grads = grads;
+        a.worker_stride = worker_stride;
+        a.weights = ctx->d_weights();
+        a.partial = ctx->d_partial(1);
+        a.key = ctx->element_keys ? ctx->d_key() : nullptr;
+        a.stash = ctx->d_stash();
+        a.n_workers = ctx->n_workers;
+        a.inv_n = 1.0f / (float)ctx->n_workers;
+        a.lr = ctx->lr;
+        const unsigned n_groups = n_spans * kSpanChunks;
+        if (n_groups > 0) {
+            if (bf16)
+                launch_lgp_keep<bf16_t>(ctx, a, n_groups, s);
+            else
+                launch_lgp_keep<float>(ctx, a, n_groups, s);
+        }
+        ctx->stash_valid = true;
+        ctx->stash_grads = grads;
+        ctx->stash_stride = (long long)worker_stride;
+        ctx->stash_bf16 = bf16;
+    } else if (shared_read) {
         LgpSweepArgs a;
         a.spans = table;
         a.bitmap = bitmap;
@@ -1036,9 +1100,10 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
 
 // Largest N for which the element-granular RS window keeps all gradients of a group in registers.
 constexpr int kRsElementMaxWorkers = 16;
-// Layer-granular windows run fused up to this many gradient elements (N x parameters): measured
-// on MI355X the fused launch wins below about 1e8 (launch-bound steps) and loses 1-2 % above.
-constexpr long long kWindowLayerMaxGradElems = 128LL << 20;
+// Layer-granular windows run fused up to this many gradient elements (N x parameters), where a
+// step is bound by its launches.  Above, the single-stage kernels win: LGP there keeps the
+// stage-2 aggregate, which the fused launch does not (it reads the stage-2 gradients twice).
+constexpr long long kWindowLayerMaxGradElems = 32LL << 20;
 
 static bool layer_window_fused(const osp_ctx *ctx)
 {
@@ -1136,6 +1201,7 @@ static osp_status rs_window(osp_ctx *ctx, const void *grads, int64_t worker_stri
     ctx->stash_stride = (long long)worker_stride;
     ctx->stash_bf16 = bf16;
     ctx->agg1 = ctx->applied1 = ctx->lgp_done = ctx->last_lgp_shared = true;
+    ctx->last_lgp_kept = false;
     ctx->agg2 = ctx->single_pass = ctx->applied2 = false;
     return OSP_OK;
 }

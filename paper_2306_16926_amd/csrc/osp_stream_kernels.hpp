@@ -350,9 +350,10 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
     }
 }
 
-// Stage 2 of an element-granular iteration whose stage 1 left the aggregate in the
-// stash: V = mu V + gbar, P = P - lr V on the stage-2 elements; keys and importance
-// of these elements were written by stage 1.
+// Stage 2 of an iteration whose aggregate is already in the stash (left there by an
+// element-granular stage 1, or by LGP over a layer-granular stage 2): V = mu V + gbar,
+// P = P - lr V on the stage-2 elements; their keys and importance were written with it.
+// MASKED: element-granular GIB over all spans; otherwise the stage-2 span table.
 struct StashArgs {
     const Span *spans;
     int chunk_elems;
@@ -363,6 +364,7 @@ struct StashArgs {
     float lr, mu;
 };
 
+template <bool MASKED>
 __global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
 {
     Piece c;
@@ -373,7 +375,7 @@ __global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
     const float *Sc = a.stash + c.start;
     for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
         const int rem = (int)c.len - (int)i;
-        const unsigned m = lane_mask<true>(rem, c.start + i, 2, a.bitmap);
+        const unsigned m = lane_mask<MASKED>(rem, c.start + i, 2, a.bitmap);
         const f4 p = ld_stream(Pc + i);
         const f4 v = ld_stream(Vc + i);
         const f4 gbar = ld_stream(Sc + i);
@@ -382,8 +384,8 @@ __global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
         const f4 step = vn * a.lr;
         const f4 pn = p - step;
         if (rem >= kVec) {
-            st_stream(Vc + i, blend(m, vn, v));
-            st_stream(Pc + i, blend(m, pn, p));
+            st_stream(Vc + i, MASKED ? blend(m, vn, v) : vn);
+            st_stream(Pc + i, MASKED ? blend(m, pn, p) : pn);
         } else {
 #pragma unroll
             for (int j = 0; j < kVec; ++j)
@@ -573,6 +575,124 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
                     pw[i + t] = pn[t];
         }
     }
+}
+
+// ---------------------------------------------------------------------------
+// LGP that keeps the stage-2 aggregate (layer-granular GIB, replicas in sync).
+// LGP reads every worker's stage-2 gradients, and so does the stage-2 aggregate
+// a little later.  Here one workgroup owns a chunk of ALL workers: with a block
+// of gradients in registers it writes each replica's estimate P - lr g_w (P: the
+// PS arena, which holds the replicas' stale values), adds the block to the
+// aggregate in the aggregate's own order, and finally leaves the aggregate, its
+// importance and keys in the workspace.  The stage-2 call on the same gradient
+// arenas then needs one stream instead of N (k_update_from_stash).
+// ---------------------------------------------------------------------------
+struct LgpKeepArgs {
+    const Span *spans;                 // stage-2 span table
+    int chunk_elems;
+    const float *P;
+    float *Pw;
+    long long param_stride;
+    const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
+    long long worker_stride;
+    const float *weights;              // WEIGHTED
+    double *partial;                   // [n_chunks] importance partial of stage 2
+    uint32_t *key;                     // KEYS
+    float *stash;
+    int n_workers;
+    float inv_n, lr;
+};
+
+// B consecutive workers: their replicas' LGP values are stored (m: which of the lane's 4
+// elements exist), then their gradients join the running sum as in add_workers.
+template <int B, bool WEIGHTED, typename GT>
+__device__ __forceinline__ void lgp_and_add(f4 &acc, int w0, const GT *__restrict__ g0,
+                                            long long worker_stride, unsigned i,
+                                            const float *__restrict__ weights, f4 p, float lr,
+                                            float *__restrict__ w_base, long long param_stride,
+                                            unsigned m)
+{
+    f4 g[B];
+#pragma unroll
+    for (int j = 0; j < B; ++j)
+        g[j] = ld_grad<GT>(g0 + (long long)(w0 + j) * worker_stride + i);
+#pragma unroll
+    for (int j = 0; j < B; ++j) {
+        const f4 step = g[j] * lr;
+        const f4 pn = p - step;
+        float *dst = w_base + (long long)(w0 + j) * param_stride + i;
+        if (m == 0xFu) {
+            st_stream(dst, pn);
+        } else {
+#pragma unroll
+            for (int t = 0; t < kVec; ++t)
+                if (m & (1u << t))
+                    dst[t] = pn[t];
+        }
+    }
+    if (WEIGHTED) {
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            g[j] = g[j] * weights[w0 + j];
+    }
+    f4 s = g[0];
+    if (w0 != 0)
+        s = acc + s;
+#pragma unroll
+    for (int j = 1; j < B; ++j)
+        s = s + g[j];
+    acc = s;
+}
+
+template <bool WEIGHTED, bool KEYS, typename GT = float>
+__global__ __launch_bounds__(kBlock) void k_lgp_keep(const LgpKeepArgs a)
+{
+    Piece c;
+    if (!owned_piece(a.spans, a.chunk_elems, c))
+        return;
+    const int N = a.n_workers;
+    const float *Pc = a.P + c.start;
+    float *Wc = a.Pw + c.start;
+    const GT *Gc = static_cast<const GT *>(a.grads) + c.start;
+    double imp = 0.0;
+    for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
+        const int rem = (int)c.len - (int)i;
+        const unsigned m = rem >= kVec ? 0xFu : ((1u << rem) - 1u);
+        const f4 p = ld_stream(Pc + i);
+        f4 acc;
+        int w = 0;
+        for (; w + kWorkerBlock <= N; w += kWorkerBlock)
+            lgp_and_add<kWorkerBlock, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights, p, a.lr,
+                                                    Wc, a.param_stride, m);
+        const int rest = N - w;
+        if (rest & 8) { lgp_and_add<8, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights, p, a.lr, Wc, a.param_stride, m); w += 8; }
+        if (rest & 4) { lgp_and_add<4, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights, p, a.lr, Wc, a.param_stride, m); w += 4; }
+        if (rest & 2) { lgp_and_add<2, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights, p, a.lr, Wc, a.param_stride, m); w += 2; }
+        if (rest & 1) { lgp_and_add<1, WEIGHTED, GT>(acc, w, Gc, a.worker_stride, i, a.weights, p, a.lr, Wc, a.param_stride, m); }
+        const f4 gbar = WEIGHTED ? acc : acc * a.inv_n;
+        const f4 prod = gbar * p;
+        const f4 q = abs4(prod);
+        if (m & 1u) imp += (double)q.x;        // (the order k_aggregate_update adds them in)
+        if (m & 2u) imp += (double)q.y;
+        if (m & 4u) imp += (double)q.z;
+        if (m & 8u) imp += (double)q.w;
+        if (m == 0xFu) {
+            st_stream(a.stash + c.start + i, gbar);
+            if (KEYS)
+                st_stream(reinterpret_cast<float *>(a.key + c.start + i), keys4(q));
+        } else {
+#pragma unroll
+            for (int t = 0; t < kVec; ++t)
+                if (m & (1u << t)) {
+                    a.stash[c.start + i + t] = gbar[t];
+                    if (KEYS)
+                        a.key[c.start + i + t] = importance_key(q[t]);
+                }
+        }
+    }
+    const double total = wave_sum(imp);
+    if (threadIdx.x == 0)
+        a.partial[c.chunk] = total;
 }
 
 // ---------------------------------------------------------------------------

@@ -35,6 +35,21 @@ def test_bf16_gradients_halve_only_the_gradient_reads():
     assert sum(f32[n] - b16[n] for n in SIX) == 2 * N * M + 2 * N * E2
 
 
+def test_bytes_not_moved_are_itemised():
+    """LGP that keeps the stage-2 aggregate: N grads + P read, N replicas + aggregate written;
+    stage 2 then reads P, V, aggregate and writes P, V."""
+    N, E2 = 16, 1000
+    b = bench.step_bytes(N, 4000, E2, element=False)
+    moved = 4 * (N + 1) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
+    assert b["lgp"] + b["agg2"] - bench.bytes_not_moved(N, E2, 4, True, True) == moved
+    assert bench.bytes_not_moved(N, E2, 4, True, False) == 4 * (N - 1) * E2
+    assert bench.bytes_not_moved(N, E2, 4, False, False) == 0
+    # bfloat16 arenas: gradients are 2 bytes
+    b2 = bench.step_bytes(N, 4000, E2, element=False, gb=2)
+    moved2 = (2 * N + 4) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
+    assert b2["lgp"] + b2["agg2"] - bench.bytes_not_moved(N, E2, 2, True, True) == moved2
+
+
 def test_more_than_one_gpu_is_refused_with_a_message():
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"],
                        capture_output=True, text=True, timeout=120)

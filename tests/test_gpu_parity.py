@@ -291,6 +291,70 @@ def test_element_stage2_gradient_sources(stage2_input):
             compare_gib(job, o, f"element split, step {step}")
 
 
+@pytest.mark.parametrize("stage2_input", ["same_buffer", "other_values", "other_stride"])
+@pytest.mark.parametrize("n_workers,keep", [(6, True), (6, False), (3, True), (19, True)])
+def test_layer_lgp_keeps_stage2_aggregate(stage2_input, n_workers, keep):
+    """Layer-granular GIB, replicas in sync, N >= 4: LGP leaves the aggregate of the stage-2
+    gradients (with importance and keys) for the stage-2 call, which uses it only when it is
+    handed the very arenas LGP read; any other buffer is aggregated afresh.  The option
+    switches it off; below 4 workers it is not used.  Results equal the oracle's either way."""
+    say("layer kept aggregate", stage2_input, n_workers, keep)
+    wl = W.custom([37, 1, 128, 5, 9000, 64, 3, 4096, 4097, 30001], n_workers, 0.5, align=4,
+                  config_id=24)
+    rng = np.random.default_rng(12)
+    arena = wl.arena_elems()
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    wts = None
+    if n_workers == 19:
+        wts = rng.random(n_workers).astype(F); wts /= wts.sum()
+    o = make_oracle(wl, weights=wts)
+    job = device_job(wl, weights=wts, element_keys=True)
+    c = job.ctx
+    c.osp_set_keep_stage2_aggregate(keep)
+    for step in range(4):
+        gib = random_layer_gib(rng, wl.n_tensors)
+        if step == 3:
+            gib[:] = 0                                  # everything in stage 2
+        o.set_gib(GRAN_LAYER, gib); c.osp_set_gib(GRAN_LAYER, gib)
+        g1 = wl.make_grads(0, step)
+        stride1 = g1.shape[1]
+        if stage2_input == "other_values":
+            g2 = wl.make_grads(1, step)
+        elif stage2_input == "other_stride":
+            g2 = np.zeros((wl.n_workers, stride1 + 8), F)
+            g2[:, :stride1] = g1
+        else:
+            g2 = g1
+        gd1 = job.upload_grads(g1)
+        gd2 = gd1 if stage2_input == "same_buffer" else job.upload_grads(g2)
+        o.ps_aggregate_update(1, g1); c.osp_ps_aggregate_update(1, gd1, stride1)
+        if step != 1:                                   # LGP before or after the install
+            o.apply_stage(1); c.osp_apply_stage(1)
+        o.lgp_correct(g1); c.osp_lgp_correct(gd1, stride1)
+        assert c.osp_lgp_read_shared()
+        assert c.osp_lgp_kept_aggregate() == (keep and n_workers >= 4)
+        compare_state(job, o, "lgp")
+        if step == 1:
+            o.apply_stage(1); c.osp_apply_stage(1)
+        if step == 2:
+            with pytest.raises(Exception):
+                c.osp_set_keep_stage2_aggregate(not keep)   # not between the two stages
+        o.ps_aggregate_update(2, g2); c.osp_ps_aggregate_update(2, gd2, g2.shape[1])
+        compare_state(job, o, "agg2")
+        o.apply_stage(2); c.osp_apply_stage(2)
+        compare_state(job, o, "apply2")
+        keys = c.osp_get_keys()
+        assert np.array_equal(keys[real], o.keys()[real]), "element keys"
+        if step % 2 == 0:
+            o.split(GRAN_LAYER, wl.budget); c.osp_split(GRAN_LAYER, wl.budget)
+            imp = c.osp_get_importance()
+            assert np.allclose(imp, o.importance, rtol=1e-12, atol=0)
+            compare_gib(job, o, f"layer split, step {step}")
+        else:
+            o.split(GRAN_ELEMENT, wl.budget); c.osp_split(GRAN_ELEMENT, wl.budget)
+            compare_gib(job, o, f"element split after layer stages, step {step}")
+
+
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
 @pytest.mark.parametrize("order", ["rs_lgp_last", "lgp_before_install", "lgp_after_stage2", "no_install1"])
 @pytest.mark.parametrize("n_workers", [3, 12])
