@@ -372,68 +372,3 @@ def osp_ics_upper_bound(bandwidth_elems_per_s, loss_rate, t_compute_s, n_workers
 
 def osp_tune_budget(epoch, loss_i, loss_1, u_max, model_elems) -> int:
     return int(lib.osp_tune_budget(epoch, loss_i, loss_1, u_max, model_elems))
-
-
-# module-level aliases with the C names, taking the context first
-def osp_split(ctx: Context, granularity, budget_elems, stream=None):
-    return ctx.osp_split(granularity, budget_elems, stream)
-
-
-def osp_ps_aggregate_update(ctx: Context, stage, grads, worker_stride, stream=None):
-    return ctx.osp_ps_aggregate_update(stage, grads, worker_stride, stream)
-
-
-def osp_lgp_correct(ctx: Context, grads, worker_stride, stream=None):
-    return ctx.osp_lgp_correct(grads, worker_stride, stream)
-
-
-def osp_ps_aggregate_update_bf16(ctx: Context, stage, grads, worker_stride, stream=None):
-    return ctx.osp_ps_aggregate_update_bf16(stage, grads, worker_stride, stream)
-
-
-def osp_lgp_correct_bf16(ctx: Context, grads, worker_stride, stream=None):
-    return ctx.osp_lgp_correct_bf16(grads, worker_stride, stream)
-
-
-def osp_apply_stage(ctx: Context, stage, stream=None):
-    return ctx.osp_apply_stage(stage, stream)
-
-
-def osp_split_gradients(ctx: Context, grads, worker_stride, g_important, important_stride,
-                        g_unimportant, unimportant_stride, stream=None):
-    return ctx.osp_split_gradients(grads, worker_stride, g_important, important_stride,
-                                   g_unimportant, unimportant_stride, stream)
-
-
-def osp_ps_aggregate_update_packed(ctx: Context, stage, packed, packed_stride, stream=None):
-    return ctx.osp_ps_aggregate_update_packed(stage, packed, packed_stride, stream)
-
-
-def osp_split_gradients_bf16(ctx: Context, grads, worker_stride, g_important, important_stride,
-                             g_unimportant, unimportant_stride, stream=None):
-    return ctx.osp_split_gradients_bf16(grads, worker_stride, g_important, important_stride,
-                                        g_unimportant, unimportant_stride, stream)
-
-
-def osp_ps_aggregate_update_packed_bf16(ctx: Context, stage, packed, packed_stride, stream=None):
-    return ctx.osp_ps_aggregate_update_packed_bf16(stage, packed, packed_stride, stream)
-
-
-def osp_rs_window(ctx: Context, grads, worker_stride, stream=None):
-    return ctx.osp_rs_window(grads, worker_stride, stream)
-
-
-def osp_ics_window(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
-    return ctx.osp_ics_window(grads, worker_stride, granularity, budget_elems, stream)
-
-
-def osp_rs_window_bf16(ctx: Context, grads, worker_stride, stream=None):
-    return ctx.osp_rs_window_bf16(grads, worker_stride, stream)
-
-
-def osp_ics_window_bf16(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
-    return ctx.osp_ics_window_bf16(grads, worker_stride, granularity, budget_elems, stream)
-
-
-def osp_sync_step(ctx: Context, grads, worker_stride, granularity, budget_elems, stream=None):
-    return ctx.osp_sync_step(grads, worker_stride, granularity, budget_elems, stream)

@@ -56,9 +56,19 @@ def test_worker_counts(n_workers):
 
 @pytest.mark.parametrize("name,gran", [("resnet18", GRAN_LAYER), ("resnet18", GRAN_ELEMENT),
                                        ("resnet50", GRAN_LAYER), ("resnet50", GRAN_ELEMENT)])
-def test_cnn_shaped_two_steps(name, gran):
+def test_cnn_shaped_three_steps(name, gran):
+    """Three chained iterations: the GIB of iteration t is the one iteration t-1 produced
+    (Sec. 4.1.1), so the third step runs on a GIB that itself came from a staged step."""
     say(name, gran)
-    sizes = run_steps(W.get(name), gran, 2, threads=8)
+    sizes = run_steps(W.get(name), gran, 3, threads=8)
+    assert sizes[-1] > 0
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_resnet18_shaped_other_seeds(seed, gran):
+    say("resnet18 seed", seed, gran)
+    sizes = run_steps(W.get("resnet18"), gran, 3, seed=seed, threads=8)
     assert sizes[-1] > 0
 
 
@@ -125,83 +135,82 @@ def test_full_size_resnet152_layer_windows():
 
 def test_full_size_bert_base_layer():
     say("full size bert_base")
-    sizes = full_size_steps("bert_base", 2)
+    sizes = full_size_steps("bert_base", 3)
     assert sizes[-1] > 0
 
 
 def test_full_size_vgg16_layer():
     say("full size vgg16")
-    sizes = full_size_steps("vgg16", 2)
+    sizes = full_size_steps("vgg16", 3)
     assert sizes[-1] == 35_597_096                 # everything but the 102.76 M-element fc tensor
 
 
-def test_full_size_resnet152_element_properties():
-    """Element granularity at full size: keys bit-exact against the oracle, and
-    the partition checked through the three properties that determine it
-    uniquely (size, threshold, ties taken in index order); the oracle's own
-    split is a full sort and is compared directly only at smaller sizes."""
-    say("full size resnet152 element")
+def full_size_element(name):
+    """Element granularity at full size, in the benchmark's launch configuration: three
+    chained iterations (a BSP step, the six single calls, the two windows), each on the
+    bitmap the iteration before produced.  After every iteration: P, V and every replica
+    element by element, the keys bit-exact, the bitmap bit-exact.  The expected bitmap of the
+    first iteration is the oracle's own split (a full sort); the later ones are built from the
+    oracle's keys by selection (brute.select_element_bits), which a CPU test pins to that sort."""
     from paper_2306_16926_amd.device import DeviceJob
-    wl = W.get("resnet152")
+    wl = W.get(name)
     stride, arena = wl.worker_stride(), wl.arena_elems()
     o = make_oracle(wl, omp=True, param_stride=stride)
     job = DeviceJob(wl.numel, wl.offsets(), arena, wl.n_workers, wl.lr, wl.momentum,
                     wl.make_params(0), element_keys=True, param_stride=stride)
+    c = job.ctx
+    real = brute.real_mask(wl.numel, wl.offsets(), arena)
+    k = wl.budget
+
+    def compare(tag, full_sort):
+        P, V, Pw = job.download()
+        close_enough(P, o.P, tag + " P"); close_enough(V, o.V, tag + " V")
+        for w in range(wl.n_workers):              # row by row: bounded temporaries
+            close_enough(Pw[w, :arena], o.Pw[w, :arena], f"{tag} Pw[{w}]")
+        del P, V, Pw
+        okeys = o.keys()
+        assert np.array_equal(c.osp_get_keys()[real], okeys[real]), tag + " keys"
+        if full_sort:
+            say("   ", tag, "oracle split (full sort)")
+            o.split(GRAN_ELEMENT, k)
+        else:
+            o.set_gib(GRAN_ELEMENT, brute.select_element_bits(okeys, real, k, arena))
+        _, bits, n2 = c.osp_get_gib()
+        assert n2 == k == o.n_stage2
+        assert np.array_equal(bits, o.gib_bits), tag + " element bitmap"
+
+    say(" ", name, "step 0: BSP pass + element split")
     g = wl.make_grads(0, 0, stride=stride, threads=16)
     gd = job.upload_grads(g)
-    o.ps_aggregate_update(0, g)
-    job.ctx.osp_ps_aggregate_update(0, gd, stride)
-    real = brute.real_mask(wl.numel, wl.offsets(), arena)
-    keys = job.ctx.osp_get_keys()
-    okeys = o.keys()
-    assert np.array_equal(keys[real], okeys[real])
-    k = wl.budget
-    job.ctx.osp_split(GRAN_ELEMENT, k)
-    _, bits, n2 = job.ctx.osp_get_gib()
-    imp = np.unpackbits(bits.view(np.uint8), bitorder="little")[:arena] == 1
-    assert imp[~real].all()                        # padding is never selected
-    s2 = ~imp & real
-    assert n2 == k == int(s2.sum())
-    T = okeys[s2].max()
-    assert T <= okeys[imp & real].min()
-    tie = real & (okeys == T)
-    tie_idx = np.nonzero(tie)[0]
-    taken = s2[tie_idx]
-    assert (np.diff(taken.astype(np.int8)) <= 0).all()      # taken ties come first in index order
-    assert (okeys[s2] <= T).all() and s2[real & (okeys < T)].all()
-    # then run the staged calls on that bitmap against the oracle (masked kernels at full size)
-    o.set_gib(GRAN_ELEMENT, bits)
+    o.ps_aggregate_update(0, g); o.apply_stage(0)
+    c.osp_ps_aggregate_update(0, gd, stride); c.osp_apply_stage(0); c.osp_split(GRAN_ELEMENT, k)
+    compare("step 0", True)
+    say(" ", name, "step 1: six calls on the element bitmap")
     g = wl.make_grads(0, 1, stride=stride, threads=16, out=g)
     gd = job.upload_grads(g)
     o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
     o.ps_aggregate_update(2, g); o.apply_stage(2)
-    c = job.ctx
-    c.osp_ps_aggregate_update(1, gd, stride); c.osp_apply_stage(1); c.osp_lgp_correct(gd, stride)
-    c.osp_ps_aggregate_update(2, gd, stride); c.osp_apply_stage(2)
-    P, V, Pw = job.download()
-    close_enough(P, o.P, "P"); close_enough(V, o.V, "V")
-    for w in range(wl.n_workers):
-        close_enough(Pw[w, :arena], o.Pw[w, :arena], f"Pw[{w}]")
-    # and once more through the two windows (fused kernels at full size); the element split that
-    # closes the window is checked through the keys it ranks
-    say("  windows")
+    job.sync_step(gd, GRAN_ELEMENT, k)
+    compare("step 1", False)
+    say(" ", name, "step 2: the two windows")
     g = wl.make_grads(0, 2, stride=stride, threads=16, out=g)
     gd = job.upload_grads(g)
     o.ps_aggregate_update(1, g); o.apply_stage(1); o.lgp_correct(g)
     o.ps_aggregate_update(2, g); o.apply_stage(2)
     c.osp_rs_window(gd, stride); c.osp_ics_window(gd, stride, GRAN_ELEMENT, k)
-    P, V, Pw = job.download()
-    close_enough(P, o.P, "P"); close_enough(V, o.V, "V")
-    for w in range(wl.n_workers):
-        close_enough(Pw[w, :arena], o.Pw[w, :arena], f"Pw[{w}]")
-    assert np.array_equal(c.osp_get_keys()[real], o.keys()[real])
-    _, bits, n2 = c.osp_get_gib()
-    assert n2 == k
+    assert c.osp_windows_fused() & 1, "the RS window is expected to run fused at this size"
+    compare("step 2", False)
 
 
-# --------------------------------------------------------------------------
-# each call on its own, with an injected GIB
-# --------------------------------------------------------------------------
+def test_full_size_resnet152_element():
+    say("full size resnet152 element")
+    full_size_element("resnet152")
+
+
+def test_full_size_vgg16_element():
+    say("full size vgg16 element")
+    full_size_element("vgg16")
+
 
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
 def test_calls_one_by_one_with_injected_gib(gran):

@@ -486,6 +486,28 @@ def test_split_element_matches_bruteforce_tiny(frac):
     assert same(o.keys()[b.real], b.keys()[b.real])
 
 
+@pytest.mark.parametrize("frac", [0.0, 0.3, 1.0])
+@pytest.mark.parametrize("ties", [False, True])
+def test_selection_helper_equals_the_oracles_full_sort(frac, ties):
+    """brute.select_element_bits (selection on given keys; used as the expected bitmap where
+    the oracle's full sort takes too long) against the oracle's own split."""
+    wl = W.get("tiny")
+    o = make_oracle(wl)
+    g = wl.make_grads(0, 0)
+    if ties:                                      # few distinct magnitudes: long runs of equal keys
+        g = (np.round(g * F(2000.0)) / F(2000.0)).astype(F)
+        o.P[:] = np.sign(o.P) * F(0.25)
+    o.ps_aggregate_update(0, g)
+    budget = int(frac * wl.n_params)
+    real = brute.real_mask(wl.numel, wl.offsets(), wl.arena_elems())
+    keys = o.keys()
+    if ties:
+        assert np.unique(keys[real]).size < 200
+    want = brute.select_element_bits(keys, real, budget, wl.arena_elems())
+    o.split(GRAN_ELEMENT, budget)
+    assert same(o.gib_bits, want)
+
+
 def test_split_element_rejects_bad_budget():
     wl = W.get("tiny")
     o = make_oracle(wl)
