@@ -145,6 +145,31 @@ osp_status osp_set_hyper(osp_ctx *ctx, float lr, float momentum);
  */
 osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *stream);
 
+/*
+ * osp_split(OSP_GRAN_ELEMENT) for callers that cannot allocate device memory and
+ * have no bound workspace at hand: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  Stateless: no context.  Selects the
+ * budget_elems smallest of n_elems importance keys in the order (key ascending,
+ * index ascending) and writes the element bitmap (bit k%32 of word k/32, 0 =
+ * stage 2; [ceil(n_elems/32)] words, bits beyond n_elems come out 1).
+ *   keys:        DEVICE, 16-byte aligned, [n_elems]; importance keys as
+ *                osp_get_keys returns them (elements that must never be selected,
+ *                such as padding, carry 0xFFFFFFFF; budget_elems must not exceed
+ *                the number of other keys).  Read-only.
+ *   elem_bitmap: DEVICE, 4-byte aligned, caller-owned, overwritten.
+ *   n_elems:     positive multiple of 4, at most 2^28 (OSP_ERR_UNSUPPORTED above).
+ * The histograms, counters, tie candidates and per-tile counts live in an array
+ * of 1.5 MB that is part of the library's image on every GPU it runs on (held
+ * until the process ends); the call clears what must start at zero with a fill
+ * kernel, launches the kernels osp_split launches, and calls no allocating
+ * routine.  Every call on one GPU uses that GPU's one array: calls that overlap
+ * in time on one GPU (two streams, two threads) race; order them.  Enqueues on
+ * `stream` and returns without waiting; errors as everywhere (message through
+ * osp_last_error(NULL)).
+ */
+osp_status osp_split_element_static(const uint32_t *keys, int64_t n_elems, int64_t budget_elems,
+                                    uint32_t *elem_bitmap, void *stream);
+
 /* Read the current GIB back (synchronizes `stream`).  Any of the three outputs
  * may be NULL.  layer_gib: [L] bytes, 1 = important (stage 1), 0 = stage 2;
  * only written when the current GIB is layer-granular.  elem_bitmap:

@@ -73,6 +73,8 @@ def _load() -> C.CDLL:
     lib.osp_set_hyper.restype = C.c_int
     lib.osp_split.argtypes = [vp, C.c_int, i64, vp]
     lib.osp_split.restype = C.c_int
+    lib.osp_split_element_static.argtypes = [vp, i64, i64, vp, vp]
+    lib.osp_split_element_static.restype = C.c_int
     lib.osp_get_gib.argtypes = [vp, vp, vp, C.POINTER(i64), vp]
     lib.osp_get_gib.restype = C.c_int
     lib.osp_read_n_stage2_async.argtypes = [vp, vp, vp]
@@ -141,7 +143,7 @@ def _load() -> C.CDLL:
 lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
-           "osp_split", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
+           "osp_split", "osp_split_element_static", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window", "osp_sync_step",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_split_gradients_bf16", "osp_ps_aggregate_update_packed_bf16",
@@ -350,6 +352,13 @@ class Context:
         key = np.zeros(self.arena_elems, np.uint32)
         self._check(lib.osp_get_keys(self._h, key.ctypes.data, _stream(stream)))
         return key
+
+
+def osp_split_element_static(keys, n_elems: int, budget_elems: int, elem_bitmap, stream=None) -> None:
+    st = lib.osp_split_element_static(_ptr(keys), int(n_elems), int(budget_elems),
+                                      _ptr(elem_bitmap), _stream(stream))
+    if st != OSP_OK:
+        raise OspError(st, lib.osp_last_error(None).decode())
 
 
 def osp_stream_copy(dst, src, nbytes: int, stream=None) -> None:

@@ -388,6 +388,87 @@ static void launch_lgp_keep(const osp_ctx *ctx, const LgpKeepArgs &a, unsigned n
     }
 }
 
+// The launches of one element-granular selection: `budget` smallest keys in the order
+// (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch; hist is
+// (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the length of the
+// candidate list), cleared here by a fill kernel.
+struct SelectScratch {
+    SplitState *state;
+    unsigned long long *hist;
+    TieCandidate *cand;
+    unsigned int *tile_ties;
+    unsigned long long *tile_before;
+};
+
+static void enqueue_element_select(const uint32_t *key, long long n_vec, long long n_words,
+                                   long long n_tiles, long long budget, const SelectScratch &w,
+                                   uint32_t *bitmap, hipStream_t s)
+{
+    unsigned long long *h0 = w.hist, *h1 = w.hist + kRadixBins, *h2 = w.hist + 2 * kRadixBins;
+    unsigned int *n_cand = reinterpret_cast<unsigned int *>(w.hist + 3 * kRadixBins);
+    long long want = (n_vec + kSplitBlock - 1) / kSplitBlock;
+    const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
+    k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(w.hist),
+                                          (long long)(3 * kRadixBins + 1) * 2, 0u);
+    k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h0);
+    k_select_pick<<<1, kSplitBlock, 0, s>>>(0, budget, h0, w.state);
+    k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h1);
+    k_select_pick<<<1, kSplitBlock, 0, s>>>(1, budget, h1, w.state);
+    k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h2, w.cand, n_cand);
+    k_select_pick<<<1, kSplitBlock, 0, s>>>(2, budget, h2, w.state, w.cand, n_cand);
+    const unsigned tiles = (unsigned)n_tiles;
+    k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, w.state, w.tile_ties);
+    k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(w.tile_ties, n_tiles, w.state, w.tile_before);
+    k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.tile_ties,
+                                                        w.tile_before, bitmap);
+}
+
+// ---------------------------------------------------------------------------
+// Scratch of osp_split_element_static: one array per GPU, held until the process
+// ends.  In host code the array's name is only a handle for hipGetSymbolAddress;
+// the address kernels are given is looked up once per device.
+// ---------------------------------------------------------------------------
+constexpr long long kStaticMaxElems = 1LL << 28;
+constexpr size_t kStaticOffHist = 256;                                   // SplitState first
+constexpr size_t kStaticOffCand = kStaticOffHist + 49408;                // (3 * 2048 + 1) * 8, rounded up
+constexpr size_t kStaticOffTies = kStaticOffCand + (size_t)kTieCandidates * sizeof(TieCandidate);
+constexpr size_t kStaticTiles = (size_t)(kStaticMaxElems / kSelTile);
+constexpr size_t kStaticOffBefore = kStaticOffTies + kStaticTiles * sizeof(unsigned int);
+constexpr size_t kStaticScratchBytes = kStaticOffBefore + kStaticTiles * sizeof(unsigned long long);
+static_assert(sizeof(SplitState) <= kStaticOffHist, "state fits in front of the histograms");
+static_assert(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long) <= kStaticOffCand - kStaticOffHist,
+              "histograms fit");
+static_assert(kStaticOffCand % 256 == 0 && kStaticOffTies % 256 == 0 && kStaticOffBefore % 256 == 0,
+              "every part starts on a 256-byte boundary");
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static unsigned char *g_scratch_ptr[kMaxDevices];      // device address of `scratch`, per device
+
+// Device address of this process's scratch array on the current device (looked up on the
+// first call per device; a race between two first calls stores the same value twice).
+static hipError_t static_scratch(unsigned char **out)
+{
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess)
+        return e;
+    if (dev < 0 || dev >= kMaxDevices)
+        return hipErrorInvalidDevice;
+    unsigned char *p = __atomic_load_n(&g_scratch_ptr[dev], __ATOMIC_ACQUIRE);
+    if (!p) {
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess)
+            return e;
+        if (!p)
+            return hipErrorInvalidSymbol;
+        __atomic_store_n(&g_scratch_ptr[dev], p, __ATOMIC_RELEASE);
+    }
+    *out = p;
+    return hipSuccess;
+}
+
 extern "C" {
 
 osp_status osp_create(const osp_config *cfg, osp_ctx **out)
@@ -1621,26 +1702,14 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         }
         ctx->have_layer_importance = true;
     } else {
-        const long long nv = ctx->n_vec;
-        long long want = (nv + kSplitBlock - 1) / kSplitBlock;
-        const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
-        k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
-                                         (long long)(3 * kRadixBins + 1) * 2, 0u);
-        k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(0));
-        k_select_pick<<<1, kSplitBlock, 0, s>>>(0, (long long)budget_elems, ctx->d_hist(0), ctx->d_state());
-        k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(1));
-        k_select_pick<<<1, kSplitBlock, 0, s>>>(1, (long long)budget_elems, ctx->d_hist(1), ctx->d_state());
-        k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_hist(2),
-                                                           ctx->d_cand(), ctx->d_n_cand());
-        k_select_pick<<<1, kSplitBlock, 0, s>>>(2, (long long)budget_elems, ctx->d_hist(2), ctx->d_state(),
-                                               ctx->d_cand(), ctx->d_n_cand());
-        const unsigned tiles = (unsigned)ctx->n_tiles;
-        k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->d_state(), ctx->d_tile_ties());
-        k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(ctx->d_tile_ties(), ctx->n_tiles, ctx->d_state(),
-                                                     ctx->d_tile_before());
-        k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(ctx->d_key(), nv, ctx->n_words, ctx->d_state(),
-                                                      ctx->d_tile_ties(), ctx->d_tile_before(),
-                                                      ctx->d_bitmap());
+        SelectScratch w;
+        w.state = ctx->d_state();
+        w.hist = ctx->d_hist(0);
+        w.cand = ctx->d_cand();
+        w.tile_ties = ctx->d_tile_ties();
+        w.tile_before = ctx->d_tile_before();
+        enqueue_element_select(ctx->d_key(), ctx->n_vec, ctx->n_words, ctx->n_tiles,
+                               (long long)budget_elems, w, ctx->d_bitmap(), s);
         ctx->counts_pending = false;    // stage tables belong to layer-granular GIBs only
         ctx->n_stage2_host = budget_elems;
     }
@@ -1655,6 +1724,38 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     ctx->gib_gran = granularity;
     ctx->agg1 = ctx->agg2 = ctx->single_pass = ctx->lgp_done = ctx->applied1 = ctx->applied2 = false;
     return OSP_OK;
+}
+
+osp_status osp_split_element_static(const uint32_t *keys, int64_t n_elems, int64_t budget_elems,
+                                    uint32_t *elem_bitmap, void *stream)
+{
+    osp_ctx *ctx = nullptr;                    // messages go to the thread's slot (osp_last_error(NULL))
+    if (!keys || !elem_bitmap)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "keys and elem_bitmap must not be NULL");
+    if (!aligned16(keys) || reinterpret_cast<uintptr_t>(elem_bitmap) % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "keys must be 16-byte and elem_bitmap 4-byte aligned");
+    if (n_elems <= 0 || n_elems % 4 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "n_elems must be a positive multiple of 4 (got %lld)",
+                    (long long)n_elems);
+    if (n_elems > kStaticMaxElems)
+        return fail(ctx, OSP_ERR_UNSUPPORTED,
+                    "n_elems %lld exceeds the %lld keys the built-in scratch is sized for",
+                    (long long)n_elems, kStaticMaxElems);
+    if (budget_elems < 0 || budget_elems > n_elems)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "budget %lld outside [0, %lld]",
+                    (long long)budget_elems, (long long)n_elems);
+    unsigned char *base = nullptr;
+    OSP_HIP(static_scratch(&base));
+    SelectScratch w;
+    w.state = reinterpret_cast<SplitState *>(base);
+    w.hist = reinterpret_cast<unsigned long long *>(base + kStaticOffHist);
+    w.cand = reinterpret_cast<TieCandidate *>(base + kStaticOffCand);
+    w.tile_ties = reinterpret_cast<unsigned int *>(base + kStaticOffTies);
+    w.tile_before = reinterpret_cast<unsigned long long *>(base + kStaticOffBefore);
+    const long long n_tiles = (n_elems + kSelTile - 1) / kSelTile;
+    enqueue_element_select(keys, n_elems / 4, (n_elems + 31) / 32, n_tiles, (long long)budget_elems,
+                           w, elem_bitmap, (hipStream_t)stream);
+    return launch_check(ctx, "element select kernels");
 }
 
 osp_status osp_stream_copy(void *dst, const void *src, size_t bytes, void *stream)

@@ -181,6 +181,14 @@ def test_newer_entry_points_validate_before_touching_anything():
         with pytest.raises(B.OspError) as e:
             call()
         assert e.value.status == want, i
+    # the allocation-free element split: every argument error is answered before any GPU call
+    for a, want in (((0, 64, 8, 16), B.OSP_ERR_INVALID_ARG), ((16, 64, 8, 0), B.OSP_ERR_INVALID_ARG),
+                    ((24, 64, 8, 16), B.OSP_ERR_INVALID_ARG), ((16, 64, 8, 18), B.OSP_ERR_INVALID_ARG),
+                    ((16, 0, 0, 16), B.OSP_ERR_INVALID_ARG), ((16, 62, 8, 16), B.OSP_ERR_INVALID_ARG),
+                    ((16, 64, 65, 16), B.OSP_ERR_INVALID_ARG), ((16, 64, -1, 16), B.OSP_ERR_INVALID_ARG),
+                    ((16, (1 << 28) + 4, 8, 16), B.OSP_ERR_UNSUPPORTED)):
+        assert L.osp_split_element_static(a[0], a[1], a[2], a[3], None) == want, a
+        assert len(L.osp_last_error(None)) > 0
     # reference kernels: argument checks only (no launch for bad shapes)
     assert L.osp_stream_pattern(0, 1, 16, 16, 1, 16, 16, None) == B.OSP_ERR_INVALID_ARG
     assert L.osp_stream_pattern(16, 0, 16, 16, 1, 16, 16, None) == B.OSP_ERR_INVALID_ARG
