@@ -22,11 +22,15 @@
  *   made with the device current that owns these buffers.  All pointers in osp_config and the
  *   gib/out arguments of osp_set_gib / osp_get_* are HOST pointers.
  *   `stream` is a hipStream_t passed as void* (NULL = the default stream).
- *   Kernels are enqueued on it and the call returns without waiting, except
- *   osp_bind, osp_set_gib and the osp_get_* calls, which synchronize it, and
- *   the first staged call after a layer-granular osp_split, which waits (on
- *   the host) for that split to finish: it needs the sizes of the two stage
- *   sets to shape its launch, and it is ordered behind the split anyway.
+ *   Kernels are enqueued on it and the call returns without waiting for the
+ *   GPU.  That holds for every call of the synchronization step (the staged
+ *   calls, the windows, osp_split): launches over a stage of a layer-granular
+ *   GIB read the size of the stage on the device, so whole iterations can be
+ *   enqueued while an earlier split has not run yet, and a step can be
+ *   captured into a HIP graph and replayed.  The calls that do wait: osp_bind,
+ *   osp_set_gib and the osp_get_* calls synchronize the stream; osp_n_stage2,
+ *   osp_split_gradients and osp_ps_aggregate_update_packed need the stage-2
+ *   size on the HOST and wait for a layer-granular split that is still running.
  *
  * Concurrency
  *   The calls of one context update shared buffers and must not overlap in
@@ -159,7 +163,7 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
  *   elem_bitmap: DEVICE, 4-byte aligned, caller-owned, overwritten.
  *   n_elems:     positive multiple of 4, at most 2^28 (OSP_ERR_UNSUPPORTED above).
  * The histograms, counters, tie candidates and per-tile counts live in an array
- * of 1.5 MB that is part of the library's image on every GPU it runs on (held
+ * of 1.2 MB that is part of the library's image on every GPU it runs on (held
  * until the process ends); the call clears what must start at zero with a fill
  * kernel, launches the kernels osp_split launches, and calls no allocating
  * routine.  Every call on one GPU uses that GPU's one array: calls that overlap
@@ -185,10 +189,22 @@ osp_status osp_get_gib(osp_ctx *ctx, uint8_t *layer_gib, uint32_t *elem_bitmap,
  * without stalling the stream. */
 osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream);
 
+/* A log of stage-2 sizes without any stream operation per iteration: from now on
+ * every osp_split (the one inside osp_ics_window too) also stores the size of the
+ * stage 2 it has just chosen at log[k % capacity], k = 0, 1, ... counting the
+ * splits since this call.  log: memory the DEVICE can write, 8-byte aligned
+ * (device memory, or the device address of mapped pinned host memory),
+ * caller-owned, valid until the log is taken away (log = NULL), the context is
+ * rebound or destroyed.  Enqueues one small kernel on `stream`; entries are
+ * valid once the stream has passed the split that writes them.  Replays of a
+ * captured split keep counting. */
+osp_status osp_set_stage2_log(osp_ctx *ctx, int64_t *log, int64_t capacity, void *stream);
+
 /* The current stage-2 element count, on the host, without a stream operation:
- * the split publishes it in pinned host memory.  Waits (bounded) only if a
- * layer-granular osp_split is still running; any staged call made after that
- * split has already waited, so calling this behind one costs nothing. */
+ * the split publishes it in pinned host memory.  Waits if a layer-granular
+ * osp_split is still running (or has not started: do not call it between the
+ * capture of a graph that holds a split and the graph's first replay).  Callers
+ * that must not wait use osp_read_n_stage2_async. */
 osp_status osp_n_stage2(osp_ctx *ctx, int64_t *n_stage2);
 
 /* Install a GIB from the host (first iteration, tests, resume).  gib_host is

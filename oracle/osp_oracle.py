@@ -262,7 +262,36 @@ class OracleOSP:
         self.n_stage2 = int(n2)
         return self.n_stage2
 
-    def sync_step(self, grads: np.ndarray, granularity: int, budget_elems: int) -> int:
+    def split_element_by_selection(self, budget_elems: int) -> int:
+        """The partition split(GRAN_ELEMENT, budget) defines (the first `budget` parameters in
+        the order: key ascending, arena index ascending), found by selection on this oracle's
+        keys instead of the full sort, for the sizes where the sort takes minutes: T = the
+        budget-th smallest key; every key below T is in stage 2; of the keys equal to T the
+        first budget - (number below) in index order are.  Pinned to split() by
+        tests/test_oracle_pins.py; split() stays the definition."""
+        n_real = int(np.sum(self.numel))
+        if budget_elems < 0 or budget_elems > n_real:
+            raise ValueError("budget outside [0, number of parameters]")
+        keys = self.keys()
+        real = np.zeros(self.arena, bool)
+        for a, n in zip(self.offset, self.numel):
+            real[int(a):int(a) + int(n)] = True
+        s2 = np.zeros(self.words * 32, bool)
+        if budget_elems > 0:
+            T = np.partition(keys[real], budget_elems - 1)[budget_elems - 1]
+            below = real & (keys < T)
+            r = budget_elems - int(below.sum())
+            ties = np.nonzero(real & (keys == T))[0]
+            assert 1 <= r <= ties.size
+            s2[:self.arena] = below
+            s2[ties[:r]] = True
+        self.granularity = GRAN_ELEMENT
+        self.gib_bits[:] = np.packbits(~s2, bitorder="little").view(np.uint32)
+        self.n_stage2 = int(budget_elems)
+        return self.n_stage2
+
+    def sync_step(self, grads: np.ndarray, granularity: int, budget_elems: int,
+                  element_by_selection: bool = False) -> int:
         """One full step in the paper's order (Sec. 3.1, Eq. 5 ordering):
         RS window = aggregate stage 1, hand back, LGP; ICS window = aggregate
         stage 2, correct the local estimate, compute the next GIB."""
@@ -271,4 +300,6 @@ class OracleOSP:
         self.lgp_correct(grads)
         self.ps_aggregate_update(2, grads)
         self.apply_stage(2)
+        if granularity == GRAN_ELEMENT and element_by_selection:
+            return self.split_element_by_selection(budget_elems)
         return self.split(granularity, budget_elems)

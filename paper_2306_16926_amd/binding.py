@@ -14,7 +14,8 @@ from typing import Optional, Sequence
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libosp.so")
+# OSP_LIB: load this build of the library instead of the in-tree one
+LIB_PATH = os.environ.get("OSP_LIB") or os.path.join(_HERE, "libosp.so")
 
 OSP_OK, OSP_ERR_INVALID_ARG, OSP_ERR_BAD_STATE, OSP_ERR_NOMEM, OSP_ERR_HIP, OSP_ERR_UNSUPPORTED = range(6)
 OSP_GRAN_LAYER, OSP_GRAN_ELEMENT = 0, 1
@@ -79,6 +80,8 @@ def _load() -> C.CDLL:
     lib.osp_get_gib.restype = C.c_int
     lib.osp_read_n_stage2_async.argtypes = [vp, vp, vp]
     lib.osp_read_n_stage2_async.restype = C.c_int
+    lib.osp_set_stage2_log.argtypes = [vp, vp, i64, vp]
+    lib.osp_set_stage2_log.restype = C.c_int
     lib.osp_n_stage2.argtypes = [vp, C.POINTER(i64)]
     lib.osp_n_stage2.restype = C.c_int
     lib.osp_set_gib.argtypes = [vp, C.c_int, vp, vp]
@@ -143,7 +146,7 @@ def _load() -> C.CDLL:
 lib = _load()
 
 EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_set_hyper",
-           "osp_split", "osp_split_element_static", "osp_get_gib", "osp_read_n_stage2_async", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
+           "osp_split", "osp_split_element_static", "osp_get_gib", "osp_read_n_stage2_async", "osp_set_stage2_log", "osp_n_stage2", "osp_set_gib", "osp_ps_aggregate_update",
            "osp_lgp_correct", "osp_apply_stage", "osp_rs_window", "osp_ics_window", "osp_sync_step",
            "osp_split_gradients", "osp_ps_aggregate_update_packed",
            "osp_split_gradients_bf16", "osp_ps_aggregate_update_packed_bf16",
@@ -279,6 +282,14 @@ class Context:
     def osp_read_n_stage2_async(self, out_host, stream=None) -> None:
         """out_host: address (or pinned int64 tensor / array element) the count is copied to."""
         self._check(lib.osp_read_n_stage2_async(self._h, _ptr(out_host), _stream(stream)))
+
+    def osp_set_stage2_log(self, log, capacity: Optional[int] = None, stream=None) -> None:
+        """log: int64 device tensor (or device address) every later split appends its stage-2
+        size to, round robin; None takes the log away."""
+        if capacity is None:
+            capacity = 0 if log is None else log.numel()
+        self._check(lib.osp_set_stage2_log(self._h, _ptr(log), int(capacity), _stream(stream)))
+        self._log = log                         # borrowed buffer stays alive
 
     def osp_ps_aggregate_update(self, stage: int, grads, worker_stride: int, stream=None) -> None:
         self._check(lib.osp_ps_aggregate_update(self._h, stage, _ptr(grads), int(worker_stride),

@@ -15,6 +15,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 using namespace osp;
@@ -57,7 +58,7 @@ struct osp_ctx {
     // ---- workspace layout (byte offsets) ----
     size_t off_spans = 0, off_slayer = 0, off_lsp = 0, off_numel = 0, off_lists = 0, off_partial = 0, off_imp = 0,
            off_order = 0, off_lbase = 0, off_rscratch = 0, off_segs = 0, off_lsb = 0, off_big = 0, off_segsum = 0, off_gib = 0, off_state = 0, off_weights = 0, off_key = 0, off_stash = 0, off_pack = 0,
-           off_bitmap = 0, off_hist = 0, off_cand = 0, off_tile_ties = 0, off_tile_before = 0, ws_bytes = 0;
+           off_bitmap = 0, off_hist = 0, off_cand = 0, off_tile_ties = 0, ws_bytes = 0;
 
     // ---- bound buffers ----
     bool bound = false;
@@ -86,17 +87,18 @@ struct osp_ctx {
     bool stash_bf16 = false;
 
     // ---- stage-table lengths (layer-granular GIB) ----
-    // The split runs on the device; the ranking kernel publishes the two table
-    // lengths and a sequence number in pinned host memory.  counts_pending: a split
-    // with sequence number split_seq has been enqueued and its lengths have not been
-    // read yet.  counts_stream is the stream that split was enqueued on (fallback wait).
+    // The split runs on the device and leaves the lengths of the two stage tables in device
+    // memory, where the kernels that walk the tables read them: no call waits for a split.
+    // The ranking kernel also publishes the lengths, the stage-2 size and a sequence number in
+    // pinned host memory; the host uses them to size grids (a hint: any grid is correct) and
+    // to answer osp_n_stage2.  counts_pending: a split with sequence number split_seq has been
+    // enqueued and its lengths have not been seen yet; stage_spans are the last ones seen.
     int stage_spans[2] = {0, 0};
     int tables = 0;                     // which of the two sets of stage tables is current
     bool counts_pending = false;
     unsigned split_seq = 0;
     StageCounts *pinned_counts = nullptr;      // hipHostMalloc (mapped)
     StageCounts *pinned_counts_dev = nullptr;  // the same memory as the device sees it
-    hipStream_t counts_stream = nullptr;
     long long n_stage2_host = 0;        // stage-2 elements under the current GIB (see counts_pending)
 
     std::string err;
@@ -138,7 +140,6 @@ struct osp_ctx {
     unsigned int *d_n_cand() const { return reinterpret_cast<unsigned int *>(d_hist(3)); }
     TieCandidate *d_cand() const { return at<TieCandidate>(off_cand); }
     unsigned int *d_tile_ties() const { return at<unsigned int>(off_tile_ties); }
-    unsigned long long *d_tile_before() const { return at<unsigned long long>(off_tile_before); }
 };
 
 namespace {
@@ -202,11 +203,10 @@ void layout_workspace(osp_ctx *c)
     if (c->element_keys) {
         c->off_key = take((size_t)c->arena * sizeof(uint32_t));
         c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
-        // three histograms, then the length of the tie-candidate list (cleared with them)
+        // three histograms, then the length of the tie-candidate list (zero between splits)
         c->off_hist = take(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long));
         c->off_cand = take((size_t)kTieCandidates * sizeof(TieCandidate));
         c->off_tile_ties = take((size_t)c->n_tiles * sizeof(unsigned int));
-        c->off_tile_before = take((size_t)c->n_tiles * sizeof(unsigned long long));
     }
     c->ws_bytes = o;
 }
@@ -226,54 +226,105 @@ osp_status check_grads(osp_ctx *ctx, const void *grads, int64_t stride, bool bf1
 
 bool stage2_pending(const osp_ctx *c) { return c->agg1 && !c->agg2; }
 
-// Enqueue the fill of both stage lists (bases must already be on the device)
-// and the copy of their lengths to the pinned buffer.
+// Enqueue the fill of both stage lists (bases must already be on the device).
 osp_status enqueue_stage_lists(osp_ctx *ctx, hipStream_t s)
 {
     const int ns = (int)ctx->spans.size();
     k_stage_lists<<<(ns + kSplitBlock - 1) / kSplitBlock, kSplitBlock, 0, s>>>(
         ns, ctx->d_spans(), ctx->d_slayer(), ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
-        ctx->d_list(1), ctx->d_list(2));
+        ctx->d_state(), ctx->tables, ctx->d_list(1), ctx->d_list(2));
     // (the table lengths were written straight into pinned host memory by the kernel before)
-    ctx->counts_stream = s;
     ctx->counts_pending = true;
     return OSP_OK;
 }
 
-// Lengths of the stage lists, waiting for the split that produced them if it
-// is still running (the kernel that needs them is ordered behind it anyway).
+// Take over the lengths the last split published, if it has published them.  Never waits.
+bool refresh_counts(osp_ctx *ctx)
+{
+    if (!ctx->counts_pending)
+        return true;
+    if (__atomic_load_n(&ctx->pinned_counts->seq, __ATOMIC_ACQUIRE) != ctx->split_seq)
+        return false;
+    const int n1 = ctx->pinned_counts->n[0], n2 = ctx->pinned_counts->n[1];
+    if (n1 < 0 || n2 < 0 || (long long)n1 + n2 != (long long)ctx->spans.size())
+        return false;                   // (stage_counts reports this)
+    ctx->stage_spans[0] = n1;
+    ctx->stage_spans[1] = n2;
+    ctx->n_stage2_host = ctx->pinned_counts->n_stage2;
+    ctx->counts_pending = false;
+    return true;
+}
+
+// The same for the calls that need the sizes on the HOST (osp_n_stage2, the gradient
+// splitter's and the packed aggregate's stride checks): waits for the split that produces
+// them, first polling the sequence number (the lengths are published by the ranking kernel,
+// before the table-filling work behind it), yielding the core between polls; after 2 s it
+// waits for the device instead, which also surfaces a device error instead of spinning on it.
 osp_status stage_counts(osp_ctx *ctx)
 {
-    if (ctx->counts_pending) {
-        // Poll the sequence number instead of waiting for the whole split to retire: the
-        // lengths are published by the ranking kernel, so the next launch can be enqueued
-        // while the table-filling kernel behind it still runs.  Bounded: after 2 s fall back
-        // to synchronizing the split's stream (which also surfaces a device error instead of
-        // spinning on it).
-        const volatile unsigned *seq = &ctx->pinned_counts->seq;
-        const auto t0 = std::chrono::steady_clock::now();
-        unsigned spins = 0;
-        while (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq) {
-            if ((++spins & 1023u) == 0 &&
-                std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
-                OSP_HIP(hipStreamSynchronize(ctx->counts_stream));
-                if (__atomic_load_n(seq, __ATOMIC_ACQUIRE) != ctx->split_seq)
-                    return fail(ctx, OSP_ERR_HIP, "the split did not publish its stage-table lengths");
-                break;
-            }
+    if (!ctx->counts_pending)
+        return OSP_OK;
+    const auto t0 = std::chrono::steady_clock::now();
+    unsigned spins = 0;
+    while (__atomic_load_n(&ctx->pinned_counts->seq, __ATOMIC_ACQUIRE) != ctx->split_seq) {
+        if (++spins < 4096u) {
             __builtin_ia32_pause();
+            continue;
         }
-        ctx->stage_spans[0] = ctx->pinned_counts->n[0];
-        ctx->stage_spans[1] = ctx->pinned_counts->n[1];
-        ctx->n_stage2_host = ctx->pinned_counts->n_stage2;
-        ctx->counts_pending = false;
-        const long long ns = (long long)ctx->spans.size();
-        if (ctx->stage_spans[0] < 0 || ctx->stage_spans[1] < 0 ||
-            (long long)ctx->stage_spans[0] + ctx->stage_spans[1] != ns)
-            return fail(ctx, OSP_ERR_HIP, "stage tables are inconsistent (%d + %d != %lld spans)",
-                        ctx->stage_spans[0], ctx->stage_spans[1], ns);
+        std::this_thread::yield();
+        if ((spins & 255u) == 0 && std::chrono::steady_clock::now() - t0 > std::chrono::seconds(2)) {
+            OSP_HIP(hipDeviceSynchronize());
+            if (__atomic_load_n(&ctx->pinned_counts->seq, __ATOMIC_ACQUIRE) != ctx->split_seq)
+                return fail(ctx, OSP_ERR_HIP, "the split did not publish its stage-table lengths");
+            break;
+        }
     }
+    if (!refresh_counts(ctx))
+        return fail(ctx, OSP_ERR_HIP, "stage tables are inconsistent (%d + %d != %lld spans)",
+                    ctx->pinned_counts->n[0], ctx->pinned_counts->n[1], (long long)ctx->spans.size());
     return OSP_OK;
+}
+
+bool stream_is_capturing(hipStream_t s)
+{
+    if (!s)
+        return false;                   // the default stream cannot be captured
+    hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(s, &st) != hipSuccess) {
+        (void)hipGetLastError();
+        return false;
+    }
+    return st != hipStreamCaptureStatusNone;
+}
+
+// How to launch over the table of one stage of the current layer-granular GIB.  The kernels
+// find the table's end on the device (its first cleared entry) and cope with any grid;
+// grid_spans is what the grid is sized for: the exact length when the host has seen it (0: the
+// stage is empty, nothing to launch), otherwise the last published length, and never less than
+// an eighth of all spans, so that a stage that has grown since is still walked by many
+// workgroups (a surplus workgroup costs a few per cent of a working one).  A launch that is
+// being captured into a graph is sized the same way: replays may meet other lengths.
+struct StageLaunch {
+    const Span *table;
+    unsigned grid_spans;
+};
+
+StageLaunch stage_launch(osp_ctx *ctx, int stage, hipStream_t s)
+{
+    StageLaunch L;
+    L.table = ctx->d_list(stage);
+    const unsigned total = (unsigned)ctx->spans.size();
+    const bool exact = refresh_counts(ctx) && !stream_is_capturing(s);
+    if (exact) {
+        L.grid_spans = (unsigned)ctx->stage_spans[stage - 1];
+    } else {
+        int hint = ctx->counts_pending ? ctx->pinned_counts->n[stage - 1] : ctx->stage_spans[stage - 1];
+        if (hint < 0)
+            hint = 0;
+        unsigned g = (unsigned)hint > (total + 7) / 8 ? (unsigned)hint : (total + 7) / 8;
+        L.grid_spans = g > total ? total : g;
+    }
+    return L;
 }
 
 osp_status launch_check(osp_ctx *ctx, const char *what)
@@ -287,15 +338,16 @@ osp_status launch_check(osp_ctx *ctx, const char *what)
 } // namespace
 
 template <typename GT>
-static void launch_aggregate(int variant, dim3 grid, dim3 block, hipStream_t s, const AggArgs &a)
+static void launch_aggregate(int variant, dim3 grid, dim3 block, hipStream_t s, const Span *table,
+                             const AggArgs &a)
 {
     switch (variant) {
-    case 0: k_aggregate_update<false, false, false, GT><<<grid, block, 0, s>>>(a); break;
-    case 1: k_aggregate_update<false, false, true, GT><<<grid, block, 0, s>>>(a); break;
-    case 2: k_aggregate_update<false, true, false, GT><<<grid, block, 0, s>>>(a); break;
-    case 3: k_aggregate_update<false, true, true, GT><<<grid, block, 0, s>>>(a); break;
-    case 5: k_aggregate_update<true, false, true, GT><<<grid, block, 0, s>>>(a); break;
-    default: k_aggregate_update<true, true, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 0: k_aggregate_update<false, false, false, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 1: k_aggregate_update<false, false, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 2: k_aggregate_update<false, true, false, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 3: k_aggregate_update<false, true, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 5: k_aggregate_update<true, false, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    default: k_aggregate_update<true, true, true, GT><<<grid, block, 0, s>>>(table, a); break;
     }
 }
 
@@ -376,28 +428,29 @@ static void launch_aggregate_packed(int variant, dim3 grid, dim3 block, hipStrea
 }
 
 template <typename GT>
-static void launch_lgp_keep(const osp_ctx *ctx, const LgpKeepArgs &a, unsigned n_groups, hipStream_t s)
+static void launch_lgp_keep(const osp_ctx *ctx, const Span *table, const LgpKeepArgs &a,
+                            unsigned n_groups, hipStream_t s)
 {
     const dim3 grid(n_groups), block(kBlock);
     const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
     switch (variant) {
-    case 0: k_lgp_keep<false, false, GT><<<grid, block, 0, s>>>(a); break;
-    case 1: k_lgp_keep<false, true, GT><<<grid, block, 0, s>>>(a); break;
-    case 2: k_lgp_keep<true, false, GT><<<grid, block, 0, s>>>(a); break;
-    default: k_lgp_keep<true, true, GT><<<grid, block, 0, s>>>(a); break;
+    case 0: k_lgp_keep<false, false, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 1: k_lgp_keep<false, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 2: k_lgp_keep<true, false, GT><<<grid, block, 0, s>>>(table, a); break;
+    default: k_lgp_keep<true, true, GT><<<grid, block, 0, s>>>(table, a); break;
     }
 }
 
 // The launches of one element-granular selection: `budget` smallest keys in the order
-// (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch; hist is
-// (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the length of the
-// candidate list), cleared here by a fill kernel.
+// (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch: the split state
+// (tickets zero), hist = (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the
+// length of the candidate list; all zero on entry and left zero), the candidate list, the
+// per-tile tie counts.
 struct SelectScratch {
     SplitState *state;
     unsigned long long *hist;
     TieCandidate *cand;
     unsigned int *tile_ties;
-    unsigned long long *tile_before;
 };
 
 static void enqueue_element_select(const uint32_t *key, long long n_vec, long long n_words,
@@ -408,19 +461,14 @@ static void enqueue_element_select(const uint32_t *key, long long n_vec, long lo
     unsigned int *n_cand = reinterpret_cast<unsigned int *>(w.hist + 3 * kRadixBins);
     long long want = (n_vec + kSplitBlock - 1) / kSplitBlock;
     const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
-    k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(w.hist),
-                                          (long long)(3 * kRadixBins + 1) * 2, 0u);
-    k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h0);
-    k_select_pick<<<1, kSplitBlock, 0, s>>>(0, budget, h0, w.state);
-    k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h1);
-    k_select_pick<<<1, kSplitBlock, 0, s>>>(1, budget, h1, w.state);
-    k_select_histogram<2><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, w.state, h2, w.cand, n_cand);
-    k_select_pick<<<1, kSplitBlock, 0, s>>>(2, budget, h2, w.state, w.cand, n_cand);
     const unsigned tiles = (unsigned)n_tiles;
+    k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h0);
+    k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h1);
+    k_select_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.cand, n_cand, bitmap);
+    k_select_finish<<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h2, w.cand, n_cand, bitmap);
+    // (the last two return at once unless many keys share the threshold's upper 22 bits)
     k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, w.state, w.tile_ties);
-    k_select_scan_tiles<<<1, kSplitBlock, 0, s>>>(w.tile_ties, n_tiles, w.state, w.tile_before);
-    k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.tile_ties,
-                                                        w.tile_before, bitmap);
+    k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.tile_ties, bitmap);
 }
 
 // ---------------------------------------------------------------------------
@@ -433,12 +481,11 @@ constexpr size_t kStaticOffHist = 256;                                   // Spli
 constexpr size_t kStaticOffCand = kStaticOffHist + 49408;                // (3 * 2048 + 1) * 8, rounded up
 constexpr size_t kStaticOffTies = kStaticOffCand + (size_t)kTieCandidates * sizeof(TieCandidate);
 constexpr size_t kStaticTiles = (size_t)(kStaticMaxElems / kSelTile);
-constexpr size_t kStaticOffBefore = kStaticOffTies + kStaticTiles * sizeof(unsigned int);
-constexpr size_t kStaticScratchBytes = kStaticOffBefore + kStaticTiles * sizeof(unsigned long long);
+constexpr size_t kStaticScratchBytes = kStaticOffTies + kStaticTiles * sizeof(unsigned int);
 static_assert(sizeof(SplitState) <= kStaticOffHist, "state fits in front of the histograms");
 static_assert(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long) <= kStaticOffCand - kStaticOffHist,
               "histograms fit");
-static_assert(kStaticOffCand % 256 == 0 && kStaticOffTies % 256 == 0 && kStaticOffBefore % 256 == 0,
+static_assert(kStaticOffCand % 256 == 0 && kStaticOffTies % 256 == 0,
               "every part starts on a 256-byte boundary");
 
 static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
@@ -680,6 +727,9 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         // padding keys stay 0xFFFFFFFF for good: above every real key, never selected
         k_fill_u32<<<1024, kSplitBlock, 0, s>>>(ctx->d_key(), ctx->arena, 0xFFFFFFFFu);
         k_fill_u32<<<256, kSplitBlock, 0, s>>>(ctx->d_bitmap(), ctx->n_words, 0xFFFFFFFFu);
+        // histograms and the candidate count start at zero; every split leaves them so
+        k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
+                                             (long long)(3 * kRadixBins + 1) * 2, 0u);
     }
     osp_status st = launch_check(ctx, "bind fill kernels");
     if (st != OSP_OK)
@@ -730,7 +780,8 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         OSP_HIP(hipMemcpyAsync(&ctx->d_state()->n_stage2, &n2, sizeof n2, hipMemcpyHostToDevice, s));
         ctx->tables ^= 1;               // the new GIB's tables go into the other set
         k_stage_bases<<<1, 64, 0, s>>>(ctx->n_tensors, ctx->d_gib(), ctx->d_lsp(), ctx->d_lbase(),
-                                       ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
+                                       ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq,
+                                       ctx->tables);
         osp_status st = enqueue_stage_lists(ctx, s);
         if (st != OSP_OK)
             return st;
@@ -738,6 +789,9 @@ osp_status osp_set_gib(osp_ctx *ctx, int granularity, const void *gib_host, void
         if (st != OSP_OK)
             return st;
         OSP_HIP(hipStreamSynchronize(s));
+        st = stage_counts(ctx);         // (published by now)
+        if (st != OSP_OK)
+            return st;
     } else {
         const uint32_t *g = (const uint32_t *)gib_host;
         std::vector<uint32_t> bits;
@@ -795,9 +849,34 @@ osp_status osp_read_n_stage2_async(osp_ctx *ctx, int64_t *out_host, void *stream
         return fail(ctx, OSP_ERR_INVALID_ARG, "out_host is NULL");
     if (!ctx->bound || !ctx->have_gib)
         return fail(ctx, OSP_ERR_BAD_STATE, "no GIB yet (osp_set_gib or osp_split first)");
+    // Pinned (mapped) host memory is written by a one-lane kernel: a few microseconds of stream
+    // time and a node that can be captured into a graph, where a copy of 8 bytes through the
+    // copy path costs several times that.  Any other host memory takes the copy.
+    void *dev = nullptr;
+    if (hipHostGetDevicePointer(&dev, out_host, 0) == hipSuccess && dev) {
+        k_publish_i64<<<1, 1, 0, (hipStream_t)stream>>>(&ctx->d_state()->n_stage2,
+                                                        static_cast<long long *>(dev));
+        return launch_check(ctx, "k_publish_i64");
+    }
+    (void)hipGetLastError();
     OSP_HIP(hipMemcpyAsync(out_host, &ctx->d_state()->n_stage2, sizeof(int64_t),
                            hipMemcpyDeviceToHost, (hipStream_t)stream));
     return OSP_OK;
+}
+
+osp_status osp_set_stage2_log(osp_ctx *ctx, int64_t *log, int64_t capacity, void *stream)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    if (log && capacity < 1)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "capacity must be >= 1 (got %lld)", (long long)capacity);
+    if (reinterpret_cast<uintptr_t>(log) % 8 != 0)
+        return fail(ctx, OSP_ERR_INVALID_ARG, "log must be 8-byte aligned");
+    if (!ctx->bound)
+        return fail(ctx, OSP_ERR_BAD_STATE, "osp_bind first");
+    k_set_stage2_log<<<1, 1, 0, (hipStream_t)stream>>>(ctx->d_state(), reinterpret_cast<long long *>(log),
+                                                      log ? (long long)capacity : 1);
+    return launch_check(ctx, "k_set_stage2_log");
 }
 
 osp_status osp_n_stage2(osp_ctx *ctx, int64_t *n_stage2)
@@ -837,15 +916,16 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
 
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
+    hipStream_t s = (hipStream_t)stream;
     unsigned n_groups = (unsigned)ctx->spans.size() * kSpanChunks;
-    if (listed) {
-        st = stage_counts(ctx);
-        if (st != OSP_OK)
-            return st;
-        n_groups = (unsigned)ctx->stage_spans[stage - 1] * kSpanChunks;
-    }
     AggArgs a;
-    a.spans = listed ? ctx->d_list(stage) : ctx->d_spans();
+    const Span *table = ctx->d_spans();
+    a.cap_spans = (unsigned)ctx->spans.size();
+    if (listed) {
+        const StageLaunch L = stage_launch(ctx, stage, s);
+        table = L.table;
+        n_groups = L.grid_spans * kSpanChunks;
+    }
     a.chunk_elems = ctx->chunk_elems;
     a.bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     a.P = ctx->P;
@@ -870,11 +950,10 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
     a.lr = ctx->lr;
     a.mu = ctx->mu;
     const dim3 grid(n_groups), block(kBlock);
-    hipStream_t s = (hipStream_t)stream;
     const int variant = (masked ? 4 : 0) | (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
     if (from_stash) {
         StashArgs sa;
-        sa.spans = a.spans;
+        sa.cap_spans = a.cap_spans;
         sa.chunk_elems = a.chunk_elems;
         sa.bitmap = a.bitmap;
         sa.P = ctx->P;
@@ -883,16 +962,16 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
         sa.lr = ctx->lr;
         sa.mu = ctx->mu;
         if (masked)
-            k_update_from_stash<true><<<grid, block, 0, s>>>(sa);
+            k_update_from_stash<true><<<grid, block, 0, s>>>(table, sa);
         else if (n_groups > 0)
-            k_update_from_stash<false><<<grid, block, 0, s>>>(sa);
+            k_update_from_stash<false><<<grid, block, 0, s>>>(table, sa);
     } else if (n_groups > 0) {        // an empty stage launches nothing
         if (variant == 4 || variant == 6)
             return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
         if (bf16)
-            launch_aggregate<bf16_t>(variant, grid, block, s, a);
+            launch_aggregate<bf16_t>(variant, grid, block, s, table, a);
         else
-            launch_aggregate<float>(variant, grid, block, s, a);
+            launch_aggregate<float>(variant, grid, block, s, table, a);
     }
     st = launch_check(ctx, "k_aggregate_update");
     if (st != OSP_OK)
@@ -948,16 +1027,16 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
     if (ctx->applied2)
         return fail(ctx, OSP_ERR_BAD_STATE, "LGP after the stage-2 correction would undo it");
     const bool masked = ctx->gib_gran == OSP_GRAN_ELEMENT;
-    unsigned n_spans = (unsigned)ctx->spans.size();
-    if (!masked) {
-        st = stage_counts(ctx);
-        if (st != OSP_OK)
-            return st;
-        n_spans = (unsigned)ctx->stage_spans[1];
-    }
-    const Span *table = masked ? ctx->d_spans() : ctx->d_list(2);
-    const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     hipStream_t s = (hipStream_t)stream;
+    unsigned n_spans = (unsigned)ctx->spans.size();
+    const Span *table = ctx->d_spans();
+    const unsigned cap_spans = (unsigned)ctx->spans.size();
+    if (!masked) {
+        const StageLaunch L = stage_launch(ctx, 2, s);
+        table = L.table;
+        n_spans = L.grid_spans;
+    }
+    const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     // The replicas' stage-2 values are still the PS's (stale) ones: read them once from the PS.
     // Needs the PS's stage-2 values untouched (stage 2 not aggregated yet) and, for an
     // element-granular GIB, this iteration's stage 1 already installed.
@@ -970,7 +1049,7 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
     ctx->last_lgp_kept = keep;
     if (keep) {
         LgpKeepArgs a;
-        a.spans = table;
+        a.cap_spans = cap_spans;
         a.chunk_elems = ctx->chunk_elems;
         a.P = ctx->P;
         a.Pw = ctx->Pw;
@@ -987,9 +1066,9 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
         const unsigned n_groups = n_spans * kSpanChunks;
         if (n_groups > 0) {
             if (bf16)
-                launch_lgp_keep<bf16_t>(ctx, a, n_groups, s);
+                launch_lgp_keep<bf16_t>(ctx, table, a, n_groups, s);
             else
-                launch_lgp_keep<float>(ctx, a, n_groups, s);
+                launch_lgp_keep<float>(ctx, table, a, n_groups, s);
         }
         ctx->stash_valid = true;
         ctx->stash_grads = grads;
@@ -997,14 +1076,13 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
         ctx->stash_bf16 = bf16;
     } else if (shared_read) {
         LgpSweepArgs a;
-        a.spans = table;
+        a.cap_spans = cap_spans;
         a.bitmap = bitmap;
         a.P = ctx->P;
         a.Pw = ctx->Pw;
         a.param_stride = ctx->param_stride;
         a.grads = grads;
         a.worker_stride = worker_stride;
-        a.n_spans = n_spans;
         const SweepShape sh = sweep_shape(ctx, n_spans);
         a.pieces_per_span = sh.pieces_per_span;
         a.pieces_shift = sh.pieces_shift;
@@ -1018,19 +1096,19 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
         if (sh.n_blocks > 0) {
             if (bf16) {
                 if (masked)
-                    k_lgp_sweep<true, bf16_t, kSweepVec><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<true, bf16_t, kSweepVec><<<grid, block, 0, s>>>(table, a);
                 else
-                    k_lgp_sweep<false, bf16_t, kSweepVec><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<false, bf16_t, kSweepVec><<<grid, block, 0, s>>>(table, a);
             } else {
                 if (masked)
-                    k_lgp_sweep<true, float, kSweepVec><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<true, float, kSweepVec><<<grid, block, 0, s>>>(table, a);
                 else
-                    k_lgp_sweep<false, float, kSweepVec><<<grid, block, 0, s>>>(a);
+                    k_lgp_sweep<false, float, kSweepVec><<<grid, block, 0, s>>>(table, a);
             }
         }
     } else {
         LgpArgs a;
-        a.spans = table;
+        a.cap_spans = cap_spans;
         a.chunk_elems = ctx->chunk_elems;
         a.bitmap = bitmap;
         a.Pw = ctx->Pw;
@@ -1050,14 +1128,14 @@ static osp_status lgp_correct(osp_ctx *ctx, const void *grads, int64_t worker_st
                 const dim3 grid(n_groups, (unsigned)nw), block(kBlock);
                 if (bf16) {
                     if (masked)
-                        k_lgp_correct<true, bf16_t><<<grid, block, 0, s>>>(b);
+                        k_lgp_correct<true, bf16_t><<<grid, block, 0, s>>>(table, b);
                     else
-                        k_lgp_correct<false, bf16_t><<<grid, block, 0, s>>>(b);
+                        k_lgp_correct<false, bf16_t><<<grid, block, 0, s>>>(table, b);
                 } else {
                     if (masked)
-                        k_lgp_correct<true><<<grid, block, 0, s>>>(b);
+                        k_lgp_correct<true><<<grid, block, 0, s>>>(table, b);
                     else
-                        k_lgp_correct<false><<<grid, block, 0, s>>>(b);
+                        k_lgp_correct<false><<<grid, block, 0, s>>>(table, b);
                 }
             }
         }
@@ -1088,12 +1166,11 @@ static osp_status launch_install(osp_ctx *ctx, const Span *table, unsigned n_spa
     const uint32_t *bitmap = ctx->element_keys ? ctx->d_bitmap() : nullptr;
     if (ctx->n_workers > kFanoutMaxWorkers) {
         ApplyArgs a;
-        a.spans = table;
+        a.cap_spans = (unsigned)ctx->spans.size();
         a.bitmap = bitmap;
         a.P = ctx->P;
         a.Pw = ctx->Pw;
         a.param_stride = ctx->param_stride;
-        a.n_spans = n_spans;
         const SweepShape sh = sweep_shape(ctx, n_spans);
         a.pieces_per_span = sh.pieces_per_span;
         a.pieces_shift = sh.pieces_shift;
@@ -1107,13 +1184,13 @@ static osp_status launch_install(osp_ctx *ctx, const Span *table, unsigned n_spa
         const dim3 block(kApplyBlock);
         if (sh.n_blocks > 0) {
             if (masked)
-                k_apply_stage_sweep<true, kSweepVec><<<grid, block, 0, s>>>(a);
+                k_apply_stage_sweep<true, kSweepVec><<<grid, block, 0, s>>>(table, a);
             else
-                k_apply_stage_sweep<false, kSweepVec><<<grid, block, 0, s>>>(a);
+                k_apply_stage_sweep<false, kSweepVec><<<grid, block, 0, s>>>(table, a);
         }
     } else {
         FanoutArgs a;
-        a.spans = table;
+        a.cap_spans = (unsigned)ctx->spans.size();
         a.chunk_elems = ctx->chunk_elems;
         a.bitmap = bitmap;
         a.P = ctx->P;
@@ -1124,9 +1201,9 @@ static osp_status launch_install(osp_ctx *ctx, const Span *table, unsigned n_spa
         const dim3 grid(n_spans * kSpanChunks), block(kBlock);
         if (n_spans > 0) {
             if (masked)
-                k_apply_stage_fanout<true><<<grid, block, 0, s>>>(a);
+                k_apply_stage_fanout<true><<<grid, block, 0, s>>>(table, a);
             else
-                k_apply_stage_fanout<false><<<grid, block, 0, s>>>(a);
+                k_apply_stage_fanout<false><<<grid, block, 0, s>>>(table, a);
         }
     }
     return launch_check(ctx, "k_apply_stage");
@@ -1160,13 +1237,12 @@ osp_status osp_apply_stage(osp_ctx *ctx, int stage, void *stream)
     const bool masked = stage != 0 && ctx->gib_gran == OSP_GRAN_ELEMENT && !overwrite_all;
     const bool listed = stage != 0 && ctx->gib_gran == OSP_GRAN_LAYER;
     unsigned n_spans = (unsigned)ctx->spans.size();
+    const Span *table = ctx->d_spans();
     if (listed) {
-        osp_status sc = stage_counts(ctx);
-        if (sc != OSP_OK)
-            return sc;
-        n_spans = (unsigned)ctx->stage_spans[stage - 1];
+        const StageLaunch L = stage_launch(ctx, stage, (hipStream_t)stream);
+        table = L.table;
+        n_spans = L.grid_spans;
     }
-    const Span *table = listed ? ctx->d_list(stage) : ctx->d_spans();
     osp_status st = launch_install(ctx, table, n_spans, stage, masked, (hipStream_t)stream);
     if (st != OSP_OK)
         return st;
@@ -1252,8 +1328,7 @@ static osp_status rs_window(osp_ctx *ctx, const void *grads, int64_t worker_stri
         // both tables (all spans), and the kernel reads where the first one ends.
         WindowLayerArgs a;
         a.agg_spans = ctx->d_list(1);
-        a.n_agg_groups = 0;
-        a.n_agg_spans = &ctx->d_state()->stage_spans[0];
+        a.n_agg_spans = &ctx->d_state()->stage_spans[ctx->tables][0];
         a.lgp_spans = ctx->d_list(2);
         a.chunk_elems = ctx->chunk_elems;
         a.P = ctx->P;
@@ -1325,21 +1400,21 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
     const bool fused = element ? (ctx->applied1 && N <= kWindowMaxWorkers) : layer_window_fused(ctx);
     ctx->windows_fused = (ctx->windows_fused & 1) | (fused ? 2 : 0);
     hipStream_t s = (hipStream_t)stream;
-    if (!fused && !element) {
+    if (!fused && !element && !stream_is_capturing(s)) {
         // Layer-granular GIB: the split only needs the stage-2 aggregate, and it writes the new
         // stage tables into the other set.  Enqueued ahead of the install, it publishes the new
-        // table lengths while the install still runs, and the next iteration's first launch
-        // (which is shaped by them) is enqueued without the GPU running dry in between.
+        // table lengths while the install still runs, so a host that keeps pace with the GPU
+        // sizes the next iteration's grids exactly.  (Not while a graph is being captured: a
+        // captured split writes the set of tables its own iteration read, see osp_split.)
         st = aggregate_update(ctx, 2, grads, worker_stride, stream, bf16);
         if (st != OSP_OK)
             return st;
-        const Span *old_table = ctx->d_list(2);
-        const unsigned old_spans = (unsigned)ctx->stage_spans[1];   // (known: the aggregate waited)
+        const StageLaunch old2 = stage_launch(ctx, 2, s);    // the tables this iteration ran on
         const bool stage1_installed = ctx->applied1;
         st = osp_split(ctx, granularity, budget_elems, stream);
         if (st != OSP_OK)
             return st;
-        st = launch_install(ctx, old_table, old_spans, 2, false, s);
+        st = launch_install(ctx, old2.table, old2.grid_spans, 2, false, s);
         if (st != OSP_OK)
             return st;
         if (stage1_installed)
@@ -1386,13 +1461,10 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
             else
                 k_ics_window_element<false, false><<<grid, block, 0, s>>>(a);
         } else {
-            st = stage_counts(ctx);
-            if (st != OSP_OK)
-                return st;
+            // (the launch covers all groups; the kernel reads the stage-2 table's length)
             WindowLayerArgs a;
             a.agg_spans = ctx->d_list(2);
-            a.n_agg_groups = (unsigned)ctx->stage_spans[1] * kSpanChunks;
-            a.n_agg_spans = nullptr;
+            a.n_agg_spans = &ctx->d_state()->stage_spans[ctx->tables][1];
             a.lgp_spans = nullptr;
             a.chunk_elems = ctx->chunk_elems;
             a.P = ctx->P;
@@ -1408,7 +1480,7 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
             a.inv_n = 1.0f / (float)N;
             a.lr = ctx->lr;
             a.mu = ctx->mu;
-            launch_window_layer(ctx, a, a.n_agg_groups, s, bf16);
+            launch_window_layer(ctx, a, (unsigned)ctx->spans.size() * kSpanChunks, s, bf16);
         }
         st = launch_check(ctx, "osp_ics_window");
         if (st != OSP_OK)
@@ -1667,12 +1739,19 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         return fail(ctx, OSP_ERR_BAD_STATE,
                     "split needs the importances of a complete iteration (stage 2 or stage 0 aggregate)");
     hipStream_t s = (hipStream_t)stream;
+    const int old_tables = ctx->tables;
+    const bool old_pending = ctx->counts_pending;
     if (granularity == OSP_GRAN_LAYER) {
         const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
         k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
             ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
         const int ns = (int)ctx->spans.size();
-        ctx->tables ^= 1;               // the new GIB's tables go into the other set
+        // The new GIB's tables go into the other set, so that a launch over the old ones may
+        // still follow.  A split captured into a graph stays on its set: every replay reads
+        // the tables the replay before it wrote (the captured launches name one set for good),
+        // and nothing that reads the old tables is captured behind it.
+        if (!stream_is_capturing(s))
+            ctx->tables ^= 1;
         if (ctx->n_tensors <= kRankTile) {
             // one workgroup ranks in LDS and, unless the tables are long, fills them as well
             const bool fill = ns <= kRankFillMaxSpans;
@@ -1680,9 +1759,9 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
                 ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(), ctx->d_big(), (int)ctx->big_layers.size(),
                 ctx->d_imp(), ctx->d_numel(), ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                 ctx->d_order(), ctx->d_lbase(), ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq,
-                fill ? ns : 0, ctx->d_spans(), ctx->d_slayer(), ctx->d_list(1), ctx->d_list(2));
+                ctx->tables, fill ? ns : 0, ctx->d_spans(), ctx->d_slayer(), ctx->d_list(1),
+                ctx->d_list(2));
             if (fill) {
-                ctx->counts_stream = s;
                 ctx->counts_pending = true;
             } else {
                 osp_status ls = enqueue_stage_lists(ctx, s);
@@ -1695,7 +1774,8 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
                                                   ctx->d_imp(), ctx->d_numel(),
                                                   ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                                                   ctx->d_order(), ctx->d_lbase(), ctx->d_rscratch(),
-                                                  ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq);
+                                                  ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq,
+                                                  ctx->tables);
             osp_status ls = enqueue_stage_lists(ctx, s);
             if (ls != OSP_OK)
                 return ls;
@@ -1707,7 +1787,6 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         w.hist = ctx->d_hist(0);
         w.cand = ctx->d_cand();
         w.tile_ties = ctx->d_tile_ties();
-        w.tile_before = ctx->d_tile_before();
         enqueue_element_select(ctx->d_key(), ctx->n_vec, ctx->n_words, ctx->n_tiles,
                                (long long)budget_elems, w, ctx->d_bitmap(), s);
         ctx->counts_pending = false;    // stage tables belong to layer-granular GIBs only
@@ -1715,8 +1794,11 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     }
     osp_status st = launch_check(ctx, "split kernels");
     if (st != OSP_OK) {
-        if (granularity == OSP_GRAN_LAYER)
-            ctx->tables ^= 1;           // the old GIB and its tables stay current
+        // The old GIB stays current with its set of tables, whose lengths on the device the
+        // failed split did not touch (it works on the other set).  Sequence numbers are not
+        // reused: part of the split may have been enqueued.
+        ctx->tables = old_tables;
+        ctx->counts_pending = old_pending;
         return st;
     }
     ctx->have_gib = true;
@@ -1751,8 +1833,11 @@ osp_status osp_split_element_static(const uint32_t *keys, int64_t n_elems, int64
     w.hist = reinterpret_cast<unsigned long long *>(base + kStaticOffHist);
     w.cand = reinterpret_cast<TieCandidate *>(base + kStaticOffCand);
     w.tile_ties = reinterpret_cast<unsigned int *>(base + kStaticOffTies);
-    w.tile_before = reinterpret_cast<unsigned long long *>(base + kStaticOffBefore);
     const long long n_tiles = (n_elems + kSelTile - 1) / kSelTile;
+    // The array keeps what the last call on this GPU left: the split state (its tickets) and
+    // the histograms must start at zero, whatever became of that call.
+    k_fill_u32<<<24, kSplitBlock, 0, (hipStream_t)stream>>>(reinterpret_cast<uint32_t *>(base),
+                                                            (long long)(kStaticOffCand / 4), 0u);
     enqueue_element_select(keys, n_elems / 4, (n_elems + 31) / 32, n_tiles, (long long)budget_elems,
                            w, elem_bitmap, (hipStream_t)stream);
     return launch_check(ctx, "element select kernels");

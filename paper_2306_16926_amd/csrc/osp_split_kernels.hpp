@@ -5,12 +5,11 @@
 // (importance, index) and take the longest prefix that fits the budget.
 //
 // Element granularity: exact selection of the `budget` smallest 32-bit keys
-// with ties broken by arena index.  Three radix passes (11 + 11 + 10 bits, most
-// significant first) with per-workgroup LDS histograms find the threshold key T
-// and the number r of elements equal to T that still belong to stage 2; a
-// per-tile count of ties plus an exclusive scan over tiles turns "the first r
-// ties in index order" into a local decision, and the last pass writes the
-// bitmap.  Integer arithmetic only.
+// with ties broken by arena index: two radix passes (11 + 11 bits, most
+// significant first) with per-workgroup LDS histograms find the upper 22 bits
+// of the threshold key, a third pass writes the bitmap and lists the few keys
+// that share those bits, and one workgroup decides among them.  Integer
+// arithmetic only.
 #pragma once
 #include "osp_stream_kernels.hpp"
 
@@ -38,30 +37,54 @@ __device__ __forceinline__ void publish_counts(StageCounts *out, int n1, int n2,
     __hip_atomic_store(&out->seq, seq, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_SYSTEM);
 }
 
+// One value from device memory into host memory the device can write (pinned, mapped).
+__global__ void k_publish_i64(const long long *__restrict__ src, long long *__restrict__ dst_host)
+{
+    __hip_atomic_store(dst_host, *src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_SYSTEM);
+}
+
 struct SplitState {                    // one per context, in the workspace
     long long n_stage2;                // elements in stage 2 under the current GIB
-    int stage_spans[2];                // spans in the stage-1 / stage-2 table (layer GIB)
+    int stage_spans[2][2];             // [table set][stage - 1]: spans in that set's stage table
+                                       // (layer GIB; two sets of tables, written alternately)
     unsigned long long k_rem;          // rank still to be found inside the current radix bucket
     unsigned long long ties_to_take;   // r
     unsigned int prefix;               // key bits decided so far (right-aligned)
     unsigned int threshold;            // T
     unsigned int done;                 // 1: budget 0, nothing is selected
-    unsigned int all_ties;             // 1: every key equal to T is taken (no per-tile counts needed)
-    unsigned int collect;              // 1: the last radix pass lists the keys of its bucket
-    unsigned int ties_by_limit;        // 1: a key equal to T is taken iff its index < tie_limit
-    unsigned long long tie_limit;
+    unsigned int all_ties;             // 1: every key equal to T is taken
+    unsigned int collect;              // 1: few keys share the threshold's 22-bit prefix; the bitmap
+                                       // pass lists them and one workgroup decides among them
+    unsigned int tickets[3];           // workgroups that have finished radix pass 0, 1, 2
+    long long *log;                    // caller's log of stage-2 sizes, or null (osp_set_stage2_log)
+    long long log_cap;
+    unsigned long long n_splits;       // splits since the log was set
 };
 
-// Keys that share the threshold's upper 22 bits, listed by the last radix pass when there are
-// few of them (the usual case): the ties among them are then cut by arena index in one
-// workgroup instead of two more passes over all keys.
+// Every split leaves the size of its stage 2 in the caller's log (if there is one).
+__device__ __forceinline__ void log_stage2(SplitState *st, long long n_stage2)
+{
+    if (st->log != nullptr)
+        st->log[st->n_splits % (unsigned long long)st->log_cap] = n_stage2;
+    st->n_splits += 1;
+}
+
+__global__ void k_set_stage2_log(SplitState *st, long long *log, long long cap)
+{
+    st->log = log;
+    st->log_cap = cap;
+    st->n_splits = 0;
+}
+
+// Keys that share the threshold's upper 22 bits, listed by the bitmap pass when there are few of
+// them (the usual case): one workgroup then decides among them instead of more passes over all
+// keys.
 struct TieCandidate {
     unsigned long long index;          // arena index of the element
     unsigned int key;
     unsigned int pad;
 };
 constexpr unsigned kTieCandidates = 65536;    // capacity of the list
-constexpr int kTieSortMax = 2048;             // ties cut through LDS up to this many
 
 // ---------------------------------------------------------------------------
 // layer granularity
@@ -177,7 +200,7 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
     const int *__restrict__ layer_span_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
     long long *__restrict__ scratch, SplitState *__restrict__ st,
-    StageCounts *__restrict__ counts_out, unsigned seq)
+    StageCounts *__restrict__ counts_out, unsigned seq, int set)
 {
     __shared__ __align__(16) unsigned long long tile[kRankTile];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -286,9 +309,10 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
         carry2 += tot2;
     }
     if (threadIdx.x == 0) {
-        st->stage_spans[0] = carry1;
-        st->stage_spans[1] = carry2;
-        publish_counts(counts_out, carry1, carry2, st->n_stage2, seq);   // the host shapes the next launches
+        st->stage_spans[set][0] = carry1;
+        st->stage_spans[set][1] = carry2;
+        log_stage2(st, st->n_stage2);
+        publish_counts(counts_out, carry1, carry2, st->n_stage2, seq);   // a hint for the host's next grids
     }
 }
 
@@ -304,7 +328,7 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
     const int *__restrict__ big_layers, int n_big, double *__restrict__ imp,
     const long long *__restrict__ numel, const int *__restrict__ layer_span_begin, long long budget,
     uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
-    SplitState *__restrict__ st, StageCounts *__restrict__ counts_out, unsigned seq,
+    SplitState *__restrict__ st, StageCounts *__restrict__ counts_out, unsigned seq, int set,
     int n_spans, const Span *__restrict__ spans, const int *__restrict__ span_layer,
     Span *__restrict__ list_s1, Span *__restrict__ list_s2)
 {
@@ -454,18 +478,30 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
     }
     if (threadIdx.x == 0) {
         st->n_stage2 = n_stage2_found;
-        st->stage_spans[0] = carry1;
-        st->stage_spans[1] = carry2;
+        st->stage_spans[set][0] = carry1;
+        st->stage_spans[set][1] = carry2;
+        log_stage2(st, n_stage2_found);
         publish_counts(counts_out, carry1, carry2, n_stage2_found, seq);
     }
     __syncthreads();
+    // Span k goes to its place in its stage's table; the same place behind the other table's
+    // last entry is cleared (the two lengths add up to the number of spans, so this clears
+    // exactly the unused entries: a table ends at its first cleared entry).
+    Span cleared;
+    cleared.start = 0; cleared.n_elems = 0; cleared.chunk_base = 0;
 #pragma unroll
     for (int j = 0; j < kSpansPer; ++j) {
         const int k = j * BLOCK + (int)threadIdx.x;
         if (k < n_spans) {
             const int l = my_span_layer[j];
             const int pos = base_of_layer[l] + (k - first_span_of_layer[l]);
-            (important_layer[l] ? list_s1 : list_s2)[pos] = my_span[j];
+            if (important_layer[l]) {
+                list_s1[pos] = my_span[j];
+                list_s2[carry2 + pos] = cleared;
+            } else {
+                list_s2[pos] = my_span[j];
+                list_s1[carry1 + pos] = cleared;
+            }
         }
     }
 }
@@ -474,7 +510,7 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
 __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
                               const int *__restrict__ layer_span_begin,
                               int *__restrict__ layer_base, SplitState *__restrict__ st,
-                              StageCounts *__restrict__ counts_out, unsigned seq)
+                              StageCounts *__restrict__ counts_out, unsigned seq, int set)
 {
     if (blockIdx.x != 0 || threadIdx.x != 0)
         return;
@@ -489,114 +525,68 @@ __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
             n2 += ns;
         }
     }
-    st->stage_spans[0] = n1;
-    st->stage_spans[1] = n2;
+    st->stage_spans[set][0] = n1;
+    st->stage_spans[set][1] = n2;
     publish_counts(counts_out, n1, n2, st->n_stage2, seq);
 }
 
 // Fill the two stage tables: span k of layer l goes to position
-// layer_base[l] + (k - first span of l) of the table of l's stage.
+// layer_base[l] + (k - first span of l) of the table of l's stage, and the same position
+// behind the other table's last entry is cleared (see k_layer_rank_lds).
 __global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
     int n_spans, const Span *__restrict__ spans, const int *__restrict__ span_layer,
     const uint8_t *__restrict__ gib_layer, const int *__restrict__ layer_span_begin,
-    const int *__restrict__ layer_base, Span *__restrict__ list_s1, Span *__restrict__ list_s2)
+    const int *__restrict__ layer_base, const SplitState *__restrict__ st, int set,
+    Span *__restrict__ list_s1, Span *__restrict__ list_s2)
 {
     const int k = blockIdx.x * kSplitBlock + threadIdx.x;
     if (k >= n_spans)
         return;
     const int l = span_layer[k];
     const int pos = layer_base[l] + (k - layer_span_begin[l]);
-    (gib_layer[l] ? list_s1 : list_s2)[pos] = spans[k];
+    Span cleared;
+    cleared.start = 0; cleared.n_elems = 0; cleared.chunk_base = 0;
+    if (gib_layer[l]) {
+        list_s1[pos] = spans[k];
+        list_s2[st->stage_spans[set][1] + pos] = cleared;
+    } else {
+        list_s2[pos] = spans[k];
+        list_s1[st->stage_spans[set][0] + pos] = cleared;
+    }
 }
 
 // ---------------------------------------------------------------------------
 // element granularity
+//
+// Exact selection of the `budget` smallest 32-bit keys, ties broken by arena index, in six
+// launches and three passes over the keys:
+//   1. histogram of the top 11 bits; the workgroup that finishes last finds the bucket of the
+//      budget-th smallest key;
+//   2. histogram of the next 11 bits inside that bucket; its last workgroup finds the 22-bit
+//      prefix P of the threshold and how many keys share it;
+//   3. bitmap pass: a key whose upper 22 bits are below P goes to stage 2, above P to stage 1;
+//      the (few) keys with exactly P are listed as candidates and left in stage 1 for now;
+//   4. one workgroup picks, among the candidates, the ones that still belong to stage 2 (by
+//      their low 10 bits, then by arena index) and clears their bits.
+// When more than kTieCandidates keys share P (long runs of equal keys: zeros, quantised
+// gradients) launch 4 is instead the histogram of the last 10 bits over all keys, and two more
+// launches count the ties per tile and write the bitmap again.  Those two launches are always
+// enqueued and return at once when not needed, so the host never has to know.
+// Integer arithmetic only.  The histograms and counters are left zeroed by the workgroups that
+// consume them, ready for the next split.
 // ---------------------------------------------------------------------------
 constexpr int kRadixBins = 2048;
 // pass 0: bits 31..21, pass 1: bits 20..10, pass 2: bits 9..0
-__device__ __forceinline__ int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
-__device__ __forceinline__ int radix_bits(int pass) { return pass == 2 ? 10 : 11; }
+__device__ __forceinline__ constexpr int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
+__device__ __forceinline__ constexpr int radix_bits(int pass) { return pass == 2 ? 10 : 11; }
 
-constexpr int kSelTile = 8192;         // keys per tile of the tie-count / bitmap passes
+constexpr int kSelTile = 8192;         // keys per tile of the bitmap / tie-count passes
 
 __global__ __launch_bounds__(kSplitBlock) void k_fill_u32(uint32_t *p, long long n, uint32_t v)
 {
     for (long long i = (long long)blockIdx.x * kSplitBlock + threadIdx.x; i < n;
          i += (long long)gridDim.x * kSplitBlock)
         p[i] = v;
-}
-
-template <int PASS>
-__global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
-    const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
-    unsigned long long *__restrict__ hist, TieCandidate *__restrict__ cand = nullptr,
-    unsigned int *__restrict__ n_cand = nullptr)
-{
-    __shared__ unsigned int h[kRadixBins];
-    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
-        h[b] = 0;
-    __syncthreads();
-    const int shift = radix_shift(PASS);
-    const unsigned mask = (1u << radix_bits(PASS)) - 1u;
-    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
-    const bool collect = PASS == 2 && st->collect != 0;
-    const int hi = shift + radix_bits(PASS);          // bits above this pass's digit
-    const u4 *kv = reinterpret_cast<const u4 *>(key);
-    // four 16-byte loads in flight per thread; keys of one group that fall into one bin
-    // (the rule in the first pass, whose digit is mostly exponent) cost one LDS atomic
-    constexpr int kUnroll = 4;
-    const long long stride = (long long)gridDim.x * kSplitBlock;
-    for (long long v0 = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v0 < n_vec;
-         v0 += kUnroll * stride) {
-        u4 k[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            const long long v = v0 + u * stride;
-            if (v < n_vec)
-                k[u] = __builtin_nontemporal_load(kv + v);
-        }
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) {
-            if (v0 + u * stride >= n_vec)
-                continue;
-            unsigned bin[kVec];
-            bool in[kVec];
-#pragma unroll
-            for (int j = 0; j < kVec; ++j) {
-                const unsigned x = k[u][j];
-                in[j] = PASS == 0 || (x >> hi) == prefix;
-                bin[j] = (x >> shift) & mask;
-            }
-            if (collect) {
-                // (the bucket holds at most kTieCandidates keys, so every slot exists)
-#pragma unroll
-                for (int j = 0; j < kVec; ++j)
-                    if (in[j]) {
-                        const unsigned slot = atomicAdd(n_cand, 1u);
-                        if (slot < kTieCandidates) {
-                            TieCandidate tc;
-                            tc.index = (unsigned long long)(v0 + u * stride) * kVec + j;
-                            tc.key = k[u][j];
-                            tc.pad = 0;
-                            cand[slot] = tc;
-                        }
-                    }
-            }
-            if (in[0] && in[1] && in[2] && in[3] && bin[0] == bin[1] && bin[0] == bin[2] &&
-                bin[0] == bin[3]) {
-                atomicAdd(&h[bin[0]], 4u);
-            } else {
-#pragma unroll
-                for (int j = 0; j < kVec; ++j)
-                    if (in[j])
-                        atomicAdd(&h[bin[j]], 1u);
-            }
-        }
-    }
-    __syncthreads();
-    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
-        if (h[b])
-            atomicAdd(&hist[b], (unsigned long long)h[b]);
 }
 
 // Exclusive scan of one unsigned long long per thread over the 256-thread
@@ -625,24 +615,89 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
     return base + incl - x;
 }
 
-// One workgroup: find the bucket of this pass that holds the k-th smallest key.
-__global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long budget,
-                                                        const unsigned long long *__restrict__ hist,
-                                                        SplitState *__restrict__ st,
-                                                        const TieCandidate *__restrict__ cand = nullptr,
-                                                        const unsigned int *__restrict__ n_cand = nullptr)
+// The bin that holds the want-th smallest item (want >= 1) of a histogram whose counts are
+// spread over the workgroup, PER consecutive bins per thread: the unique bin with
+// below < want <= below + count.  Every thread gets the answer; bin < 0 if want exceeds the
+// total.  All threads of the workgroup must call it.
+template <int PER>
+__device__ __forceinline__ void find_rank_bin(const unsigned long long (&c)[PER],
+                                              unsigned long long want, int &bin,
+                                              unsigned long long &below, unsigned long long &count)
 {
-    __shared__ unsigned long long tie_index[kTieSortMax];
-    __shared__ unsigned int n_ties;
-    __shared__ int found_bin;
-    __shared__ unsigned long long found_below, found_count;
-    if (pass == 0 && threadIdx.x == 0) {
+    __shared__ int s_bin;
+    __shared__ unsigned long long s_below, s_count;
+    unsigned long long mine = 0;
+#pragma unroll
+    for (int j = 0; j < PER; ++j)
+        mine += c[j];
+    if (threadIdx.x == 0)
+        s_bin = -1;
+    const unsigned long long before = block_exclusive_scan(mine, nullptr);   // (barriers inside)
+    if (before < want && want <= before + mine) {
+        unsigned long long run = before;
+#pragma unroll
+        for (int j = 0; j < PER; ++j) {
+            if (run < want && want <= run + c[j]) {
+                s_bin = (int)threadIdx.x * PER + j;
+                s_below = run;
+                s_count = c[j];
+            }
+            run += c[j];
+        }
+    }
+    __syncthreads();
+    bin = s_bin;
+    below = s_below;
+    count = s_count;
+    __syncthreads();                   // the shared slots are free for the next call
+}
+
+// True in exactly one workgroup of the launch: the one whose threads all get here last.  What
+// every workgroup wrote (with device-scope atomics) before the call is visible to that one
+// afterwards through device-scope loads.  The ticket counter is left at zero.
+__device__ __forceinline__ bool last_workgroup(unsigned int *ticket)
+{
+    __shared__ bool last;
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned t = atomicAdd(ticket, 1u);
+        last = t == gridDim.x - 1;
+        if (last)
+            *ticket = 0;
+    }
+    __syncthreads();
+    if (last)
+        __threadfence();
+    return last;
+}
+
+__device__ __forceinline__ unsigned long long load_device_scope(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One workgroup, after the histogram of radix pass PASS is complete: find the bucket of the
+// k-th smallest key and record it; the histogram is read through device-scope loads and left
+// zeroed.
+template <int PASS>
+__device__ __forceinline__ void select_pick(long long budget, unsigned long long *__restrict__ hist,
+                                            SplitState *__restrict__ st)
+{
+    constexpr int per = kRadixBins / kSplitBlock;          // 8 consecutive bins per thread
+    unsigned long long c[per];
+#pragma unroll
+    for (int j = 0; j < per; ++j) {
+        c[j] = load_device_scope(&hist[threadIdx.x * per + j]);
+        hist[threadIdx.x * per + j] = 0;
+    }
+    if (PASS == 0 && threadIdx.x == 0) {
         st->done = budget == 0 ? 1u : 0u;
         st->n_stage2 = budget;
+        log_stage2(st, budget);
     }
-    const unsigned long long k = pass == 0 ? (unsigned long long)budget : st->k_rem;
-    const bool done = pass == 0 ? budget == 0 : st->done != 0;
-    if (done) {
+    const unsigned long long k = PASS == 0 ? (unsigned long long)budget : st->k_rem;
+    if (PASS == 0 && budget == 0) {    // nothing is selected (later launches see st->done)
         if (threadIdx.x == 0) {
             st->threshold = 0;
             st->ties_to_take = 0;
@@ -650,98 +705,108 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_pick(int pass, long long
             st->k_rem = 0;
             st->all_ties = 0;
             st->collect = 0;
-            st->ties_by_limit = 0;
         }
         return;
     }
-    constexpr int per = kRadixBins / kSplitBlock;          // 8 consecutive bins per thread
-    unsigned long long c[per];
-    unsigned long long mine = 0;
+    int bin;
+    unsigned long long below, count;
+    find_rank_bin<per>(c, k, bin, below, count);
+    if (threadIdx.x != 0)
+        return;
+    if (bin < 0) {                     // cannot happen for budget <= number of keys
+        st->done = 1;
+        st->threshold = 0;
+        st->ties_to_take = 0;
+        st->all_ties = 0;
+        st->collect = 0;
+        return;
+    }
+    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
+    const unsigned np = (prefix << radix_bits(PASS)) | (unsigned)bin;
+    st->prefix = np;
+    st->k_rem = k - below;
+    if (PASS == 0)
+        st->collect = 0;
+    if (PASS == 1)                     // few keys share the 22-bit prefix: the bitmap pass lists them
+        st->collect = count <= kTieCandidates ? 1u : 0u;
+    if (PASS == 2) {
+        st->threshold = np;
+        st->ties_to_take = k - below;
+        // (distinct keys around the threshold: all keys equal to T are taken)
+        st->all_ties = (k - below == count) ? 1u : 0u;
+    }
+}
+
+// Histogram of one radix digit over all keys (PASS 0), or over the keys whose higher bits
+// equal the prefix found so far; per-workgroup counts in LDS, flushed with one global atomic
+// per non-empty bin.  The last workgroup to finish picks the bucket (select_pick).
+template <int PASS>
+__device__ __forceinline__ void select_histogram(const uint32_t *__restrict__ key, long long n_vec,
+                                                 long long budget, SplitState *__restrict__ st,
+                                                 unsigned long long *__restrict__ hist)
+{
+    __shared__ unsigned int h[kRadixBins];
+    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+        h[b] = 0;
+    __syncthreads();
+    constexpr int shift = radix_shift(PASS);
+    constexpr unsigned mask = (1u << radix_bits(PASS)) - 1u;
+    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
+    constexpr int hi = shift + radix_bits(PASS);      // bits above this pass's digit
+    const u4 *kv = reinterpret_cast<const u4 *>(key);
+    // four 16-byte loads in flight per thread; keys of one group that fall into one bin
+    // (the rule in the first pass, whose digit is mostly exponent) cost one LDS atomic
+    constexpr int kUnroll = 4;
+    const long long stride = (long long)gridDim.x * kSplitBlock;
+    for (long long v0 = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v0 < n_vec;
+         v0 += kUnroll * stride) {
+        u4 k[kUnroll];
 #pragma unroll
-    for (int j = 0; j < per; ++j) {
-        c[j] = hist[threadIdx.x * per + j];
-        mine += c[j];
-    }
-    if (threadIdx.x == 0)
-        found_bin = -1;
-    const unsigned long long before = block_exclusive_scan(mine, nullptr);
-    // the k-th smallest (k >= 1) lies in the unique bin with below < k <= below + count
-    if (before < k && k <= before + mine) {
-        unsigned long long below = before;
+        for (int u = 0; u < kUnroll; ++u) {
+            const long long v = v0 + u * stride;
+            if (v < n_vec)
+                k[u] = __builtin_nontemporal_load(kv + v);
+        }
 #pragma unroll
-        for (int j = 0; j < per; ++j) {
-            if (below < k && k <= below + c[j]) {
-                found_bin = threadIdx.x * per + j;
-                found_below = below;
-                found_count = c[j];
+        for (int u = 0; u < kUnroll; ++u) {
+            if (v0 + u * stride >= n_vec)
+                continue;
+            unsigned bin[kVec];
+            bool in[kVec];
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const unsigned x = k[u][j];
+                in[j] = PASS == 0 || (x >> hi) == prefix;
+                bin[j] = (x >> shift) & mask;
             }
-            below += c[j];
-        }
-    }
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        if (pass == 0)
-            st->collect = 0;
-        if (pass != 2)
-            st->ties_by_limit = 0;
-        if (found_bin < 0) {           // cannot happen for budget <= number of keys
-            st->done = 1;
-            st->threshold = 0;
-            st->ties_to_take = 0;
-            st->all_ties = 0;
-            st->collect = 0;
-        } else {
-            const unsigned prefix = pass == 0 ? 0u : st->prefix;
-            const unsigned np = (prefix << radix_bits(pass)) | (unsigned)found_bin;
-            st->prefix = np;
-            st->k_rem = k - found_below;
-            if (pass == 1)             // few keys left: the last pass lists them
-                st->collect = found_count <= kTieCandidates ? 1u : 0u;
-            if (pass == 2) {
-                st->threshold = np;
-                st->ties_to_take = k - found_below;
-                // the usual case (distinct keys around the threshold): all keys equal to T
-                // are taken, and the order among them does not matter
-                st->all_ties = (k - found_below == found_count) ? 1u : 0u;
+            if (in[0] && in[1] && in[2] && in[3] && bin[0] == bin[1] && bin[0] == bin[2] &&
+                bin[0] == bin[3]) {
+                atomicAdd(&h[bin[0]], 4u);
+            } else {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    if (in[j])
+                        atomicAdd(&h[bin[j]], 1u);
             }
         }
     }
-    if (pass != 2 || cand == nullptr)
+    __syncthreads();
+    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+        if (h[b])
+            atomicAdd(&hist[b], (unsigned long long)h[b]);
+    if (last_workgroup(&st->tickets[PASS]))
+        select_pick<PASS>(budget, hist, st);
+}
+
+template <int PASS>
+__global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
+    const uint32_t *__restrict__ key, long long n_vec, long long budget,
+    SplitState *__restrict__ st, unsigned long long *__restrict__ hist)
+{
+    static_assert(PASS == 0 || PASS == 1, "the last digit is handled by k_select_finish");
+    if (PASS == 1 && st->done)
         return;
-    // Ties at the threshold that are not all taken: the first r of them in index order are.
-    // With the bucket's keys listed, gather the ties' indices, find the r-th smallest, and the
-    // bitmap pass only compares indices with it.  (All threads reach this point; what they
-    // read from st was written by thread 0 before the barrier below.)
-    __threadfence_block();
-    __syncthreads();
-    if (found_bin < 0 || st->collect == 0 || st->all_ties != 0)
-        return;
-    const unsigned T = st->threshold;
-    const unsigned long long r = st->ties_to_take;          // 1 <= r < number of ties
-    const unsigned n = *n_cand < kTieCandidates ? *n_cand : kTieCandidates;
-    if (threadIdx.x == 0)
-        n_ties = 0;
-    __syncthreads();
-    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock)
-        if (cand[c].key == T) {
-            const unsigned slot = atomicAdd(&n_ties, 1u);
-            if (slot < (unsigned)kTieSortMax)
-                tie_index[slot] = cand[c].index;
-        }
-    __syncthreads();
-    const unsigned t = n_ties;
-    if (t > (unsigned)kTieSortMax || (unsigned long long)t != found_count)
-        return;                        // too many for LDS (or the list is not complete): per-tile counts
-    for (unsigned i = threadIdx.x; i < t; i += kSplitBlock) {
-        const unsigned long long mine = tie_index[i];
-        unsigned long long smaller = 0;
-        for (unsigned j = 0; j < t; ++j)
-            smaller += tie_index[j] < mine ? 1u : 0u;
-        if (smaller == r)              // the first tie that is NOT taken
-            st->tie_limit = mine;
-    }
-    if (threadIdx.x == 0)
-        st->ties_by_limit = 1;
+    select_histogram<PASS>(key, n_vec, budget, st, hist);
 }
 
 __device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key, long long v,
@@ -754,12 +819,152 @@ __device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key,
     return pad;
 }
 
-// Per tile: how many keys equal the threshold.
+// Eight neighbouring lanes hold 4 bits each of one 32-bit bitmap word (bit = 1: important).
+__device__ __forceinline__ void store_bitmap_word(unsigned sel, long long v, long long n_words,
+                                                  uint32_t *__restrict__ bitmap)
+{
+    unsigned word = (~sel & 0xFu) << ((threadIdx.x & 7) * 4);
+    word |= __shfl_xor(word, 1, 64);
+    word |= __shfl_xor(word, 2, 64);
+    word |= __shfl_xor(word, 4, 64);
+    const long long w = v >> 3;        // 8 lanes x 4 keys = one 32-bit word
+    if ((threadIdx.x & 7) == 0 && w < n_words)
+        bitmap[w] = word;
+}
+
+// Launch 3: the bitmap from the 22-bit prefix P of the threshold.  Upper 22 bits below P:
+// stage 2.  Equal to P: listed as a candidate (when few keys share P) and left in stage 1 until
+// k_select_finish has decided; above P: stage 1.
+__global__ __launch_bounds__(kSplitBlock) void k_select_bitmap(
+    const uint32_t *__restrict__ key, long long n_vec, long long n_words,
+    const SplitState *__restrict__ st, TieCandidate *__restrict__ cand,
+    unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
+{
+    const bool none = st->done != 0;
+    const bool collect = st->collect != 0;
+    const unsigned P = st->prefix;
+    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
+    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
+        const long long v = v0 + it * kSplitBlock + threadIdx.x;
+        const u4 k = load_keys_or_pad(key, v, n_vec);
+        unsigned sel = 0;              // bit j: element j goes to stage 2
+        if (!none) {
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const unsigned hi = k[j] >> 10;
+                sel |= (hi < P ? 1u : 0u) << j;
+                if (hi == P && collect && v < n_vec) {
+                    // (at most kTieCandidates keys share P, so every slot exists)
+                    const unsigned slot = atomicAdd(n_cand, 1u);
+                    if (slot < kTieCandidates) {
+                        TieCandidate tc;
+                        tc.index = (unsigned long long)v * kVec + j;
+                        tc.key = k[j];
+                        tc.pad = 0;
+                        cand[slot] = tc;
+                    }
+                }
+            }
+        }
+        store_bitmap_word(sel, v, n_words, bitmap);
+    }
+}
+
+// Launch 4.  Few keys share the prefix (st->collect): workgroup 0 takes, among the listed
+// candidates, the r = st->k_rem smallest in the order (low 10 bits, arena index) and clears
+// their bits; the other workgroups return.  Otherwise: the histogram of the last 10 bits over
+// all keys, and its last workgroup fixes the threshold and the number of ties to take.
+constexpr int kIndexDigit = 11;        // arena indices are cut by four digits of 11 bits (< 2^44)
+
+__global__ __launch_bounds__(kSplitBlock) void k_select_finish(
+    const uint32_t *__restrict__ key, long long n_vec, long long budget,
+    SplitState *__restrict__ st, unsigned long long *__restrict__ hist,
+    const TieCandidate *__restrict__ cand, unsigned int *__restrict__ n_cand,
+    uint32_t *__restrict__ bitmap)
+{
+    if (st->done)
+        return;
+    if (!st->collect) {
+        select_histogram<2>(key, n_vec, budget, st, hist);
+        return;
+    }
+    if (blockIdx.x != 0)
+        return;
+    __shared__ unsigned int lh[kRadixBins];
+    const unsigned n = *n_cand < kTieCandidates ? *n_cand : kTieCandidates;
+    const unsigned long long r = st->k_rem;                 // 1 <= r <= n
+    const unsigned P = st->prefix;
+    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+        lh[b] = 0;
+    __syncthreads();
+    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock)
+        atomicAdd(&lh[cand[c].key & 1023u], 1u);
+    __syncthreads();
+    int low;                                                // the threshold's last 10 bits
+    unsigned long long below, count;
+    {
+        unsigned long long c4[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            c4[j] = lh[threadIdx.x * 4 + j];
+        find_rank_bin<4>(c4, r, low, below, count);
+    }
+    if (low < 0)                                            // (the list is incomplete: cannot happen)
+        return;
+    const unsigned long long r2 = r - below;                // ties to take, 1 <= r2 <= count
+    const bool all = r2 == count;
+    // Ties that are not all taken: the first r2 of them in index order are.  `cut` = the r2-th
+    // smallest index among the ties, found digit by digit from the top.
+    unsigned long long cut = ~0ull;
+    if (!all) {
+        unsigned long long idx_prefix = 0, want = r2;
+        for (int round = 0; round < 4; ++round) {
+            const int shift = kIndexDigit * (3 - round);
+            for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+                lh[b] = 0;
+            __syncthreads();
+            for (unsigned c = threadIdx.x; c < n; c += kSplitBlock) {
+                const TieCandidate tc = cand[c];
+                if ((tc.key & 1023u) == (unsigned)low &&
+                    (round == 0 || (tc.index >> (shift + kIndexDigit)) == idx_prefix))
+                    atomicAdd(&lh[(tc.index >> shift) & (kRadixBins - 1)], 1u);
+            }
+            __syncthreads();
+            unsigned long long c8[8];
+#pragma unroll
+            for (int j = 0; j < 8; ++j)
+                c8[j] = lh[threadIdx.x * 8 + j];
+            int digit;
+            unsigned long long d_below, d_count;
+            find_rank_bin<8>(c8, want, digit, d_below, d_count);
+            if (digit < 0)
+                return;                                     // (cannot happen)
+            idx_prefix = (idx_prefix << kIndexDigit) | (unsigned long long)digit;
+            want -= d_below;
+        }
+        cut = idx_prefix;
+    }
+    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock) {
+        const TieCandidate tc = cand[c];
+        const unsigned l = tc.key & 1023u;
+        if (l < (unsigned)low || (l == (unsigned)low && (all || tc.index <= cut)))
+            atomicAnd(&bitmap[tc.index >> 5], ~(1u << (unsigned)(tc.index & 31)));
+    }
+    if (threadIdx.x == 0) {
+        st->threshold = (P << 10) | (unsigned)low;
+        st->ties_to_take = r2;
+        st->all_ties = all ? 1u : 0u;
+        *n_cand = 0;
+    }
+}
+
+// Launch 5 (only when many keys share the threshold's prefix): per tile, how many keys equal
+// the threshold.
 __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
     const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
     unsigned int *__restrict__ tile_ties)
 {
-    if (st->all_ties || st->done || st->ties_by_limit)  // uniform: the bitmap pass will not read the counts
+    if (st->collect || st->done || st->all_ties)    // uniform: the bitmap pass will not read the counts
         return;
     const unsigned T = st->threshold;
     const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
@@ -774,49 +979,31 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
         tile_ties[blockIdx.x] = (unsigned int)total;
 }
 
-// One workgroup: exclusive scan of the per-tile tie counts, in tile order.
-__global__ __launch_bounds__(kSplitBlock) void k_select_scan_tiles(
-    const unsigned int *__restrict__ tile_ties, long long n_tiles,
-    const SplitState *__restrict__ st, unsigned long long *__restrict__ tile_before)
-{
-    if (st->all_ties || st->done || st->ties_by_limit)
-        return;
-    const long long per = (n_tiles + kSplitBlock - 1) / kSplitBlock;
-    const long long b = (long long)threadIdx.x * per;
-    const long long e = b + per < n_tiles ? b + per : n_tiles;
-    unsigned long long mine = 0;
-    for (long long t = b; t < e; ++t)
-        mine += tile_ties[t];
-    unsigned long long run = block_exclusive_scan(mine, nullptr);
-    for (long long t = b; t < e; ++t) {
-        tile_before[t] = run;
-        run += tile_ties[t];
-    }
-}
-
-// Write the element bitmap: bit = 1 (important, stage 1) unless the element is
-// among the `budget` smallest in the order (key, index).
+// Launch 6 (same condition): the bitmap from the full threshold T; of the keys equal to T the
+// first r in index order go to stage 2.  A tile adds up the tie counts of the tiles before it.
 __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
     const uint32_t *__restrict__ key, long long n_vec, long long n_words,
     const SplitState *__restrict__ st, const unsigned int *__restrict__ tile_ties,
-    const unsigned long long *__restrict__ tile_before, uint32_t *__restrict__ bitmap)
+    uint32_t *__restrict__ bitmap)
 {
+    if (st->collect || st->done)
+        return;
     const unsigned T = st->threshold;
     const unsigned long long r = st->ties_to_take;
-    const bool none = st->done != 0;
     const bool all = st->all_ties != 0;
-    const bool by_limit = st->ties_by_limit != 0;
-    const unsigned long long limit = st->tie_limit;
-    const unsigned long long before = (none || all || by_limit) ? 0 : tile_before[blockIdx.x];
-    const unsigned long long ties = (none || all || by_limit) ? 0 : tile_ties[blockIdx.x];
-    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside,
-    // 3: those with an arena index below `limit` are
+    unsigned long long before = 0, ties = 0;
+    if (!all) {
+        unsigned long long mine = 0;
+        for (long long t = threadIdx.x; t < (long long)blockIdx.x; t += kSplitBlock)
+            mine += tile_ties[t];
+        block_exclusive_scan(mine, &before);
+        ties = tile_ties[blockIdx.x];
+    }
+    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
     int tie_mode;
     if (all)
         tie_mode = 1;
-    else if (by_limit && !none)
-        tie_mode = 3;
-    else if (none || ties == 0 || before >= r)
+    else if (ties == 0 || before >= r)
         tie_mode = 0;
     else if (before + ties <= r)
         tie_mode = 1;
@@ -828,38 +1015,28 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
         const long long v = v0 + it * kSplitBlock + threadIdx.x;
         const u4 k = load_keys_or_pad(key, v, n_vec);
         unsigned sel = 0;              // bit j: element j goes to stage 2
-        if (!none) {
-            unsigned long long my_before = 0;
-            if (tie_mode == 2) {
-                const unsigned long long n = (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
-                unsigned long long total;
-                my_before = run + block_exclusive_scan(n, &total);
-                run += total;
-            }
-#pragma unroll
-            for (int j = 0; j < kVec; ++j) {
-                const unsigned x = k[j];
-                bool s = x < T;
-                if (x == T) {
-                    if (tie_mode == 1)
-                        s = true;
-                    else if (tie_mode == 2) {
-                        s = my_before < r;
-                        ++my_before;
-                    } else if (tie_mode == 3) {
-                        s = (unsigned long long)v * kVec + j < limit;
-                    }
-                }
-                sel |= (s ? 1u : 0u) << j;
-            }
+        unsigned long long my_before = 0;
+        if (tie_mode == 2) {
+            const unsigned long long n = (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+            unsigned long long total;
+            my_before = run + block_exclusive_scan(n, &total);
+            run += total;
         }
-        unsigned word = (~sel & 0xFu) << ((threadIdx.x & 7) * 4);
-        word |= __shfl_xor(word, 1, 64);
-        word |= __shfl_xor(word, 2, 64);
-        word |= __shfl_xor(word, 4, 64);
-        const long long w = v >> 3;    // 8 lanes x 4 keys = one 32-bit word
-        if ((threadIdx.x & 7) == 0 && w < n_words)
-            bitmap[w] = word;
+#pragma unroll
+        for (int j = 0; j < kVec; ++j) {
+            const unsigned x = k[j];
+            bool s = x < T;
+            if (x == T) {
+                if (tie_mode == 1)
+                    s = true;
+                else if (tie_mode == 2) {
+                    s = my_before < r;
+                    ++my_before;
+                }
+            }
+            sel |= (s ? 1u : 0u) << j;
+        }
+        store_bitmap_word(sel, v, n_words, bitmap);
     }
 }
 

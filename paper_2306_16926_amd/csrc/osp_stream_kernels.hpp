@@ -50,7 +50,8 @@ struct Piece {                         // the chunk one workgroup owns
     int chunk;
 };
 
-// Workgroup b owns chunk (b % 64) of span (b / 64); false if the span is shorter.
+// Launches over the table of all spans: workgroup b owns chunk (b % 64) of span (b / 64);
+// false if the span is shorter.
 __device__ __forceinline__ bool owned_piece(const Span *__restrict__ spans, int chunk_elems,
                                             Piece &p)
 {
@@ -64,6 +65,52 @@ __device__ __forceinline__ bool owned_piece(const Span *__restrict__ spans, int 
     p.chunk = s.chunk_base + j;
     return true;
 }
+
+// Group g of a launch is chunk (g % 64) of span (g / 64) of the launch's table.  A stage table
+// (layer-granular GIB) is written on the device by the split, and no launch over it waits for
+// its length to reach the host: every table has room for all spans, the entries behind the
+// stage's last span are cleared (n_elems == 0), and a workgroup walks groups blockIdx.x,
+// blockIdx.x + gridDim.x, ... until it meets a cleared entry or the table's capacity.  The host
+// sizes the grid from the last length it has seen; when that was right every workgroup owns
+// exactly one group, when it was too small some own a second one, when it was too large the
+// surplus workgroups return at once.  The grid never exceeds 64 * capacity.
+struct GroupWalk {
+    const Span *spans;
+    Span s;                            // entry of group g
+    unsigned g, cap_groups;
+    int chunk_elems;
+
+    __device__ __forceinline__ GroupWalk(const Span *__restrict__ table, unsigned cap_spans, int chunk)
+        : spans(table), chunk_elems(chunk)
+    {
+        g = blockIdx.x;
+        cap_groups = cap_spans * kSpanChunks;
+        s = table[g / kSpanChunks];
+    }
+
+    // The next chunk this workgroup owns; false when there is none.
+    __device__ __forceinline__ bool next(Piece &p)
+    {
+        while (s.n_elems != 0) {
+            const int j = g % kSpanChunks;
+            const int off = j * chunk_elems;
+            const bool ok = off < s.n_elems;      // (false: the span is shorter than 64 chunks)
+            if (ok) {
+                p.start = s.start + off;
+                p.len = s.n_elems - off < chunk_elems ? s.n_elems - off : chunk_elems;
+                p.chunk = s.chunk_base + j;
+            }
+            g += gridDim.x;
+            if (g < cap_groups)
+                s = spans[g / kSpanChunks];
+            else
+                s.n_elems = 0;
+            if (ok)
+                return true;
+        }
+        return false;
+    }
+};
 
 using f4 = __attribute__((ext_vector_type(4))) float;
 using u4 = __attribute__((ext_vector_type(4))) unsigned int;
@@ -205,8 +252,11 @@ __device__ __forceinline__ double masked_sum(unsigned m, f4 q)
 // ---------------------------------------------------------------------------
 // PS aggregate + update (+ PGP importance), one stage.
 // ---------------------------------------------------------------------------
+// (The span table of a launch is a kernel parameter of its own, declared restrict: the
+// walkers read it inside their loops, behind the kernel's stores, and only a table that
+// provably none of these stores can touch is read through the scalar path.)
 struct AggArgs {
-    const Span *spans;                 // one per 64 workgroups
+    unsigned cap_spans;                // entries the table has room for (see GroupWalk)
     int chunk_elems;
     const uint32_t *bitmap;            // bit per element (element-granular GIB), when MASKED
     float *P;
@@ -252,11 +302,11 @@ __device__ __forceinline__ void add_workers(f4 &acc, int w0, const GT *__restric
 constexpr int kWorkerBlock = 16;       // most gradient streams in flight per lane
 
 template <bool MASKED, bool WEIGHTED, bool KEYS, typename GT = float>
-__global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
+__global__ __launch_bounds__(kBlock) void k_aggregate_update(const Span *__restrict__ table, const AggArgs a)
 {
+    GroupWalk walk(table, a.cap_spans, a.chunk_elems);
     Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
-        return;
+    while (walk.next(c)) {
     const int N = a.n_workers;
     // uniform bases of this chunk in every stream
     float *Pc = a.P + c.start;
@@ -348,6 +398,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
         if (threadIdx.x == 0)
             a.partial_other[c.chunk] = total_other;
     }
+    }
 }
 
 // Stage 2 of an iteration whose aggregate is already in the stash (left there by an
@@ -355,7 +406,7 @@ __global__ __launch_bounds__(kBlock) void k_aggregate_update(const AggArgs a)
 // P = P - lr V on the stage-2 elements; their keys and importance were written with it.
 // MASKED: element-granular GIB over all spans; otherwise the stage-2 span table.
 struct StashArgs {
-    const Span *spans;
+    unsigned cap_spans;                // entries the table has room for
     int chunk_elems;
     const uint32_t *bitmap;
     float *P;
@@ -365,11 +416,11 @@ struct StashArgs {
 };
 
 template <bool MASKED>
-__global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
+__global__ __launch_bounds__(kBlock) void k_update_from_stash(const Span *__restrict__ table, const StashArgs a)
 {
+    GroupWalk walk(table, a.cap_spans, a.chunk_elems);
     Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
-        return;
+    while (walk.next(c)) {
     float *Pc = a.P + c.start;
     float *Vc = a.V + c.start;
     const float *Sc = a.stash + c.start;
@@ -395,6 +446,7 @@ __global__ __launch_bounds__(kBlock) void k_update_from_stash(const StashArgs a)
                 }
         }
     }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -416,12 +468,11 @@ constexpr int kApplyBlock = 256;
 constexpr int kPiece = kApplyBlock * kVec;     // elements per workgroup
 
 struct ApplyArgs {
-    const Span *spans;
     const uint32_t *bitmap;
     const float *P;
     float *Pw;
     long long param_stride;
-    unsigned n_spans;
+    unsigned cap_spans;                // entries the table has room for (all spans)
     unsigned pieces_per_span;          // 64 * chunk_elems / (T * kPiece)
     int pieces_shift;                  // log2(pieces_per_span) if it is a power of two, else -1
     unsigned spans_per_block;
@@ -432,29 +483,55 @@ struct ApplyArgs {
 // fastest), so the kernel needs no division to find its place.  A workgroup lives about as
 // long as two dependent cache hits (its span entry, then its parameters): each lane moves T
 // float4, T * 4 KiB per workgroup, to keep enough bytes in flight over that latency.
+// As in GroupWalk the table ends at its first cleared entry: a workgroup owns its piece of
+// blocks blockIdx.z, blockIdx.z + gridDim.z, ... (one block each when the host sized the grid
+// from the right length).
 template <int T>
-__device__ __forceinline__ bool sweep_piece(const Span *__restrict__ spans, unsigned n_spans,
-                                            unsigned spans_per_block, unsigned pieces_per_span,
-                                            int pieces_shift, Span &s, int &off0)
-{
-    const unsigned q = blockIdx.x;
-    const unsigned sp = pieces_shift >= 0 ? q >> pieces_shift : q / pieces_per_span;
-    const unsigned si = blockIdx.z * spans_per_block + sp;
-    if (si >= n_spans)
+struct SweepWalk {
+    const Span *spans;
+    Span s;
+    unsigned si, cap_spans, stride_spans;
+    int off0;                          // the lane's first element inside its span
+
+    __device__ __forceinline__ SweepWalk(const Span *__restrict__ table, unsigned cap,
+                                         unsigned spb, unsigned pieces_per_span, int pieces_shift)
+        : spans(table), cap_spans(cap)
+    {
+        const unsigned q = blockIdx.x;
+        const unsigned sp = pieces_shift >= 0 ? q >> pieces_shift : q / pieces_per_span;
+        off0 = (int)(q - sp * pieces_per_span) * (kPiece * T) + (int)threadIdx.x * kVec;
+        si = blockIdx.z * spb + sp;
+        stride_spans = gridDim.z * spb;
+        s.n_elems = 0;
+        if (si < cap)
+            s = table[si];
+    }
+
+    // The span of the next block this workgroup has a piece in; false when there is none.
+    __device__ __forceinline__ bool next(Span &out)
+    {
+        while (s.n_elems != 0) {
+            out = s;
+            const bool ok = off0 < s.n_elems;
+            si += stride_spans;
+            if (si < cap_spans)
+                s = spans[si];
+            else
+                s.n_elems = 0;
+            if (ok)
+                return true;
+        }
         return false;
-    s = spans[si];
-    off0 = (int)(q - sp * pieces_per_span) * (kPiece * T) + (int)threadIdx.x * kVec;
-    return off0 < s.n_elems;
-}
+    }
+};
 
 template <bool MASKED, int T>
-__global__ __launch_bounds__(kApplyBlock) void k_apply_stage_sweep(const ApplyArgs a)
+__global__ __launch_bounds__(kApplyBlock) void k_apply_stage_sweep(const Span *__restrict__ table, const ApplyArgs a)
 {
+    SweepWalk<T> walk(table, a.cap_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift);
+    const int off0 = walk.off0;
     Span s;
-    int off0;
-    if (!sweep_piece<T>(a.spans, a.n_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift,
-                        s, off0))
-        return;
+    while (walk.next(s)) {
     const float *src = a.P + s.start;
     float *dst = a.Pw + (long long)blockIdx.y * a.param_stride + s.start;
     f4 p[T];
@@ -482,10 +559,11 @@ __global__ __launch_bounds__(kApplyBlock) void k_apply_stage_sweep(const ApplyAr
                     dst[off + j] = p[t][j];
         }
     }
+    }
 }
 
 struct FanoutArgs {
-    const Span *spans;
+    unsigned cap_spans;                // entries the table has room for
     int chunk_elems;
     const uint32_t *bitmap;
     const float *P;
@@ -496,11 +574,11 @@ struct FanoutArgs {
 };
 
 template <bool MASKED>
-__global__ __launch_bounds__(kBlock) void k_apply_stage_fanout(const FanoutArgs a)
+__global__ __launch_bounds__(kBlock) void k_apply_stage_fanout(const Span *__restrict__ table, const FanoutArgs a)
 {
+    GroupWalk walk(table, a.cap_spans, a.chunk_elems);
     Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
-        return;
+    while (walk.next(c)) {
     const int N = a.n_workers;
     const float *Pc = a.P + c.start;
     float *Wc = a.Pw + c.start;
@@ -531,13 +609,14 @@ __global__ __launch_bounds__(kBlock) void k_apply_stage_fanout(const FanoutArgs 
                         Wc[(long long)w * a.param_stride + i + j] = p[j];
         }
     }
+    }
 }
 
 // ---------------------------------------------------------------------------
 // LGP: stage-2 parameters of every replica advance by the local gradient.
 // ---------------------------------------------------------------------------
-struct LgpArgs {
-    const Span *spans;                 // stage-2 spans, or all spans (MASKED)
+struct LgpArgs {                       // (table: stage-2 spans, or all spans when MASKED)
+    unsigned cap_spans;                // entries the table has room for
     int chunk_elems;
     const uint32_t *bitmap;
     float *Pw;
@@ -550,11 +629,11 @@ struct LgpArgs {
 // grid = (chunks of stage 2, workers): one workgroup moves one chunk of ONE
 // replica, so the whole GPU sweeps one worker's arena at a time (three streams).
 template <bool MASKED, typename GT = float>
-__global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
+__global__ __launch_bounds__(kBlock) void k_lgp_correct(const Span *__restrict__ table, const LgpArgs a)
 {
+    GroupWalk walk(table, a.cap_spans, a.chunk_elems);
     Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
-        return;
+    while (walk.next(c)) {
     const long long w = blockIdx.y;
     float *pw = a.Pw + w * a.param_stride + c.start;
     const GT *gw = static_cast<const GT *>(a.grads) + w * a.worker_stride + c.start;
@@ -575,6 +654,7 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
                     pw[i + t] = pn[t];
         }
     }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -587,8 +667,8 @@ __global__ __launch_bounds__(kBlock) void k_lgp_correct(const LgpArgs a)
 // importance and keys in the workspace.  The stage-2 call on the same gradient
 // arenas then needs one stream instead of N (k_update_from_stash).
 // ---------------------------------------------------------------------------
-struct LgpKeepArgs {
-    const Span *spans;                 // stage-2 span table
+struct LgpKeepArgs {                   // (table: stage-2 spans)
+    unsigned cap_spans;                // entries the table has room for
     int chunk_elems;
     const float *P;
     float *Pw;
@@ -647,11 +727,11 @@ __device__ __forceinline__ void lgp_and_add(f4 &acc, int w0, const GT *__restric
 constexpr int kKeepBlock = 16;         // workers whose gradients a lane holds at once (8: 4 % slower)
 
 template <bool WEIGHTED, bool KEYS, typename GT = float>
-__global__ __launch_bounds__(kBlock) void k_lgp_keep(const LgpKeepArgs a)
+__global__ __launch_bounds__(kBlock) void k_lgp_keep(const Span *__restrict__ table, const LgpKeepArgs a)
 {
+    GroupWalk walk(table, a.cap_spans, a.chunk_elems);
     Piece c;
-    if (!owned_piece(a.spans, a.chunk_elems, c))
-        return;
+    while (walk.next(c)) {
     const int N = a.n_workers;
     const float *Pc = a.P + c.start;
     float *Wc = a.Pw + c.start;
@@ -695,6 +775,7 @@ __global__ __launch_bounds__(kBlock) void k_lgp_keep(const LgpKeepArgs a)
     const double total = wave_sum(imp);
     if (threadIdx.x == 0)
         a.partial[c.chunk] = total;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -766,14 +847,13 @@ __global__ __launch_bounds__(kBlock) void k_stream_pattern(const PatternArgs a)
 // the group is written whole as "P, minus lr g on the stage-2 elements".
 // ---------------------------------------------------------------------------
 struct LgpSweepArgs {
-    const Span *spans;
     const uint32_t *bitmap;
     const float *P;
     float *Pw;
     long long param_stride;
     const void *grads;                 // fp32 or bfloat16 arenas (template parameter GT)
     long long worker_stride;
-    unsigned n_spans;
+    unsigned cap_spans;                // entries the table has room for (all spans)
     unsigned pieces_per_span;
     int pieces_shift;
     unsigned spans_per_block;
@@ -781,13 +861,12 @@ struct LgpSweepArgs {
 };
 
 template <bool MASKED, typename GT, int T>
-__global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
+__global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const Span *__restrict__ table, const LgpSweepArgs a)
 {
+    SweepWalk<T> walk(table, a.cap_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift);
+    const int off0 = walk.off0;
     Span s;
-    int off0;
-    if (!sweep_piece<T>(a.spans, a.n_spans, a.spans_per_block, a.pieces_per_span, a.pieces_shift,
-                        s, off0))
-        return;
+    while (walk.next(s)) {
     const long long w = blockIdx.y;
     const float *src = a.P + s.start;
     const GT *grad = static_cast<const GT *>(a.grads) + w * a.worker_stride + s.start;
@@ -820,6 +899,7 @@ __global__ __launch_bounds__(kApplyBlock) void k_lgp_sweep(const LgpSweepArgs a)
                 if (m & (1u << j))
                     dst[off + j] = pn[j];
         }
+    }
     }
 }
 

@@ -239,12 +239,12 @@ __global__ __launch_bounds__(kBlock) void k_ics_window_element(const IcsElementA
 // ---------------------------------------------------------------------------
 struct WindowLayerArgs {
     const Span *agg_spans;             // span table of the window's stage
-    unsigned n_agg_groups;             // workgroups of the first kind, unless n_agg_spans is given
-    const int *n_agg_spans;            // device: length of agg_spans, or null.  Lets the RS window
-                                       // be enqueued right behind a split whose table lengths the
-                                       // host does not know yet (the launch covers both tables,
-                                       // whose lengths add up to the number of all spans)
-    const Span *lgp_spans;             // stage-2 span table (RS window)
+    const int *n_agg_spans;            // device: length of agg_spans.  The launch covers as many
+                                       // groups as all spans have, so a window is enqueued right
+                                       // behind a split whose table lengths the host does not
+                                       // know yet (RS window: both tables, whose lengths add up
+                                       // to the number of all spans)
+    const Span *lgp_spans;             // stage-2 span table (RS window), or null (ICS window)
     int chunk_elems;
     float *P;
     float *V;
@@ -279,7 +279,7 @@ template <bool WEIGHTED, bool KEYS, typename GT = float>
 __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a)
 {
     const int N = a.n_workers;
-    const unsigned n_agg = a.n_agg_spans ? (unsigned)*a.n_agg_spans * kSpanChunks : a.n_agg_groups;
+    const unsigned n_agg = (unsigned)*a.n_agg_spans * kSpanChunks;
     Piece c;
     if (blockIdx.x < n_agg) {
         if (!piece_at(a.agg_spans, a.chunk_elems, blockIdx.x, c))
@@ -334,7 +334,7 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
         if (threadIdx.x == 0)
             a.partial[c.chunk] = total;
     } else {
-        if (!piece_at(a.lgp_spans, a.chunk_elems, blockIdx.x - n_agg, c))
+        if (!a.lgp_spans || !piece_at(a.lgp_spans, a.chunk_elems, blockIdx.x - n_agg, c))
             return;
         const float *Pc = a.P + c.start;
         float *Wc = a.Pw + c.start;

@@ -38,24 +38,6 @@ def stage2_mask_from_bits(bits, numel, offset, arena):
     return (b == 0) & real_mask(numel, offset, arena)
 
 
-def select_element_bits(keys, real, k, arena):
-    """The element partition by its plain definition, from given keys, for sizes where a full
-    sort takes too long: stage 2 = the first k real elements in the order (key, arena index).
-    T = the k-th smallest key; every key below T is in; of the keys equal to T the first
-    k - (number below) in index order are.  Returns the bitmap (1 = important, padding 1)."""
-    words = (arena + 31) // 32
-    s2 = np.zeros(words * 32, bool)
-    if k > 0:
-        T = np.partition(keys[real], k - 1)[k - 1]
-        below = real & (keys < T)
-        r = k - int(below.sum())
-        ties = np.nonzero(real & (keys == T))[0]
-        assert 1 <= r <= ties.size
-        s2[:arena] = below
-        s2[ties[:r]] = True
-    return np.packbits(~s2, bitorder="little").view(np.uint32).copy()
-
-
 def aggregate(grads, weights=None):
     """Sequential fp32 sum over workers in ascending index (Sec. 2.1.1)."""
     n = grads.shape[0]

@@ -171,6 +171,9 @@ def test_newer_entry_points_validate_before_touching_anything():
         (lambda: c.osp_lgp_correct_bf16(8, 16, stream=0), B.OSP_ERR_INVALID_ARG),      # stride < arena
         (lambda: c.osp_lgp_correct_bf16(8, 20, stream=0), B.OSP_ERR_BAD_STATE),
         (lambda: c.osp_n_stage2(), B.OSP_ERR_BAD_STATE),                               # no GIB
+        (lambda: c.osp_set_stage2_log(16, 0, stream=0), B.OSP_ERR_INVALID_ARG),        # no room
+        (lambda: c.osp_set_stage2_log(20, 4, stream=0), B.OSP_ERR_INVALID_ARG),        # alignment
+        (lambda: c.osp_set_stage2_log(16, 4, stream=0), B.OSP_ERR_BAD_STATE),          # not bound
         (lambda: c.osp_rs_window_bf16(12, 20, stream=0), B.OSP_ERR_INVALID_ARG),       # 8-byte alignment
         (lambda: c.osp_rs_window_bf16(8, 20, stream=0), B.OSP_ERR_BAD_STATE),
         (lambda: c.osp_ics_window_bf16(8, 20, 0, 5, stream=0), B.OSP_ERR_BAD_STATE),

@@ -35,19 +35,32 @@ def test_bf16_gradients_halve_only_the_gradient_reads():
     assert sum(f32[n] - b16[n] for n in SIX) == 2 * N * M + 2 * N * E2
 
 
-def test_bytes_not_moved_are_itemised():
+def test_bytes_moved_are_itemised():
     """LGP that keeps the stage-2 aggregate: N grads + P read, N replicas + aggregate written;
-    stage 2 then reads P, V, aggregate and writes P, V."""
-    N, E2 = 16, 1000
-    b = bench.step_bytes(N, 4000, E2, element=False)
-    moved = 4 * (N + 1) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
-    assert b["lgp"] + b["agg2"] - bench.bytes_not_moved(N, E2, 4, True, True) == moved
-    assert bench.bytes_not_moved(N, E2, 4, True, False) == 4 * (N - 1) * E2
-    assert bench.bytes_not_moved(N, E2, 4, False, False) == 0
+    stage 2 then reads P, V, aggregate and writes P, V.  Never more than the metric credits."""
+    N, M, E2 = 16, 4000, 1000
+    b = bench.step_bytes(N, M, E2, element=False)
+    kept = bench.moved_bytes(N, M, E2, False, 4, True, True, False, False)
+    assert kept["lgp"] + kept["agg2"] == 4 * (N + 1) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
+    shared = bench.moved_bytes(N, M, E2, False, 4, True, False, False, False)
+    assert b["lgp"] - shared["lgp"] == 4 * (N - 1) * E2 and shared["agg2"] == b["agg2"]
+    plain = bench.moved_bytes(N, M, E2, False, 4, False, False, False, False)
+    for n in SIX:
+        assert plain[n] == b[n]
+        assert kept[n] <= b[n] and shared[n] <= b[n]
+    assert plain["rs_window"] == b["rs_window"] and plain["ics_window"] == b["ics_window"]
     # bfloat16 arenas: gradients are 2 bytes
-    b2 = bench.step_bytes(N, 4000, E2, element=False, gb=2)
-    moved2 = (2 * N + 4) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
-    assert b2["lgp"] + b2["agg2"] - bench.bytes_not_moved(N, E2, 2, True, True) == moved2
+    kept2 = bench.moved_bytes(N, M, E2, False, 2, True, True, False, False)
+    assert kept2["lgp"] + kept2["agg2"] == (2 * N + 4) * E2 + 4 * (N + 1) * E2 + 12 * E2 + 8 * E2
+
+
+def test_element_windows_move_one_pass_each():
+    """Fused element-granular RS window: N gradients, P, V and the bitmap read; P, V, keys, the
+    kept aggregate and N replicas written; all over whole arenas."""
+    N, M, E2 = 16, 3200, 1600
+    mv = bench.moved_bytes(N, M, E2, True, 4, True, False, True, False)
+    assert mv["rs_window"] == (4 * N + 8) * M + M // 8 + (16 + 4 * N) * M
+    assert mv["ics_window"] == (20 * M + M // 8) + 4 * (N + 1) * M + (16 * M + M // 8)
 
 
 def test_more_than_one_gpu_is_refused_with_a_message():

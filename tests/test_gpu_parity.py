@@ -151,7 +151,8 @@ def full_size_element(name):
     bitmap the iteration before produced.  After every iteration: P, V and every replica
     element by element, the keys bit-exact, the bitmap bit-exact.  The expected bitmap of the
     first iteration is the oracle's own split (a full sort); the later ones are built from the
-    oracle's keys by selection (brute.select_element_bits), which a CPU test pins to that sort."""
+    oracle's keys by selection (OracleOSP.split_element_by_selection), which a CPU test pins to
+    that sort."""
     from paper_2306_16926_amd.device import DeviceJob
     wl = W.get(name)
     stride, arena = wl.worker_stride(), wl.arena_elems()
@@ -174,7 +175,7 @@ def full_size_element(name):
             say("   ", tag, "oracle split (full sort)")
             o.split(GRAN_ELEMENT, k)
         else:
-            o.set_gib(GRAN_ELEMENT, brute.select_element_bits(okeys, real, k, arena))
+            o.split_element_by_selection(k)
         _, bits, n2 = c.osp_get_gib()
         assert n2 == k == o.n_stage2
         assert np.array_equal(bits, o.gib_bits), tag + " element bitmap"

@@ -167,6 +167,178 @@ def test_two_streams_with_events(gran):
 
 
 # --------------------------------------------------------------------------
+# no staged call waits for the GPU: whole layer-granular iterations are enqueued while the
+# stream is still busy with earlier work (Sec. 3.1: the ICS of iteration t runs under the
+# compute of iteration t+1, so the host must be able to enqueue RS(t+1) behind it)
+# --------------------------------------------------------------------------
+
+def scaled_grads(wl, step, scales_seed, align=None):
+    """The workload's gradients with every tensor multiplied by its own power of two, redrawn
+    per step: the layer ranking, hence the lengths of the two stage tables, changes from one
+    iteration to the next."""
+    g = wl.make_grads(0, step, align, threads=8)
+    rng = np.random.default_rng([scales_seed, step])
+    for a, n in zip(wl.offsets(align), wl.numel):
+        g[:, int(a):int(a) + int(n)] *= F(2.0) ** int(rng.integers(-6, 7))
+    return g
+
+
+def busy_kernel_ms(torch, ms):
+    """Enqueue about `ms` milliseconds of GPU work on the current stream; returns an event
+    recorded behind it."""
+    cycles = 2_000_000
+    torch.cuda._sleep(cycles)                          # warm-up and calibration
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record(); torch.cuda._sleep(cycles); b.record()
+    torch.cuda.synchronize()
+    per_ms = cycles / max(a.elapsed_time(b), 1e-3)
+    torch.cuda._sleep(int(per_ms * ms))
+    done = torch.cuda.Event()
+    done.record()
+    return done
+
+
+@pytest.mark.parametrize("calls", ["six", "windows"])
+@pytest.mark.parametrize("shape", ["tiny", "n16", "n8_many_tensors"])
+def test_layer_steps_are_enqueued_without_waiting(calls, shape):
+    import torch
+    say("no host wait", calls, shape)
+    if shape == "tiny":
+        wl = W.get("tiny")
+    elif shape == "n16":
+        wl = W.custom([70000, 33, 5000, 131072, 4099, 64, 20000, 90001], 16, 0.5, align=4,
+                      config_id=71)
+    else:
+        rng = np.random.default_rng(5)
+        wl = W.custom([int(x) for x in rng.integers(1, 40000, 150)], 8, 0.5, align=4, config_id=72)
+    o = make_oracle(wl)
+    job = device_job(wl)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    steps = 4
+    budgets = [int(f * wl.n_params) for f in (0.2, 0.7, 0.4, 0.5)]
+    grads = [scaled_grads(wl, step, 11) for step in range(steps)]
+    dev = [job.upload_grads(g) for g in grads]
+    log = torch.zeros(steps, dtype=torch.int64, device="cuda")
+    c.osp_set_stage2_log(log)
+    busy = busy_kernel_ms(torch, 400.0)
+    for step in range(steps):
+        gd = dev[step]; s_ = gd.shape[1]
+        if calls == "six":
+            job.sync_step(gd, GRAN_LAYER, budgets[step])
+        else:
+            job.sync_step_windows(gd, GRAN_LAYER, budgets[step])
+    still_busy = not busy.query()
+    torch.cuda.synchronize()
+    assert still_busy, "a call waited for the GPU (or the busy kernel was too short)"
+    sizes = []
+    for step in range(steps):
+        o.sync_step(grads[step], GRAN_LAYER, budgets[step])
+        sizes.append(o.n_stage2)
+    assert len(set(sizes)) > 1, sizes                  # the table lengths did change
+    assert [int(x) for x in log.cpu()] == sizes        # every iteration cut the layers as the oracle did
+    compare_state(job, o, "no host wait")
+    compare_gib(job, o, "no host wait")
+    assert c.osp_n_stage2() == o.n_stage2
+
+
+@pytest.mark.parametrize("calls", ["six", "windows"])
+@pytest.mark.parametrize("shape", ["tiny", "n16"])
+def test_layer_steps_replay_as_a_graph(calls, shape):
+    """A layer-granular iteration captured once and replayed: the launches read the lengths of
+    the stage tables on the device, so the captured grids stay valid when the split of one
+    replay cuts the layers differently from the one the graph was captured under."""
+    import torch
+    say("layer graph replay", calls, shape)
+    wl = (W.get("tiny") if shape == "tiny" else
+          W.custom([70000, 33, 5000, 131072, 4099, 64, 20000, 90001], 16, 0.5, align=4, config_id=71))
+    o = make_oracle(wl)
+    job = device_job(wl)
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    g = scaled_grads(wl, 0, 13)
+    static = job.upload_grads(g); s_ = static.shape[1]
+    step_fn = job.sync_step if calls == "six" else job.sync_step_windows
+    for step in range(2):                               # eager: reach a staged GIB
+        g = scaled_grads(wl, step, 13)
+        static.copy_(torch.from_numpy(g))
+        o.sync_step(g, GRAN_LAYER, wl.budget)
+        step_fn(static, GRAN_LAYER, wl.budget)
+    torch.cuda.synchronize()
+    compare_state(job, o, "before capture")
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):                       # capture runs nothing
+        step_fn(static, GRAN_LAYER, wl.budget)
+    sizes = []
+    for step in range(2, 7):
+        g = scaled_grads(wl, step, 13)
+        static.copy_(torch.from_numpy(g))               # eager work between the replays
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        o.sync_step(g, GRAN_LAYER, wl.budget)
+        sizes.append(o.n_stage2)
+        compare_state(job, o, f"replay of step {step}")
+        compare_gib(job, o, f"replay of step {step}")
+    assert len(set(sizes)) > 1, sizes
+    # and eager again on top of the replays
+    g = scaled_grads(wl, 7, 13)
+    static.copy_(torch.from_numpy(g))
+    o.sync_step(g, GRAN_LAYER, wl.budget)
+    step_fn(static, GRAN_LAYER, wl.budget)
+    compare_state(job, o, "eager after replays")
+    compare_gib(job, o, "eager after replays")
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_stage2_log_round_robin(gran):
+    """osp_set_stage2_log: every split stores the size of the stage 2 it chose, round robin in
+    the caller's buffer, counted from the call; taking the log away stops it."""
+    import torch
+    say("stage-2 log", gran)
+    wl = W.get("tiny")
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=(gran == GRAN_ELEMENT))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    budgets = [int(f * wl.n_params) for f in (0.3, 0.0, 0.6, 0.1, 0.45)]
+    log = torch.full((3,), -1, dtype=torch.int64, device="cuda")
+    sizes = []
+    for step, b in enumerate(budgets):
+        if step == 1:
+            c.osp_set_stage2_log(log)                   # counting starts here
+        if step == 4:
+            c.osp_set_stage2_log(None)
+        g = scaled_grads(wl, step, 17)
+        gd = job.upload_grads(g)
+        sizes.append(o.sync_step(g, gran, b))
+        if step % 2:
+            job.sync_step_windows(gd, gran, b)
+        else:
+            job.sync_step(gd, gran, b)
+    torch.cuda.synchronize()
+    compare_gib(job, o, "log")
+    # splits 1, 2, 3 were logged at slots 0, 1, 2; split 4 was not
+    assert [int(x) for x in log.cpu()] == sizes[1:4]
+    # capacity 2: slot = count % 2
+    log2 = torch.full((2,), -1, dtype=torch.int64, device="cuda")
+    c.osp_set_stage2_log(log2)
+    for step in range(5, 8):
+        g = scaled_grads(wl, step, 17)
+        gd = job.upload_grads(g)
+        sizes.append(o.sync_step(g, gran, budgets[step - 4]))
+        job.sync_step(gd, gran, budgets[step - 4])
+    torch.cuda.synchronize()
+    assert [int(x) for x in log2.cpu()] == [sizes[7], sizes[6]]
+    with pytest.raises(Exception):
+        c.osp_set_stage2_log(log2, capacity=0)
+
+
+# --------------------------------------------------------------------------
 # random legal call sequences over every entry point that touches the state
 # --------------------------------------------------------------------------
 

@@ -488,9 +488,9 @@ def test_split_element_matches_bruteforce_tiny(frac):
 
 @pytest.mark.parametrize("frac", [0.0, 0.3, 1.0])
 @pytest.mark.parametrize("ties", [False, True])
-def test_selection_helper_equals_the_oracles_full_sort(frac, ties):
-    """brute.select_element_bits (selection on given keys; used as the expected bitmap where
-    the oracle's full sort takes too long) against the oracle's own split."""
+def test_split_by_selection_equals_the_full_sort(frac, ties):
+    """OracleOSP.split_element_by_selection (used where the full sort takes too long) against
+    split(), the definition."""
     wl = W.get("tiny")
     o = make_oracle(wl)
     g = wl.make_grads(0, 0)
@@ -500,12 +500,35 @@ def test_selection_helper_equals_the_oracles_full_sort(frac, ties):
     o.ps_aggregate_update(0, g)
     budget = int(frac * wl.n_params)
     real = brute.real_mask(wl.numel, wl.offsets(), wl.arena_elems())
-    keys = o.keys()
     if ties:
-        assert np.unique(keys[real]).size < 200
-    want = brute.select_element_bits(keys, real, budget, wl.arena_elems())
+        assert np.unique(o.keys()[real]).size < 200
+    assert o.split_element_by_selection(budget) == budget
+    got = o.gib_bits.copy()
     o.split(GRAN_ELEMENT, budget)
-    assert same(o.gib_bits, want)
+    assert same(got, o.gib_bits)
+    assert o.n_stage2 == budget
+
+
+def test_split_by_selection_adversarial():
+    """All keys equal, the cut inside a run of ties that crosses a bitmap word, NaN on top."""
+    wl = small_wl(2)
+    o = make_oracle(wl)
+    n = wl.n_params
+    for case in range(4):
+        q = np.zeros(o.arena, F)
+        real = brute.real_mask(o.numel, o.offset, o.arena)
+        vals = {0: np.ones(n, F), 1: np.zeros(n, F),
+                2: np.random.default_rng(1).integers(0, 3, n).astype(F),
+                3: np.random.default_rng(2).standard_normal(n).astype(F)}[case]
+        if case == 3:
+            vals[3] = np.nan; vals[n // 2] = np.inf
+        q[real] = np.abs(vals)
+        o.q[:] = q
+        for budget in (0, 1, n // 3, n - 1, n):
+            o.split_element_by_selection(budget)
+            got = o.gib_bits.copy()
+            o.split(GRAN_ELEMENT, budget)
+            assert same(got, o.gib_bits), (case, budget)
 
 
 def test_split_element_rejects_bad_budget():
