@@ -442,10 +442,10 @@ static void launch_lgp_keep(const osp_ctx *ctx, const Span *table, const LgpKeep
 }
 
 // The launches of one element-granular selection: `budget` smallest keys in the order
-// (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch: the split state
-// (tickets zero), hist = (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the
-// length of the candidate list; all zero on entry and left zero), the candidate list, the
-// per-tile tie counts.
+// (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch: the split state,
+// hist = (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the length of the
+// candidate list; all zero on entry and left zero), the candidate list, the per-tile tie
+// counts.
 struct SelectScratch {
     SplitState *state;
     unsigned long long *hist;
@@ -459,16 +459,24 @@ static void enqueue_element_select(const uint32_t *key, long long n_vec, long lo
 {
     unsigned long long *h0 = w.hist, *h1 = w.hist + kRadixBins, *h2 = w.hist + 2 * kRadixBins;
     unsigned int *n_cand = reinterpret_cast<unsigned int *>(w.hist + 3 * kRadixBins);
-    long long want = (n_vec + kSplitBlock - 1) / kSplitBlock;
-    const unsigned hgrid = (unsigned)(want < 1024 ? (want < 1 ? 1 : want) : 1024);
-    const unsigned tiles = (unsigned)n_tiles;
-    k_select_histogram<0><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h0);
-    k_select_histogram<1><<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h1);
-    k_select_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.cand, n_cand, bitmap);
-    k_select_finish<<<hgrid, kSplitBlock, 0, s>>>(key, n_vec, budget, w.state, h2, w.cand, n_cand, bitmap);
-    // (the last two return at once unless many keys share the threshold's upper 22 bits)
-    k_select_count_ties<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, w.state, w.tile_ties);
-    k_select_write_bitmap<<<tiles, kSplitBlock, 0, s>>>(key, n_vec, n_words, w.state, w.tile_ties, bitmap);
+    // histogram passes: few, large workgroups (see select_histogram)
+    const long long per_wg = (long long)kHistBlock * kHistVecPerThread;
+    long long want = (n_vec + per_wg - 1) / per_wg;
+    const unsigned hist_grid = (unsigned)(want < kHistMaxGrid ? (want < 1 ? 1 : want) : kHistMaxGrid);
+    // the tile passes walk their tiles in rounds of the grid: their prologue is paid per workgroup
+    const unsigned tgrid = (unsigned)(n_tiles < 8192 ? (n_tiles < 1 ? 1 : n_tiles) : 8192);
+    k_select_histogram0<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h0);
+    k_select_histogram1<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h0, h1);
+    k_select_bitmap<<<tgrid, kSplitBlock, 0, s>>>(key, n_vec, n_words, n_tiles, budget, w.state, h0, h1,
+                                                 w.cand, n_cand, bitmap);
+    k_select_finish<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h1, h2, w.cand, n_cand,
+                                                    bitmap);
+    // (the last two return at once unless many keys share the threshold's upper 22 bits:
+    // small grids, so that returning costs little)
+    const unsigned fgrid = tgrid < 1024 ? tgrid : 1024;
+    k_select_count_ties<<<fgrid, kSplitBlock, 0, s>>>(key, n_vec, n_tiles, budget, w.state, h2, w.tile_ties);
+    k_select_write_bitmap<<<fgrid, kSplitBlock, 0, s>>>(key, n_vec, n_words, n_tiles, budget, w.state, h2,
+                                                       w.tile_ties, bitmap);
 }
 
 // ---------------------------------------------------------------------------
@@ -1743,8 +1751,6 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
     const bool old_pending = ctx->counts_pending;
     if (granularity == OSP_GRAN_LAYER) {
         const int mode = ctx->single_pass ? 0 : (ctx->gib_gran == OSP_GRAN_LAYER ? 1 : 2);
-        k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
-            ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
         const int ns = (int)ctx->spans.size();
         // The new GIB's tables go into the other set, so that a launch over the old ones may
         // still follow.  A split captured into a graph stays on its set: every replay reads
@@ -1753,10 +1759,14 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
         if (!stream_is_capturing(s))
             ctx->tables ^= 1;
         if (ctx->n_tensors <= kRankTile) {
-            // one workgroup ranks in LDS and, unless the tables are long, fills them as well
+            // one launch: segment sums in every workgroup, then the last one ranks in LDS and,
+            // unless the tables are long, fills them as well
             const bool fill = ns <= kRankFillMaxSpans;
-            k_layer_rank_lds<kRankBlock><<<1, kRankBlock, 0, s>>>(
-                ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(), ctx->d_big(), (int)ctx->big_layers.size(),
+            const int n_seg = (int)ctx->segments.size();
+            constexpr int kPer = kRankBlock / kSplitBlock;
+            k_layer_split_lds<kRankBlock><<<(unsigned)((n_seg + kPer - 1) / kPer), kRankBlock, 0, s>>>(
+                ctx->d_segs(), n_seg, ctx->d_partial(0), ctx->d_partial(1), mode, ctx->d_segsum(),
+                ctx->n_tensors, ctx->d_lsb(), ctx->d_big(), (int)ctx->big_layers.size(),
                 ctx->d_imp(), ctx->d_numel(), ctx->d_lsp(), (long long)budget_elems, ctx->d_gib(),
                 ctx->d_order(), ctx->d_lbase(), ctx->d_state(), ctx->pinned_counts_dev, ++ctx->split_seq,
                 ctx->tables, fill ? ns : 0, ctx->d_spans(), ctx->d_slayer(), ctx->d_list(1),
@@ -1769,6 +1779,8 @@ osp_status osp_split(osp_ctx *ctx, int granularity, int64_t budget_elems, void *
                     return ls;
             }
         } else {
+            k_segment_importance<<<(unsigned)ctx->segments.size(), kSplitBlock, 0, s>>>(
+                ctx->d_segs(), ctx->d_partial(0), ctx->d_partial(1), ctx->d_gib(), mode, ctx->d_segsum());
             k_layer_rank<<<1, kRankBlock, 0, s>>>(ctx->n_tensors, ctx->d_segsum(), ctx->d_lsb(),
                                                   ctx->d_big(), (int)ctx->big_layers.size(),
                                                   ctx->d_imp(), ctx->d_numel(),

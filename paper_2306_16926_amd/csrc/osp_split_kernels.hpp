@@ -47,15 +47,16 @@ struct SplitState {                    // one per context, in the workspace
     long long n_stage2;                // elements in stage 2 under the current GIB
     int stage_spans[2][2];             // [table set][stage - 1]: spans in that set's stage table
                                        // (layer GIB; two sets of tables, written alternately)
-    unsigned long long k_rem;          // rank still to be found inside the current radix bucket
-    unsigned long long ties_to_take;   // r
-    unsigned int prefix;               // key bits decided so far (right-aligned)
+    // element split: what radix pass p decided (recorded by workgroup 0 of the launch after it)
+    unsigned long long k_rem[3];       // rank still to be found inside the bucket pass p chose
+    unsigned int prefix[3];            // key bits decided after pass p (right-aligned)
     unsigned int threshold;            // T
+    unsigned long long ties_to_take;   // r: how many of the keys equal to T go to stage 2
     unsigned int done;                 // 1: budget 0, nothing is selected
     unsigned int all_ties;             // 1: every key equal to T is taken
     unsigned int collect;              // 1: few keys share the threshold's 22-bit prefix; the bitmap
                                        // pass lists them and one workgroup decides among them
-    unsigned int tickets[3];           // workgroups that have finished radix pass 0, 1, 2
+    unsigned int layer_ticket;         // workgroups of k_layer_split_lds that have summed their segments
     long long *log;                    // caller's log of stage-2 sizes, or null (osp_set_stage2_log)
     long long log_cap;
     unsigned long long n_splits;       // splits since the log was set
@@ -85,6 +86,55 @@ struct TieCandidate {
     unsigned int pad;
 };
 constexpr unsigned kTieCandidates = 65536;    // capacity of the list
+
+// "Last workgroup done" without memory fences.  A fence at device scope writes back and
+// invalidates the whole L2 of the compute die on this GPU; a thousand workgroups doing that
+// cost more than the pass they belong to.  Instead everything that one workgroup hands to the
+// last one goes through device-scope atomics that RETURN a value: the value comes back once
+// the operation has been performed where every compute die sees it, so when a workgroup's
+// threads have all got their values back (wait_for) and passed the barrier, its ticket is drawn
+// after its data is in place; the workgroup that draws the last ticket then reads the data with
+// device-scope loads.  No workgroup waits for another.
+__device__ __forceinline__ void wait_for(unsigned long long returned)
+{   // the compiler may not drop or delay what produced `returned`
+    asm volatile("" ::"v"(returned) : "memory");
+}
+
+__device__ __forceinline__ unsigned long long load_device_scope(const unsigned long long *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+__device__ __forceinline__ double load_device_scope(const double *p)
+{
+    return __longlong_as_double((long long)__hip_atomic_load(
+        reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// Store one double where every compute die sees it; returns when it is there.
+__device__ __forceinline__ void store_device_scope(double *p, double x)
+{
+    wait_for(__hip_atomic_exchange(reinterpret_cast<unsigned long long *>(p),
+                                   (unsigned long long)__double_as_longlong(x), __ATOMIC_RELAXED,
+                                   __HIP_MEMORY_SCOPE_AGENT));
+}
+
+// True in exactly one workgroup of the launch: the one whose threads all get here last.  Every
+// thread must have waited (wait_for) for the device-scope atomics it wants the last workgroup
+// to see.  The ticket counter is left at zero.
+__device__ __forceinline__ bool last_workgroup(unsigned int *ticket)
+{
+    __shared__ bool last;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const unsigned t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        last = t == gridDim.x - 1;
+        if (last)
+            __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    return last;
+}
 
 // ---------------------------------------------------------------------------
 // layer granularity
@@ -320,10 +370,11 @@ __global__ __launch_bounds__(kRankBlock) void k_layer_rank(
 // arrays in LDS: a bitonic sort of (importance, index) pairs instead of the
 // all-pairs count, and no global round trip between the phases.  If n_spans > 0
 // the workgroup also fills the two stage tables (what k_stage_lists does), after
-// it has published their lengths.  (Measured with BLOCK = 256 for small L: 1 us
-// less at L = 62, 6 us more at L = 467; launched with kRankBlock throughout.)
+// it has published their lengths.  Run by one workgroup of BLOCK threads (the one
+// of k_layer_split_lds that finishes last).  (Measured with BLOCK = 256 for small
+// L: 1 us less at L = 62, 6 us more at L = 467; kRankBlock throughout.)
 template <int BLOCK>
-__global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
+__device__ __forceinline__ void layer_rank_in_lds(
     int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
     const int *__restrict__ big_layers, int n_big, double *__restrict__ imp,
     const long long *__restrict__ numel, const int *__restrict__ layer_span_begin, long long budget,
@@ -380,7 +431,7 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
         if (g1 - g0 <= kFewSegments) {
             double s = 0.0;
             for (int g = g0; g < g1; ++g)
-                s += seg_sum[g];
+                s += load_device_scope(&seg_sum[g]);   // (written by this launch)
             imp[l] = s;
             key[l] = importance_rank_key(s);
         }
@@ -390,7 +441,7 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
         const int g0 = layer_seg_begin[l], g1 = layer_seg_begin[l + 1];
         double s = 0.0;
         for (int g = g0 + lane; g < g1; g += 64)
-            s += seg_sum[g];
+            s += load_device_scope(&seg_sum[g]);   // (written by this launch)
         s = wave_sum(s);
         if (lane == 0) {
             imp[l] = s;
@@ -506,6 +557,62 @@ __global__ __launch_bounds__(BLOCK) void k_layer_rank_lds(
     }
 }
 
+// The whole layer-granular split in one launch for L <= kRankTile: every workgroup sums four
+// segments of per-chunk importance partials (each by 256 threads, in k_segment_importance's
+// order, so the sums are the same bit for bit), and the workgroup that finishes last ranks
+// the layers and writes the GIB and the stage tables.
+template <int BLOCK>
+__global__ __launch_bounds__(BLOCK) void k_layer_split_lds(
+    const Segment *__restrict__ segs, int n_segments, const double *__restrict__ partial_s1,
+    const double *__restrict__ partial_s2, int mode, double *__restrict__ seg_sum,
+    int L, const int *__restrict__ layer_seg_begin, const int *__restrict__ big_layers, int n_big,
+    double *__restrict__ imp, const long long *__restrict__ numel,
+    const int *__restrict__ layer_span_begin, long long budget, uint8_t *__restrict__ gib_layer,
+    int *__restrict__ order, int *__restrict__ layer_base, SplitState *__restrict__ st,
+    StageCounts *__restrict__ counts_out, unsigned seq, int set, int n_spans,
+    const Span *__restrict__ spans, const int *__restrict__ span_layer,
+    Span *__restrict__ list_s1, Span *__restrict__ list_s2)
+{
+    static_assert(BLOCK % kSplitBlock == 0, "whole segments per workgroup");
+    constexpr int kPer = BLOCK / kSplitBlock;              // segments per workgroup
+    __shared__ double wave_part[BLOCK / 64];
+    {
+        const int quarter = threadIdx.x / kSplitBlock, t = threadIdx.x % kSplitBlock;
+        const int g = blockIdx.x * kPer + quarter;
+        double x = 0.0;
+        if (g < n_segments) {
+            const Segment sg = segs[g];
+            const double *src = partial_s1;
+            if (mode == 1 && gib_layer[sg.layer] == 0)
+                src = partial_s2;
+            for (int c = sg.begin + t; c < sg.end; c += kSplitBlock) {
+                double v = src[c];
+                if (mode == 2)
+                    v += partial_s2[c];
+                x += v;
+            }
+        }
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1)
+            x += __shfl_down(x, off, 64);
+        if ((threadIdx.x & 63) == 0)
+            wave_part[threadIdx.x >> 6] = x;
+        __syncthreads();
+        if (t == 0 && g < n_segments) {
+            double total = 0.0;
+#pragma unroll
+            for (int i = 0; i < kSplitBlock / 64; ++i)
+                total += wave_part[quarter * (kSplitBlock / 64) + i];
+            store_device_scope(&seg_sum[g], total);
+        }
+    }
+    if (!last_workgroup(&st->layer_ticket))
+        return;
+    layer_rank_in_lds<BLOCK>(L, seg_sum, layer_seg_begin, big_layers, n_big, imp, numel,
+                             layer_span_begin, budget, gib_layer, order, layer_base, st, counts_out,
+                             seq, set, n_spans, spans, span_layer, list_s1, list_s2);
+}
+
 // After a GIB was uploaded from the host: only the table bases are needed.
 __global__ void k_stage_bases(int L, const uint8_t *__restrict__ gib_layer,
                               const int *__restrict__ layer_span_begin,
@@ -560,20 +667,22 @@ __global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
 //
 // Exact selection of the `budget` smallest 32-bit keys, ties broken by arena index, in six
 // launches and three passes over the keys:
-//   1. histogram of the top 11 bits; the workgroup that finishes last finds the bucket of the
-//      budget-th smallest key;
-//   2. histogram of the next 11 bits inside that bucket; its last workgroup finds the 22-bit
-//      prefix P of the threshold and how many keys share it;
-//   3. bitmap pass: a key whose upper 22 bits are below P goes to stage 2, above P to stage 1;
-//      the (few) keys with exactly P are listed as candidates and left in stage 1 for now;
+//   1. histogram of the top 11 bits;
+//   2. histogram of the next 11 bits inside the bucket of the budget-th smallest key;
+//   3. bitmap pass: with P = the upper 22 bits of the threshold, a key whose upper 22 bits are
+//      below P goes to stage 2, above P to stage 1; the (few) keys with exactly P are listed as
+//      candidates and left in stage 1 for now;
 //   4. one workgroup picks, among the candidates, the ones that still belong to stage 2 (by
 //      their low 10 bits, then by arena index) and clears their bits.
 // When more than kTieCandidates keys share P (long runs of equal keys: zeros, quantised
 // gradients) launch 4 is instead the histogram of the last 10 bits over all keys, and two more
 // launches count the ties per tile and write the bitmap again.  Those two launches are always
 // enqueued and return at once when not needed, so the host never has to know.
-// Integer arithmetic only.  The histograms and counters are left zeroed by the workgroups that
-// consume them, ready for the next split.
+// Which bucket a finished histogram puts the budget-th smallest key in is worked out by every
+// workgroup of the NEXT launch for itself (16 KB of counts from L2 and one scan: a few
+// microseconds, no launch of its own, no workgroup waiting for another); workgroup 0 also
+// records it for the launches after that.  A histogram is left zeroed by the launch after the
+// one that read it.  Integer arithmetic only.
 // ---------------------------------------------------------------------------
 constexpr int kRadixBins = 2048;
 // pass 0: bits 31..21, pass 1: bits 20..10, pass 2: bits 9..0
@@ -619,7 +728,7 @@ __device__ __forceinline__ unsigned long long block_exclusive_scan(unsigned long
 // spread over the workgroup, PER consecutive bins per thread: the unique bin with
 // below < want <= below + count.  Every thread gets the answer; bin < 0 if want exceeds the
 // total.  All threads of the workgroup must call it.
-template <int PER>
+template <int PER, int BLOCK = kSplitBlock>
 __device__ __forceinline__ void find_rank_bin(const unsigned long long (&c)[PER],
                                               unsigned long long want, int &bin,
                                               unsigned long long &below, unsigned long long &count)
@@ -632,7 +741,8 @@ __device__ __forceinline__ void find_rank_bin(const unsigned long long (&c)[PER]
         mine += c[j];
     if (threadIdx.x == 0)
         s_bin = -1;
-    const unsigned long long before = block_exclusive_scan(mine, nullptr);   // (barriers inside)
+    const unsigned long long before =
+        block_scan_exclusive<BLOCK, unsigned long long>(mine, nullptr);       // (barriers inside)
     if (before < want && want <= before + mine) {
         unsigned long long run = before;
 #pragma unroll
@@ -652,113 +762,89 @@ __device__ __forceinline__ void find_rank_bin(const unsigned long long (&c)[PER]
     __syncthreads();                   // the shared slots are free for the next call
 }
 
-// True in exactly one workgroup of the launch: the one whose threads all get here last.  What
-// every workgroup wrote (with device-scope atomics) before the call is visible to that one
-// afterwards through device-scope loads.  The ticket counter is left at zero.
-__device__ __forceinline__ bool last_workgroup(unsigned int *ticket)
-{
-    __shared__ bool last;
-    __threadfence();
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        const unsigned t = atomicAdd(ticket, 1u);
-        last = t == gridDim.x - 1;
-        if (last)
-            *ticket = 0;
-    }
-    __syncthreads();
-    if (last)
-        __threadfence();
-    return last;
-}
+// What radix pass PASS has decided, worked out by a whole workgroup from that pass's finished
+// histogram (written by an earlier launch) and from what the pass before it recorded.
+struct Picked {
+    unsigned prefix;                   // key bits decided so far, right-aligned
+    unsigned long long k_rem;          // rank of the wanted key inside the chosen bucket, >= 1
+    unsigned long long count;          // keys in the chosen bucket
+    bool ok;                           // false: budget beyond the number of keys (cannot happen)
+};
 
-__device__ __forceinline__ unsigned long long load_device_scope(const unsigned long long *p)
+template <int PASS, int BLOCK = kSplitBlock>
+__device__ __forceinline__ Picked pick_bucket(long long budget,
+                                              const unsigned long long *__restrict__ hist,
+                                              const SplitState *__restrict__ st)
 {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-
-// One workgroup, after the histogram of radix pass PASS is complete: find the bucket of the
-// k-th smallest key and record it; the histogram is read through device-scope loads and left
-// zeroed.
-template <int PASS>
-__device__ __forceinline__ void select_pick(long long budget, unsigned long long *__restrict__ hist,
-                                            SplitState *__restrict__ st)
-{
-    constexpr int per = kRadixBins / kSplitBlock;          // 8 consecutive bins per thread
+    constexpr int per = kRadixBins / BLOCK;                // consecutive bins per thread
     unsigned long long c[per];
 #pragma unroll
-    for (int j = 0; j < per; ++j) {
-        c[j] = load_device_scope(&hist[threadIdx.x * per + j]);
-        hist[threadIdx.x * per + j] = 0;
-    }
-    if (PASS == 0 && threadIdx.x == 0) {
-        st->done = budget == 0 ? 1u : 0u;
-        st->n_stage2 = budget;
-        log_stage2(st, budget);
-    }
-    const unsigned long long k = PASS == 0 ? (unsigned long long)budget : st->k_rem;
-    if (PASS == 0 && budget == 0) {    // nothing is selected (later launches see st->done)
-        if (threadIdx.x == 0) {
-            st->threshold = 0;
-            st->ties_to_take = 0;
-            st->prefix = 0;
-            st->k_rem = 0;
-            st->all_ties = 0;
-            st->collect = 0;
-        }
-        return;
-    }
+    for (int j = 0; j < per; ++j)
+        c[j] = hist[threadIdx.x * per + j];
+    const unsigned long long k = PASS == 0 ? (unsigned long long)budget : st->k_rem[PASS - 1];
+    const unsigned prefix = PASS == 0 ? 0u : st->prefix[PASS - 1];
     int bin;
     unsigned long long below, count;
-    find_rank_bin<per>(c, k, bin, below, count);
-    if (threadIdx.x != 0)
+    find_rank_bin<per, BLOCK>(c, k, bin, below, count);
+    Picked r;
+    r.ok = bin >= 0;
+    r.prefix = (prefix << radix_bits(PASS)) | (unsigned)(bin < 0 ? 0 : bin);
+    r.k_rem = k - below;
+    r.count = count;
+    return r;
+}
+
+// Workgroup 0 leaves what a pass decided for the launches after the next one.
+template <int PASS>
+__device__ __forceinline__ void record_pick(SplitState *__restrict__ st, const Picked &r)
+{
+    if (blockIdx.x != 0 || threadIdx.x != 0)
         return;
-    if (bin < 0) {                     // cannot happen for budget <= number of keys
-        st->done = 1;
-        st->threshold = 0;
-        st->ties_to_take = 0;
-        st->all_ties = 0;
-        st->collect = 0;
-        return;
-    }
-    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
-    const unsigned np = (prefix << radix_bits(PASS)) | (unsigned)bin;
-    st->prefix = np;
-    st->k_rem = k - below;
-    if (PASS == 0)
-        st->collect = 0;
+    st->prefix[PASS] = r.prefix;
+    st->k_rem[PASS] = r.k_rem;
     if (PASS == 1)                     // few keys share the 22-bit prefix: the bitmap pass lists them
-        st->collect = count <= kTieCandidates ? 1u : 0u;
+        st->collect = r.ok && r.count <= kTieCandidates ? 1u : 0u;
     if (PASS == 2) {
-        st->threshold = np;
-        st->ties_to_take = k - below;
+        st->threshold = r.prefix;
+        st->ties_to_take = r.k_rem;
         // (distinct keys around the threshold: all keys equal to T are taken)
-        st->all_ties = (k - below == count) ? 1u : 0u;
+        st->all_ties = r.k_rem == r.count ? 1u : 0u;
     }
+}
+
+__device__ __forceinline__ void zero_histogram(unsigned long long *__restrict__ hist)
+{   // one workgroup, after the last launch that reads it
+    for (int b = threadIdx.x; b < kRadixBins; b += blockDim.x)
+        hist[b] = 0;
 }
 
 // Histogram of one radix digit over all keys (PASS 0), or over the keys whose higher bits
-// equal the prefix found so far; per-workgroup counts in LDS, flushed with one global atomic
-// per non-empty bin.  The last workgroup to finish picks the bucket (select_pick).
-template <int PASS>
+// equal `prefix`; per-workgroup counts in LDS, flushed with one global atomic per non-empty
+// bin (nobody waits for them: the next launch reads the sums).  The flush is what a pass over
+// few keys costs (the second digit fills nearly all 2048 bins of every workgroup, and the GPU
+// retires some 40 G such atomics per second), hence few workgroups of kHistBlock threads.
+constexpr int kHistBlock = 1024;
+constexpr int kHistVecPerThread = 16;  // 16-byte groups a thread reads (when the grid is not capped)
+constexpr int kHistMaxGrid = 512;
+
+template <int PASS, int BLOCK>
 __device__ __forceinline__ void select_histogram(const uint32_t *__restrict__ key, long long n_vec,
-                                                 long long budget, SplitState *__restrict__ st,
+                                                 unsigned prefix,
                                                  unsigned long long *__restrict__ hist)
 {
     __shared__ unsigned int h[kRadixBins];
-    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK)
         h[b] = 0;
     __syncthreads();
     constexpr int shift = radix_shift(PASS);
     constexpr unsigned mask = (1u << radix_bits(PASS)) - 1u;
-    const unsigned prefix = PASS == 0 ? 0u : st->prefix;
     constexpr int hi = shift + radix_bits(PASS);      // bits above this pass's digit
     const u4 *kv = reinterpret_cast<const u4 *>(key);
-    // four 16-byte loads in flight per thread; keys of one group that fall into one bin
+    // eight 16-byte loads in flight per thread; keys of one group that fall into one bin
     // (the rule in the first pass, whose digit is mostly exponent) cost one LDS atomic
-    constexpr int kUnroll = 4;
-    const long long stride = (long long)gridDim.x * kSplitBlock;
-    for (long long v0 = (long long)blockIdx.x * kSplitBlock + threadIdx.x; v0 < n_vec;
+    constexpr int kUnroll = 8;
+    const long long stride = (long long)gridDim.x * BLOCK;
+    for (long long v0 = (long long)blockIdx.x * BLOCK + threadIdx.x; v0 < n_vec;
          v0 += kUnroll * stride) {
         u4 k[kUnroll];
 #pragma unroll
@@ -791,22 +877,43 @@ __device__ __forceinline__ void select_histogram(const uint32_t *__restrict__ ke
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK)
         if (h[b])
             atomicAdd(&hist[b], (unsigned long long)h[b]);
-    if (last_workgroup(&st->tickets[PASS]))
-        select_pick<PASS>(budget, hist, st);
 }
 
-template <int PASS>
-__global__ __launch_bounds__(kSplitBlock) void k_select_histogram(
+// Launch 1: the top 11 bits.
+__global__ __launch_bounds__(kHistBlock) void k_select_histogram0(
     const uint32_t *__restrict__ key, long long n_vec, long long budget,
-    SplitState *__restrict__ st, unsigned long long *__restrict__ hist)
+    SplitState *__restrict__ st, unsigned long long *__restrict__ hist0)
 {
-    static_assert(PASS == 0 || PASS == 1, "the last digit is handled by k_select_finish");
-    if (PASS == 1 && st->done)
+    if (blockIdx.x == 0 && threadIdx.x == 0) {
+        st->n_stage2 = budget;
+        log_stage2(st, budget);
+        st->done = budget == 0 ? 1u : 0u;
+        if (budget == 0) {
+            st->threshold = 0;
+            st->ties_to_take = 0;
+            st->all_ties = 0;
+            st->collect = 0;
+        }
+    }
+    select_histogram<0, kHistBlock>(key, n_vec, 0u, hist0);
+}
+
+// Launch 2: the next 11 bits inside the bucket the first histogram points to.
+__global__ __launch_bounds__(kHistBlock) void k_select_histogram1(
+    const uint32_t *__restrict__ key, long long n_vec, long long budget,
+    SplitState *__restrict__ st, const unsigned long long *__restrict__ hist0,
+    unsigned long long *__restrict__ hist1)
+{
+    if (budget == 0)
+        return;                        // nothing is selected; hist0 is zeroed by the bitmap pass
+    const Picked p0 = pick_bucket<0, kHistBlock>(budget, hist0, st);
+    record_pick<0>(st, p0);
+    if (!p0.ok)
         return;
-    select_histogram<PASS>(key, n_vec, budget, st, hist);
+    select_histogram<1, kHistBlock>(key, n_vec, p0.prefix, hist1);
 }
 
 __device__ __forceinline__ u4 load_keys_or_pad(const uint32_t *__restrict__ key, long long v,
@@ -834,80 +941,99 @@ __device__ __forceinline__ void store_bitmap_word(unsigned sel, long long v, lon
 
 // Launch 3: the bitmap from the 22-bit prefix P of the threshold.  Upper 22 bits below P:
 // stage 2.  Equal to P: listed as a candidate (when few keys share P) and left in stage 1 until
-// k_select_finish has decided; above P: stage 1.
+// k_select_finish has decided; above P: stage 1.  Workgroups walk the tiles in rounds of the
+// grid, so the prologue (P from the second histogram) is paid once per workgroup.
 __global__ __launch_bounds__(kSplitBlock) void k_select_bitmap(
-    const uint32_t *__restrict__ key, long long n_vec, long long n_words,
-    const SplitState *__restrict__ st, TieCandidate *__restrict__ cand,
+    const uint32_t *__restrict__ key, long long n_vec, long long n_words, long long n_tiles,
+    long long budget, SplitState *__restrict__ st, unsigned long long *__restrict__ hist0,
+    const unsigned long long *__restrict__ hist1, TieCandidate *__restrict__ cand,
     unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
 {
-    const bool none = st->done != 0;
-    const bool collect = st->collect != 0;
-    const unsigned P = st->prefix;
-    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
-    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
-        const long long v = v0 + it * kSplitBlock + threadIdx.x;
-        const u4 k = load_keys_or_pad(key, v, n_vec);
-        unsigned sel = 0;              // bit j: element j goes to stage 2
-        if (!none) {
+    bool none = budget == 0;
+    bool collect = false;
+    unsigned P = 0;
+    if (!none) {
+        const Picked p1 = pick_bucket<1>(budget, hist1, st);
+        record_pick<1>(st, p1);
+        none = !p1.ok;                 // (cannot happen)
+        collect = p1.count <= kTieCandidates;
+        P = p1.prefix;
+    }
+    if (blockIdx.x == 0)
+        zero_histogram(hist0);         // (read by launch 2 only)
+    constexpr int kIters = kSelTile / kSplitStride;
+    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long long v0 = tile * (kSelTile / kVec);
+        u4 keys[kIters];               // all of the tile's loads in flight at once
 #pragma unroll
-            for (int j = 0; j < kVec; ++j) {
-                const unsigned hi = k[j] >> 10;
-                sel |= (hi < P ? 1u : 0u) << j;
-                if (hi == P && collect && v < n_vec) {
-                    // (at most kTieCandidates keys share P, so every slot exists)
-                    const unsigned slot = atomicAdd(n_cand, 1u);
-                    if (slot < kTieCandidates) {
-                        TieCandidate tc;
-                        tc.index = (unsigned long long)v * kVec + j;
-                        tc.key = k[j];
-                        tc.pad = 0;
-                        cand[slot] = tc;
+        for (int it = 0; it < kIters; ++it)
+            keys[it] = load_keys_or_pad(key, v0 + it * kSplitBlock + threadIdx.x, n_vec);
+#pragma unroll
+        for (int it = 0; it < kIters; ++it) {
+            const long long v = v0 + it * kSplitBlock + threadIdx.x;
+            const u4 k = keys[it];
+            unsigned sel = 0;          // bit j: element j goes to stage 2
+            if (!none) {
+#pragma unroll
+                for (int j = 0; j < kVec; ++j) {
+                    const unsigned hi = k[j] >> 10;
+                    sel |= (hi < P ? 1u : 0u) << j;
+                    if (hi == P && collect && v < n_vec) {
+                        // (at most kTieCandidates keys share P, so every slot exists)
+                        const unsigned slot = atomicAdd(n_cand, 1u);
+                        if (slot < kTieCandidates) {
+                            TieCandidate tc;
+                            tc.index = (unsigned long long)v * kVec + j;
+                            tc.key = k[j];
+                            tc.pad = 0;
+                            cand[slot] = tc;
+                        }
                     }
                 }
             }
+            store_bitmap_word(sel, v, n_words, bitmap);
         }
-        store_bitmap_word(sel, v, n_words, bitmap);
     }
 }
 
 // Launch 4.  Few keys share the prefix (st->collect): workgroup 0 takes, among the listed
-// candidates, the r = st->k_rem smallest in the order (low 10 bits, arena index) and clears
-// their bits; the other workgroups return.  Otherwise: the histogram of the last 10 bits over
-// all keys, and its last workgroup fixes the threshold and the number of ties to take.
+// candidates, the r smallest in the order (low 10 bits, arena index) and clears their bits;
+// the other workgroups return.  Otherwise: the histogram of the last 10 bits over all keys.
 constexpr int kIndexDigit = 11;        // arena indices are cut by four digits of 11 bits (< 2^44)
 
-__global__ __launch_bounds__(kSplitBlock) void k_select_finish(
+__global__ __launch_bounds__(kHistBlock) void k_select_finish(
     const uint32_t *__restrict__ key, long long n_vec, long long budget,
-    SplitState *__restrict__ st, unsigned long long *__restrict__ hist,
-    const TieCandidate *__restrict__ cand, unsigned int *__restrict__ n_cand,
-    uint32_t *__restrict__ bitmap)
+    SplitState *__restrict__ st, unsigned long long *__restrict__ hist1,
+    unsigned long long *__restrict__ hist2, const TieCandidate *__restrict__ cand,
+    unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
 {
-    if (st->done)
+    if (blockIdx.x == gridDim.x - 1)
+        zero_histogram(hist1);         // (read by launch 3 only)
+    if (budget == 0)
         return;
+    const unsigned P = st->prefix[1];
     if (!st->collect) {
-        select_histogram<2>(key, n_vec, budget, st, hist);
+        select_histogram<2, kHistBlock>(key, n_vec, P, hist2);
         return;
     }
     if (blockIdx.x != 0)
         return;
+    constexpr int B = kHistBlock;
     __shared__ unsigned int lh[kRadixBins];
     const unsigned n = *n_cand < kTieCandidates ? *n_cand : kTieCandidates;
-    const unsigned long long r = st->k_rem;                 // 1 <= r <= n
-    const unsigned P = st->prefix;
-    for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+    const unsigned long long r = st->k_rem[1];              // 1 <= r <= n
+    for (int b = threadIdx.x; b < kRadixBins; b += B)
         lh[b] = 0;
     __syncthreads();
-    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock)
+    for (unsigned c = threadIdx.x; c < n; c += B)
         atomicAdd(&lh[cand[c].key & 1023u], 1u);
     __syncthreads();
     int low;                                                // the threshold's last 10 bits
     unsigned long long below, count;
     {
-        unsigned long long c4[4];
-#pragma unroll
-        for (int j = 0; j < 4; ++j)
-            c4[j] = lh[threadIdx.x * 4 + j];
-        find_rank_bin<4>(c4, r, low, below, count);
+        unsigned long long c1[1];
+        c1[0] = lh[threadIdx.x];
+        find_rank_bin<1, B>(c1, r, low, below, count);
     }
     if (low < 0)                                            // (the list is incomplete: cannot happen)
         return;
@@ -920,23 +1046,22 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_finish(
         unsigned long long idx_prefix = 0, want = r2;
         for (int round = 0; round < 4; ++round) {
             const int shift = kIndexDigit * (3 - round);
-            for (int b = threadIdx.x; b < kRadixBins; b += kSplitBlock)
+            for (int b = threadIdx.x; b < kRadixBins; b += B)
                 lh[b] = 0;
             __syncthreads();
-            for (unsigned c = threadIdx.x; c < n; c += kSplitBlock) {
+            for (unsigned c = threadIdx.x; c < n; c += B) {
                 const TieCandidate tc = cand[c];
                 if ((tc.key & 1023u) == (unsigned)low &&
                     (round == 0 || (tc.index >> (shift + kIndexDigit)) == idx_prefix))
                     atomicAdd(&lh[(tc.index >> shift) & (kRadixBins - 1)], 1u);
             }
             __syncthreads();
-            unsigned long long c8[8];
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                c8[j] = lh[threadIdx.x * 8 + j];
+            unsigned long long c2[2];
+            c2[0] = lh[threadIdx.x * 2];
+            c2[1] = lh[threadIdx.x * 2 + 1];
             int digit;
             unsigned long long d_below, d_count;
-            find_rank_bin<8>(c8, want, digit, d_below, d_count);
+            find_rank_bin<2, B>(c2, want, digit, d_below, d_count);
             if (digit < 0)
                 return;                                     // (cannot happen)
             idx_prefix = (idx_prefix << kIndexDigit) | (unsigned long long)digit;
@@ -944,7 +1069,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_finish(
         }
         cut = idx_prefix;
     }
-    for (unsigned c = threadIdx.x; c < n; c += kSplitBlock) {
+    for (unsigned c = threadIdx.x; c < n; c += B) {
         const TieCandidate tc = cand[c];
         const unsigned l = tc.key & 1023u;
         if (l < (unsigned)low || (l == (unsigned)low && (all || tc.index <= cut)))
@@ -958,85 +1083,96 @@ __global__ __launch_bounds__(kSplitBlock) void k_select_finish(
     }
 }
 
-// Launch 5 (only when many keys share the threshold's prefix): per tile, how many keys equal
-// the threshold.
+// Launch 5 (works only when many keys share the threshold's prefix): the threshold T from the
+// third histogram, then per tile how many keys equal T.
 __global__ __launch_bounds__(kSplitBlock) void k_select_count_ties(
-    const uint32_t *__restrict__ key, long long n_vec, const SplitState *__restrict__ st,
+    const uint32_t *__restrict__ key, long long n_vec, long long n_tiles, long long budget,
+    SplitState *__restrict__ st, const unsigned long long *__restrict__ hist2,
     unsigned int *__restrict__ tile_ties)
 {
-    if (st->collect || st->done || st->all_ties)    // uniform: the bitmap pass will not read the counts
+    if (budget == 0 || st->collect)    // uniform over the launch
         return;
-    const unsigned T = st->threshold;
-    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
-    unsigned long long n = 0;
-    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
-        const u4 k = load_keys_or_pad(key, v0 + it * kSplitBlock + threadIdx.x, n_vec);
-        n += (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+    const Picked p2 = pick_bucket<2>(budget, hist2, st);
+    record_pick<2>(st, p2);
+    if (!p2.ok || p2.k_rem == p2.count)     // all keys equal to T are taken: no counts needed
+        return;
+    const unsigned T = p2.prefix;
+    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        const long long v0 = tile * (kSelTile / kVec);
+        unsigned long long n = 0;
+        for (int it = 0; it < kSelTile / kSplitStride; ++it) {
+            const u4 k = load_keys_or_pad(key, v0 + it * kSplitBlock + threadIdx.x, n_vec);
+            n += (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+        }
+        unsigned long long total;
+        block_exclusive_scan(n, &total);
+        if (threadIdx.x == 0)
+            tile_ties[tile] = (unsigned int)total;
     }
-    unsigned long long total;
-    block_exclusive_scan(n, &total);
-    if (threadIdx.x == 0)
-        tile_ties[blockIdx.x] = (unsigned int)total;
 }
 
 // Launch 6 (same condition): the bitmap from the full threshold T; of the keys equal to T the
 // first r in index order go to stage 2.  A tile adds up the tie counts of the tiles before it.
 __global__ __launch_bounds__(kSplitBlock) void k_select_write_bitmap(
-    const uint32_t *__restrict__ key, long long n_vec, long long n_words,
-    const SplitState *__restrict__ st, const unsigned int *__restrict__ tile_ties,
-    uint32_t *__restrict__ bitmap)
+    const uint32_t *__restrict__ key, long long n_vec, long long n_words, long long n_tiles,
+    long long budget, const SplitState *__restrict__ st, unsigned long long *__restrict__ hist2,
+    const unsigned int *__restrict__ tile_ties, uint32_t *__restrict__ bitmap)
 {
-    if (st->collect || st->done)
+    if (budget == 0 || st->collect)
         return;
+    if (blockIdx.x == 0)
+        zero_histogram(hist2);         // (read by launch 5 only)
     const unsigned T = st->threshold;
     const unsigned long long r = st->ties_to_take;
     const bool all = st->all_ties != 0;
-    unsigned long long before = 0, ties = 0;
-    if (!all) {
-        unsigned long long mine = 0;
-        for (long long t = threadIdx.x; t < (long long)blockIdx.x; t += kSplitBlock)
-            mine += tile_ties[t];
-        block_exclusive_scan(mine, &before);
-        ties = tile_ties[blockIdx.x];
-    }
-    // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
-    int tie_mode;
-    if (all)
-        tie_mode = 1;
-    else if (ties == 0 || before >= r)
-        tie_mode = 0;
-    else if (before + ties <= r)
-        tie_mode = 1;
-    else
-        tie_mode = 2;
-    unsigned long long run = before;
-    const long long v0 = (long long)blockIdx.x * (kSelTile / kVec);
-    for (int it = 0; it < kSelTile / kSplitStride; ++it) {
-        const long long v = v0 + it * kSplitBlock + threadIdx.x;
-        const u4 k = load_keys_or_pad(key, v, n_vec);
-        unsigned sel = 0;              // bit j: element j goes to stage 2
-        unsigned long long my_before = 0;
-        if (tie_mode == 2) {
-            const unsigned long long n = (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
-            unsigned long long total;
-            my_before = run + block_exclusive_scan(n, &total);
-            run += total;
+    for (long long tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        unsigned long long before = 0, ties = 0;
+        if (!all) {
+            unsigned long long mine = 0;
+            for (long long t = threadIdx.x; t < tile; t += kSplitBlock)
+                mine += tile_ties[t];
+            block_exclusive_scan(mine, &before);
+            ties = tile_ties[tile];
         }
-#pragma unroll
-        for (int j = 0; j < kVec; ++j) {
-            const unsigned x = k[j];
-            bool s = x < T;
-            if (x == T) {
-                if (tie_mode == 1)
-                    s = true;
-                else if (tie_mode == 2) {
-                    s = my_before < r;
-                    ++my_before;
-                }
+        // 0: no tie of this tile is taken, 1: all are, 2: the boundary is inside
+        int tie_mode;
+        if (all)
+            tie_mode = 1;
+        else if (ties == 0 || before >= r)
+            tie_mode = 0;
+        else if (before + ties <= r)
+            tie_mode = 1;
+        else
+            tie_mode = 2;
+        unsigned long long run = before;
+        const long long v0 = tile * (kSelTile / kVec);
+        for (int it = 0; it < kSelTile / kSplitStride; ++it) {
+            const long long v = v0 + it * kSplitBlock + threadIdx.x;
+            const u4 k = load_keys_or_pad(key, v, n_vec);
+            unsigned sel = 0;          // bit j: element j goes to stage 2
+            unsigned long long my_before = 0;
+            if (tie_mode == 2) {
+                const unsigned long long n = (k.x == T) + (k.y == T) + (k.z == T) + (k.w == T);
+                unsigned long long total;
+                my_before = run + block_exclusive_scan(n, &total);
+                run += total;
             }
-            sel |= (s ? 1u : 0u) << j;
+#pragma unroll
+            for (int j = 0; j < kVec; ++j) {
+                const unsigned x = k[j];
+                bool s = x < T;
+                if (x == T) {
+                    if (tie_mode == 1)
+                        s = true;
+                    else if (tie_mode == 2) {
+                        s = my_before < r;
+                        ++my_before;
+                    }
+                }
+                sel |= (s ? 1u : 0u) << j;
+            }
+            store_bitmap_word(sel, v, n_words, bitmap);
         }
-        store_bitmap_word(sel, v, n_words, bitmap);
     }
 }
 
