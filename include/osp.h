@@ -398,6 +398,12 @@ int32_t osp_lgp_read_shared(const osp_ctx *ctx);
  * OSP_ERR_BAD_STATE between the two stages of an iteration. */
 osp_status osp_set_keep_stage2_aggregate(osp_ctx *ctx, int32_t on);
 
+/* Reuse of a kept stage-2 aggregate is decided by the `grads` pointer and stride
+ * alone (see osp_ps_aggregate_update); the library cannot see whether the caller
+ * has written new values into those arenas since.  A caller that has calls this
+ * before the stage-2 call, which then aggregates the arenas afresh.  Host only. */
+osp_status osp_drop_kept_aggregate(osp_ctx *ctx);
+
 /* 1 if the last osp_lgp_correct kept the stage-2 aggregate; 0 otherwise.  For
  * callers that account for the bytes a step really moves. */
 int32_t osp_lgp_kept_aggregate(const osp_ctx *ctx);

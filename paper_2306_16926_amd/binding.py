@@ -106,6 +106,8 @@ def _load() -> C.CDLL:
     lib.osp_ps_aggregate_update_packed_bf16.restype = C.c_int
     lib.osp_set_keep_stage2_aggregate.argtypes = [vp, C.c_int32]
     lib.osp_set_keep_stage2_aggregate.restype = C.c_int
+    lib.osp_drop_kept_aggregate.argtypes = [vp]
+    lib.osp_drop_kept_aggregate.restype = C.c_int
     lib.osp_lgp_kept_aggregate.argtypes = [vp]
     lib.osp_lgp_kept_aggregate.restype = C.c_int32
     lib.osp_rs_window.argtypes = [vp, vp, i64, vp]
@@ -155,7 +157,7 @@ EXPORTS = ["osp_create", "osp_destroy", "osp_workspace_bytes", "osp_bind", "osp_
            "osp_get_importance", "osp_get_keys",
            "osp_stream_copy", "osp_stream_pattern", "osp_ics_upper_bound", "osp_tune_budget",
            "osp_last_error", "osp_chunk_elems", "osp_n_chunks", "osp_lgp_read_shared", "osp_windows_fused",
-           "osp_set_keep_stage2_aggregate", "osp_lgp_kept_aggregate"]
+           "osp_set_keep_stage2_aggregate", "osp_lgp_kept_aggregate", "osp_drop_kept_aggregate"]
 
 
 def _ptr(t) -> int:
@@ -237,6 +239,9 @@ class Context:
 
     def osp_set_keep_stage2_aggregate(self, on: bool) -> None:
         self._check(lib.osp_set_keep_stage2_aggregate(self._h, 1 if on else 0))
+
+    def osp_drop_kept_aggregate(self) -> None:
+        self._check(lib.osp_drop_kept_aggregate(self._h))
 
     def osp_lgp_kept_aggregate(self) -> bool:
         return bool(lib.osp_lgp_kept_aggregate(self._h))

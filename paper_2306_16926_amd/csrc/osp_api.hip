@@ -657,6 +657,14 @@ osp_status osp_set_keep_stage2_aggregate(osp_ctx *ctx, int32_t on)
     return OSP_OK;
 }
 
+osp_status osp_drop_kept_aggregate(osp_ctx *ctx)
+{
+    if (!ctx)
+        return OSP_ERR_INVALID_ARG;
+    ctx->stash_valid = false;
+    return OSP_OK;
+}
+
 int64_t osp_n_chunks(const osp_ctx *ctx) { return ctx ? (int64_t)ctx->n_chunks : 0; }
 
 const char *osp_last_error(const osp_ctx *ctx)

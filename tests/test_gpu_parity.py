@@ -366,6 +366,34 @@ def test_layer_lgp_keeps_stage2_aggregate(stage2_input, n_workers, keep):
 
 
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_arena_refilled_between_the_stages(gran):
+    """The same gradient buffer with NEW values at stage 2: the library reuses the kept
+    aggregate by pointer, so the caller says that the arenas changed (osp_drop_kept_aggregate)
+    and stage 2 aggregates afresh; results equal the oracle's with the new values."""
+    say("arena refilled", gran)
+    import torch
+    wl = W.custom([37, 1, 128, 5, 9000, 64, 3, 4096, 4097, 30001], 6, 0.5, align=4, config_id=25)
+    rng = np.random.default_rng(3)
+    real = brute.real_mask(wl.numel, wl.offsets(), wl.arena_elems())
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=True)
+    c = job.ctx
+    gib = (random_layer_gib(rng, wl.n_tensors) if gran == GRAN_LAYER
+           else random_bits(rng, wl.arena_elems(), real))
+    o.set_gib(gran, gib); c.osp_set_gib(gran, gib)
+    g1, g2 = wl.make_grads(0, 0), wl.make_grads(1, 0)
+    gd = job.upload_grads(g1); s_ = gd.shape[1]
+    o.ps_aggregate_update(1, g1); o.apply_stage(1); o.lgp_correct(g1)
+    c.osp_ps_aggregate_update(1, gd, s_); c.osp_apply_stage(1); c.osp_lgp_correct(gd, s_)
+    gd.copy_(torch.from_numpy(g2))                      # the caller overwrites the arenas ...
+    c.osp_drop_kept_aggregate()                         # ... and says so
+    o.ps_aggregate_update(2, g2); o.apply_stage(2)
+    c.osp_ps_aggregate_update(2, gd, s_); c.osp_apply_stage(2)
+    compare_state(job, o, "refilled arena")
+    assert np.array_equal(c.osp_get_keys()[real], o.keys()[real])
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
 @pytest.mark.parametrize("order", ["rs_lgp_last", "lgp_before_install", "lgp_after_stage2", "no_install1"])
 @pytest.mark.parametrize("n_workers", [3, 12])
 def test_lgp_paths_and_call_orders(gran, order, n_workers):

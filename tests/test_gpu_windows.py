@@ -294,6 +294,35 @@ def test_layer_steps_replay_as_a_graph(calls, shape):
 
 
 @pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
+def test_read_n_stage2_async_into_pinned_and_pageable_memory(gran):
+    """osp_read_n_stage2_async: the stage-2 size arrives in the caller's host memory once the
+    stream has passed the call, whether that memory is pinned (written by a small kernel) or
+    pageable (a copy)."""
+    import torch
+    say("async stage-2 size", gran)
+    wl = W.get("tiny")
+    o = make_oracle(wl)
+    job = device_job(wl, element_keys=(gran == GRAN_ELEMENT))
+    c = job.ctx
+    all1 = np.ones(wl.n_tensors, np.uint8)
+    o.set_gib(GRAN_LAYER, all1); c.osp_set_gib(GRAN_LAYER, all1)
+    pinned = torch.full((3,), -1, dtype=torch.int64).pin_memory()
+    pageable = np.full(3, -1, np.int64)
+    want = []
+    for step in range(3):
+        g = wl.make_grads(0, step)
+        gd = job.upload_grads(g)
+        want.append(o.sync_step(g, gran, wl.budget))
+        job.sync_step(gd, gran, wl.budget)
+        c.osp_read_n_stage2_async(pinned.data_ptr() + 8 * step)
+        c.osp_read_n_stage2_async(pageable.ctypes.data + 8 * step)
+    torch.cuda.synchronize()
+    assert [int(x) for x in pinned] == want
+    assert pageable.tolist() == want
+    assert c.osp_n_stage2() == want[-1]
+
+
+@pytest.mark.parametrize("gran", [GRAN_LAYER, GRAN_ELEMENT])
 def test_stage2_log_round_robin(gran):
     """osp_set_stage2_log: every split stores the size of the stage 2 it chose, round robin in
     the caller's buffer, counted from the call; taking the log away stops it."""
