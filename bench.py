@@ -48,11 +48,11 @@ BRACKET_EVERY = 4               # steps between two event-bracketed steps of the
 # 2 GiB k_stream_copy).  Taken from the committed summaries, NOT measured by this run; only
 # reported for the workload and launch configuration they were taken on.
 PROFILED_TRAFFIC = {
-    # (workload, granularity, kernel): (bytes per launch, summary)
+    # (workload, granularity, kernel): (bytes per launch in the timed region, summary)
     ("vgg16", "layer", "k_aggregate_update"):
-        ((7226993 + 815368) * 1024, "profiles/sync_step_traffic_vgg16_layer.txt"),
+        (8235800000, "profiles/sync_step_vgg16_layer.txt"),
     ("vgg16", "element", "k_rs_window_element"):
-        (21137893376, "profiles/window_kernels_vgg16_element.txt"),
+        (21138700000, "profiles/sync_step_vgg16_element.txt"),
 }
 
 
