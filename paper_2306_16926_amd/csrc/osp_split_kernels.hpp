@@ -557,6 +557,155 @@ __device__ __forceinline__ void layer_rank_in_lds(
     }
 }
 
+// The same for at most 64 layers (VGG-16, ResNet-18): the ranking runs in ONE wavefront, a layer
+// per lane, with cross-lane shuffles where the LDS version has barriers (a bitonic sort of 64
+// keys is 21 compare-exchange rounds: 21 barriers of a 1024-thread workgroup there, none here);
+// one barrier before the whole workgroup fills the stage tables.  Same sums, same order of
+// operations per layer, same results.
+constexpr int kRankWaveLayers = 64;
+
+template <int BLOCK>
+__device__ __forceinline__ void layer_rank_in_wave(
+    int L, const double *__restrict__ seg_sum, const int *__restrict__ layer_seg_begin,
+    const int *__restrict__ big_layers, int n_big, double *__restrict__ imp,
+    const long long *__restrict__ numel, const int *__restrict__ layer_span_begin, long long budget,
+    uint8_t *__restrict__ gib_layer, int *__restrict__ order, int *__restrict__ layer_base,
+    SplitState *__restrict__ st, StageCounts *__restrict__ counts_out, unsigned seq, int set,
+    int n_spans, const Span *__restrict__ spans, const int *__restrict__ span_layer,
+    Span *__restrict__ list_s1, Span *__restrict__ list_s2)
+{
+    __shared__ int w_base[kRankWaveLayers], w_first[kRankWaveLayers], w_total[2];
+    __shared__ uint8_t w_important[kRankWaveLayers];
+    // (requested up front, as in the LDS version)
+    constexpr int kSpansPer = kRankFillMaxSpans / BLOCK;
+    Span my_span[kSpansPer];
+    int my_span_layer[kSpansPer];
+#pragma unroll
+    for (int j = 0; j < kSpansPer; ++j) {
+        const int k = j * BLOCK + (int)threadIdx.x;
+        if (k < n_spans) {
+            my_span[j] = spans[k];
+            my_span_layer[j] = span_layer[k];
+        }
+    }
+    if (threadIdx.x < 64) {
+        const int lane = threadIdx.x;
+        const bool live = lane < L;
+        const long long my_numel = live ? numel[lane] : 0;
+        const int first = live ? layer_span_begin[lane] : 0;
+        const int n_my_spans = live ? layer_span_begin[lane + 1] - first : 0;
+        // I^l: layers of few segments by their own lane, in order; layers of many by the whole
+        // wavefront, one layer at a time (lanes take segments lane, lane+64, ..., then the butterfly)
+        double s = 0.0;
+        if (live) {
+            const int g0 = layer_seg_begin[lane], g1 = layer_seg_begin[lane + 1];
+            if (g1 - g0 <= kFewSegments)
+                for (int g = g0; g < g1; ++g)
+                    s += load_device_scope(&seg_sum[g]);   // (written by this launch)
+        }
+        for (int i = 0; i < n_big; ++i) {
+            const int lb = big_layers[i];
+            const int g0 = layer_seg_begin[lb], g1 = layer_seg_begin[lb + 1];
+            double t = 0.0;
+            for (int g = g0 + lane; g < g1; g += 64)
+                t += load_device_scope(&seg_sum[g]);
+            t = __shfl(wave_sum(t), 0, 64);
+            if (lane == lb)
+                s = t;
+        }
+        if (live)
+            imp[lane] = s;
+        // bitonic sort of (importance, layer) over the 64 lanes; padding lanes sort last
+        unsigned long long key = live ? importance_rank_key(s) : ~0ull;
+        int idx = lane;
+#pragma unroll
+        for (int k = 2; k <= 64; k <<= 1)
+#pragma unroll
+            for (int j = k >> 1; j > 0; j >>= 1) {
+                const unsigned long long o_key = __shfl_xor(key, j, 64);
+                const int o_idx = __shfl_xor(idx, j, 64);
+                const bool other_first = o_key < key || (o_key == key && o_idx < idx);
+                const bool keep_first = ((lane & j) == 0) == ((lane & k) == 0);
+                if (keep_first == other_first) {
+                    key = o_key;
+                    idx = o_idx;
+                }
+            }
+        // lane r now holds the layer ranked r-th: running size along the ranking (sizes are
+        // positive, so "fits" holds exactly on a prefix)
+        const long long size_r = __shfl(my_numel, idx, 64);
+        long long incl = size_r;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const long long up = __shfl_up(incl, off, 64);
+            if (lane >= off)
+                incl += up;
+        }
+        const bool fits = lane < L && incl <= budget;
+        long long n_stage2 = fits ? incl : 0;              // the largest fitting prefix
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) {
+            const long long other = __shfl_xor(n_stage2, off, 64);
+            n_stage2 = other > n_stage2 ? other : n_stage2;
+        }
+        if (lane < L) {
+            order[lane] = idx;
+            w_important[idx] = fits ? 0 : 1;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        const bool important = live ? w_important[lane] != 0 : true;
+        if (live)
+            gib_layer[lane] = important ? 1 : 0;
+        // bases of the two stage tables: exclusive scans over the layers, in layer order
+        int in1 = important ? n_my_spans : 0, in2 = important ? 0 : n_my_spans;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int u1 = __shfl_up(in1, off, 64), u2 = __shfl_up(in2, off, 64);
+            if (lane >= off) {
+                in1 += u1;
+                in2 += u2;
+            }
+        }
+        const int tot1 = __shfl(in1, 63, 64), tot2 = __shfl(in2, 63, 64);
+        if (live) {
+            const int base = important ? in1 - n_my_spans : in2 - n_my_spans;
+            w_base[lane] = base;
+            w_first[lane] = first;
+            layer_base[lane] = base;
+        }
+        if (lane == 0) {
+            w_total[0] = tot1;
+            w_total[1] = tot2;
+            st->n_stage2 = n_stage2;
+            st->stage_spans[set][0] = tot1;
+            st->stage_spans[set][1] = tot2;
+            log_stage2(st, n_stage2);
+            publish_counts(counts_out, tot1, tot2, n_stage2, seq);
+        }
+    }
+    __syncthreads();
+    const int carry1 = w_total[0], carry2 = w_total[1];
+    Span cleared;
+    cleared.start = 0; cleared.n_elems = 0; cleared.chunk_base = 0;
+#pragma unroll
+    for (int j = 0; j < kSpansPer; ++j) {
+        const int k = j * BLOCK + (int)threadIdx.x;
+        if (k < n_spans) {
+            const int l = my_span_layer[j];
+            const int pos = w_base[l] + (k - w_first[l]);
+            if (w_important[l]) {
+                list_s1[pos] = my_span[j];
+                list_s2[carry2 + pos] = cleared;
+            } else {
+                list_s2[pos] = my_span[j];
+                list_s1[carry1 + pos] = cleared;
+            }
+        }
+    }
+}
+
 // The whole layer-granular split in one launch for L <= kRankTile: every workgroup sums four
 // segments of per-chunk importance partials (each by 256 threads, in k_segment_importance's
 // order, so the sums are the same bit for bit), and the workgroup that finishes last ranks
@@ -608,9 +757,14 @@ __global__ __launch_bounds__(BLOCK) void k_layer_split_lds(
     }
     if (!last_workgroup(&st->layer_ticket))
         return;
-    layer_rank_in_lds<BLOCK>(L, seg_sum, layer_seg_begin, big_layers, n_big, imp, numel,
-                             layer_span_begin, budget, gib_layer, order, layer_base, st, counts_out,
-                             seq, set, n_spans, spans, span_layer, list_s1, list_s2);
+    if (L <= kRankWaveLayers)
+        layer_rank_in_wave<BLOCK>(L, seg_sum, layer_seg_begin, big_layers, n_big, imp, numel,
+                                  layer_span_begin, budget, gib_layer, order, layer_base, st,
+                                  counts_out, seq, set, n_spans, spans, span_layer, list_s1, list_s2);
+    else
+        layer_rank_in_lds<BLOCK>(L, seg_sum, layer_seg_begin, big_layers, n_big, imp, numel,
+                                 layer_span_begin, budget, gib_layer, order, layer_base, st, counts_out,
+                                 seq, set, n_spans, spans, span_layer, list_s1, list_s2);
 }
 
 // After a GIB was uploaded from the host: only the table bases are needed.

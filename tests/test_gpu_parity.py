@@ -560,6 +560,37 @@ def test_split_element_adversarial(case):
     _split_from_keys(keys, k, numel)
 
 
+@pytest.mark.parametrize("ties,take", [(3000, 1234), (5, 2), (70_000, 69_999)])
+def test_split_element_ties_cut_at_large_indices(ties, take):
+    """Ties at the threshold spread over 8.4 M keys: the cut by arena index works through its
+    11-bit digits up to bit 23 (few ties: the candidate list; 70 000: the per-tile counts).
+    Keys go straight into the context-free entry point; expected bitmap: the oracle's sort."""
+    import torch
+    from paper_2306_16926_amd.binding import osp_split_element_static
+    say("ties at large indices", ties, take)
+    rng = np.random.default_rng(ties)
+    n = (1 << 23) + 4096
+    bits = (np.uint32(0x3F800000) + rng.permutation(n).astype(np.uint32))   # distinct, positive, finite
+    T = np.uint32(0x3FC00000)
+    bits[bits == T] = np.uint32(0x3F800000) + np.uint32(n)                   # (still distinct)
+    where = rng.choice(n, ties, replace=False)
+    where[:3] = [n - 1, (1 << 22) + 1, 5]                                    # both ends and a middle digit
+    bits[where] = T
+    k = int((bits < T).sum()) + take
+    o = OracleOSP([n], [0], n, 1, 0.1, 0.0)
+    o.q[:] = bits.view(F)
+    assert np.array_equal(o.keys(), bits)
+    o.split(GRAN_ELEMENT, k)
+    keys = torch.from_numpy(bits.view(np.int32)).cuda()
+    out = torch.zeros((n + 31) // 32, dtype=torch.int32, device="cuda")
+    osp_split_element_static(keys, n, k, out)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().view(np.uint32)
+    assert np.array_equal(got, o.gib_bits), int((got != o.gib_bits).sum())
+    s2 = np.unpackbits(got.view(np.uint8), bitorder="little")[:n] == 0
+    assert int(s2.sum()) == k and int(s2[np.sort(where)][:take].sum()) == take
+
+
 def test_split_layer_ties_nan_and_zero_layers():
     say("layer ties")
     wl = W.custom([8, 8, 8, 8, 8, 5000], 1, align=4, config_id=32)
