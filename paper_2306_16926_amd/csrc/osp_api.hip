@@ -337,17 +337,60 @@ osp_status launch_check(osp_ctx *ctx, const char *what)
 
 } // namespace
 
+// How many one-wavefront workgroups of a wide kernel a compute unit should hold.  A wavefront
+// of the aggregate has (N + 2) KB of loads in flight, and a compute unit takes as many
+// wavefronts as their registers allow (20 at N = 16): over 90 MB in flight on the whole GPU,
+// several times what keeps the memory busy, and measurably worse than less (the requests of
+// one moment then spread over more DRAM pages).  The launch therefore asks for dynamic LDS that
+// no kernel touches, sized so that only `target_bytes / bytes_per_wave` workgroups fit into a
+// compute unit's 160 KB.  Measured on VGG-16- (N = 16) and ResNet-shaped (N = 8) steps:
+// 64 KB of loads per compute unit for the aggregate and the element-granular RS window
+// (4 wavefronts at N = 16: 1.31 -> 1.27 ms and 3.92 -> 3.56 ms; 6 at N = 8), 110 KB for
+// k_lgp_keep (6 at N = 16: 0.87 -> 0.85 ms; none at N = 8), 64 KB of stores for the
+// element-granular ICS window (6 at N = 8: 0.74 -> 0.65 ms).  Fewer than 4 is never asked for
+// (3 ran 35 % slower than 4); above `most` (10; 8 for the RS window, whose (N + 4) KB of
+// stores per wavefront count as well: bfloat16 arenas at N = 8, 0.78 -> 0.74 ms) the launch is
+// left alone.  The sweep kernels (one load per lane) and k_update_from_stash lose from any such
+// bound.
+constexpr unsigned kLdsPerCu = 160u * 1024u;
+constexpr size_t kLoadsInFlightPerCu = 64u * 1024u;
+constexpr size_t kKeepLoadsInFlightPerCu = 110u * 1024u;
+
+static unsigned occupancy_lds(size_t bytes_per_wave, size_t target_bytes, size_t most = 10,
+                              bool always = false)
+{
+    size_t waves = (target_bytes + bytes_per_wave / 2) / bytes_per_wave;
+    if (waves > most) {
+        if (!always)
+            return 0;
+        waves = most;
+    }
+    if (waves < 4)
+        waves = 4;
+    return (unsigned)(kLdsPerCu / waves) & ~1023u;
+}
+
+// Bytes one wavefront moves per pass over a group of chunks: `n_grad` gradient streams of
+// `grad_bytes` per element (at most kWorkerBlock of them at once) and `n_f32` fp32 streams,
+// 4 elements per lane.
+static size_t wave_bytes(int n_grad, size_t grad_bytes, int n_f32)
+{
+    const int g = n_grad < kWorkerBlock ? n_grad : kWorkerBlock;
+    return (size_t)kBlock * kVec * ((size_t)g * grad_bytes + (size_t)n_f32 * sizeof(float));
+}
+
 template <typename GT>
 static void launch_aggregate(int variant, dim3 grid, dim3 block, hipStream_t s, const Span *table,
-                             const AggArgs &a)
+                             const AggArgs &a, int n_workers)
 {
+    const unsigned lds = occupancy_lds(wave_bytes(n_workers, sizeof(GT), 2), kLoadsInFlightPerCu);
     switch (variant) {
-    case 0: k_aggregate_update<false, false, false, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 1: k_aggregate_update<false, false, true, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 2: k_aggregate_update<false, true, false, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 3: k_aggregate_update<false, true, true, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 5: k_aggregate_update<true, false, true, GT><<<grid, block, 0, s>>>(table, a); break;
-    default: k_aggregate_update<true, true, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 0: k_aggregate_update<false, false, false, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 1: k_aggregate_update<false, false, true, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 2: k_aggregate_update<false, true, false, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 3: k_aggregate_update<false, true, true, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 5: k_aggregate_update<true, false, true, GT><<<grid, block, lds, s>>>(table, a); break;
+    default: k_aggregate_update<true, true, true, GT><<<grid, block, lds, s>>>(table, a); break;
     }
 }
 
@@ -404,14 +447,15 @@ static void launch_rs_window_element(const osp_ctx *ctx, const RsElementArgs &a,
     const dim3 block(kBlock);
     const int N = ctx->n_workers;
     const int cap = N <= 4 ? 4 : (N <= 8 ? 8 : 16);
+    const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(GT), 2), kLoadsInFlightPerCu, 8, true);
     if (ctx->weighted) {
-        if (cap == 4) k_rs_window_element<4, true, GT><<<grid, block, 0, s>>>(a);
-        else if (cap == 8) k_rs_window_element<8, true, GT><<<grid, block, 0, s>>>(a);
-        else k_rs_window_element<16, true, GT><<<grid, block, 0, s>>>(a);
+        if (cap == 4) k_rs_window_element<4, true, GT><<<grid, block, lds, s>>>(a);
+        else if (cap == 8) k_rs_window_element<8, true, GT><<<grid, block, lds, s>>>(a);
+        else k_rs_window_element<16, true, GT><<<grid, block, lds, s>>>(a);
     } else {
-        if (cap == 4) k_rs_window_element<4, false, GT><<<grid, block, 0, s>>>(a);
-        else if (cap == 8) k_rs_window_element<8, false, GT><<<grid, block, 0, s>>>(a);
-        else k_rs_window_element<16, false, GT><<<grid, block, 0, s>>>(a);
+        if (cap == 4) k_rs_window_element<4, false, GT><<<grid, block, lds, s>>>(a);
+        else if (cap == 8) k_rs_window_element<8, false, GT><<<grid, block, lds, s>>>(a);
+        else k_rs_window_element<16, false, GT><<<grid, block, lds, s>>>(a);
     }
 }
 
@@ -433,11 +477,12 @@ static void launch_lgp_keep(const osp_ctx *ctx, const Span *table, const LgpKeep
 {
     const dim3 grid(n_groups), block(kBlock);
     const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
+    const unsigned lds = occupancy_lds(wave_bytes(ctx->n_workers, sizeof(GT), 1), kKeepLoadsInFlightPerCu);
     switch (variant) {
-    case 0: k_lgp_keep<false, false, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 1: k_lgp_keep<false, true, GT><<<grid, block, 0, s>>>(table, a); break;
-    case 2: k_lgp_keep<true, false, GT><<<grid, block, 0, s>>>(table, a); break;
-    default: k_lgp_keep<true, true, GT><<<grid, block, 0, s>>>(table, a); break;
+    case 0: k_lgp_keep<false, false, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 1: k_lgp_keep<false, true, GT><<<grid, block, lds, s>>>(table, a); break;
+    case 2: k_lgp_keep<true, false, GT><<<grid, block, lds, s>>>(table, a); break;
+    default: k_lgp_keep<true, true, GT><<<grid, block, lds, s>>>(table, a); break;
     }
 }
 
@@ -985,9 +1030,9 @@ static osp_status aggregate_update(osp_ctx *ctx, int stage, const void *grads, i
         if (variant == 4 || variant == 6)
             return fail(ctx, OSP_ERR_UNSUPPORTED, "element-granular GIB without element_keys");
         if (bf16)
-            launch_aggregate<bf16_t>(variant, grid, block, s, table, a);
+            launch_aggregate<bf16_t>(variant, grid, block, s, table, a, ctx->n_workers);
         else
-            launch_aggregate<float>(variant, grid, block, s, table, a);
+            launch_aggregate<float>(variant, grid, block, s, table, a, ctx->n_workers);
     }
     st = launch_check(ctx, "k_aggregate_update");
     if (st != OSP_OK)
@@ -1466,16 +1511,18 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
             a.lr = ctx->lr;
             a.mu = ctx->mu;
             const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
+            // (N + 2) KB of stores per wavefront; bounded like the loads of the RS window
+            const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(float), 2), kLoadsInFlightPerCu);
             if (from_stash)
-                k_ics_window_element<true, false><<<grid, block, 0, s>>>(a);
+                k_ics_window_element<true, false><<<grid, block, lds, s>>>(a);
             else if (bf16 && ctx->weighted)
-                k_ics_window_element<false, true, bf16_t><<<grid, block, 0, s>>>(a);
+                k_ics_window_element<false, true, bf16_t><<<grid, block, lds, s>>>(a);
             else if (bf16)
-                k_ics_window_element<false, false, bf16_t><<<grid, block, 0, s>>>(a);
+                k_ics_window_element<false, false, bf16_t><<<grid, block, lds, s>>>(a);
             else if (ctx->weighted)
-                k_ics_window_element<false, true><<<grid, block, 0, s>>>(a);
+                k_ics_window_element<false, true><<<grid, block, lds, s>>>(a);
             else
-                k_ics_window_element<false, false><<<grid, block, 0, s>>>(a);
+                k_ics_window_element<false, false><<<grid, block, lds, s>>>(a);
         } else {
             // (the launch covers all groups; the kernel reads the stage-2 table's length)
             WindowLayerArgs a;

@@ -126,25 +126,40 @@ __device__ __forceinline__ f4 ld_stream(const float *p)
 using bf16_t = unsigned short;
 using u2 = __attribute__((ext_vector_type(2))) unsigned int;
 
+// A lane's 4 gradient elements as they come from memory (GradRaw) and widened to fp32.
+// Kernels whose gradient loads sit behind a test of the worker count load all the raw values
+// first and widen afterwards: widening inside such a branch makes the compiler wait for each
+// load where it is issued, one round trip to memory per worker.
 template <typename GT>
-__device__ __forceinline__ f4 ld_grad(const GT *p);
-
+struct GradRaw;
 template <>
-__device__ __forceinline__ f4 ld_grad<float>(const float *p)
+struct GradRaw<float> { using type = f4; };
+template <>
+struct GradRaw<bf16_t> { using type = u2; };
+
+__device__ __forceinline__ f4 ld_grad_raw(const float *p)
 {
     return __builtin_nontemporal_load(reinterpret_cast<const f4 *>(p));
 }
-
-template <>
-__device__ __forceinline__ f4 ld_grad<bf16_t>(const bf16_t *p)
+__device__ __forceinline__ u2 ld_grad_raw(const bf16_t *p)
 {
-    const u2 r = __builtin_nontemporal_load(reinterpret_cast<const u2 *>(p));
+    return __builtin_nontemporal_load(reinterpret_cast<const u2 *>(p));
+}
+__device__ __forceinline__ f4 widen(f4 r) { return r; }
+__device__ __forceinline__ f4 widen(u2 r)
+{
     f4 f;
     f.x = __uint_as_float(r.x << 16);
     f.y = __uint_as_float(r.x & 0xFFFF0000u);
     f.z = __uint_as_float(r.y << 16);
     f.w = __uint_as_float(r.y & 0xFFFF0000u);
     return f;
+}
+
+template <typename GT>
+__device__ __forceinline__ f4 ld_grad(const GT *p)
+{
+    return widen(ld_grad_raw(p));
 }
 
 __device__ __forceinline__ f4 ld_keep(const float *p)
@@ -281,6 +296,12 @@ __device__ __forceinline__ void add_workers(f4 &acc, int w0, const GT *__restric
                                             long long worker_stride, unsigned i,
                                             const float *__restrict__ weights)
 {
+    float wgt[B];
+    if (WEIGHTED) {
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            wgt[j] = weights[w0 + j];
+    }
     f4 g[B];
 #pragma unroll
     for (int j = 0; j < B; ++j)
@@ -288,7 +309,7 @@ __device__ __forceinline__ void add_workers(f4 &acc, int w0, const GT *__restric
     if (WEIGHTED) {
 #pragma unroll
         for (int j = 0; j < B; ++j)
-            g[j] = g[j] * weights[w0 + j];
+            g[j] = g[j] * wgt[j];
     }
     f4 s = g[0];
     if (w0 != 0)
@@ -692,6 +713,12 @@ __device__ __forceinline__ void lgp_and_add(f4 &acc, int w0, const GT *__restric
                                             float *__restrict__ w_base, long long param_stride,
                                             unsigned m)
 {
+    float wgt[B];
+    if (WEIGHTED) {                    // (ahead of the stores: a load issued behind them waits for them)
+#pragma unroll
+        for (int j = 0; j < B; ++j)
+            wgt[j] = weights[w0 + j];
+    }
     f4 g[B];
 #pragma unroll
     for (int j = 0; j < B; ++j)
@@ -713,7 +740,7 @@ __device__ __forceinline__ void lgp_and_add(f4 &acc, int w0, const GT *__restric
     if (WEIGHTED) {
 #pragma unroll
         for (int j = 0; j < B; ++j)
-            g[j] = g[j] * weights[w0 + j];
+            g[j] = g[j] * wgt[j];
     }
     f4 s = g[0];
     if (w0 != 0)

@@ -66,16 +66,25 @@ __global__ __launch_bounds__(kBlock) void k_rs_window_element(const RsElementArg
         const unsigned other = valid & ~m;
         const f4 p = ld_stream(Pc + i);
         const f4 v = ld_stream(Vc + i);
+        typename GradRaw<GT>::type raw[NB];
+        float wgt[NB];
+#pragma unroll
+        for (int j = 0; j < NB; ++j)
+            if (j < N) {
+                raw[j] = ld_grad_raw(Gc + (long long)j * a.worker_stride + i);
+                if (WEIGHTED)
+                    wgt[j] = a.weights[j];
+            }
         f4 g[NB];
 #pragma unroll
         for (int j = 0; j < NB; ++j)
             if (j < N)
-                g[j] = ld_grad<GT>(Gc + (long long)j * a.worker_stride + i);
-        f4 acc = WEIGHTED ? g[0] * a.weights[0] : g[0];
+                g[j] = widen(raw[j]);
+        f4 acc = WEIGHTED ? g[0] * wgt[0] : g[0];
 #pragma unroll
         for (int j = 1; j < NB; ++j)
             if (j < N) {
-                const f4 t = WEIGHTED ? g[j] * a.weights[j] : g[j];
+                const f4 t = WEIGHTED ? g[j] * wgt[j] : g[j];
                 acc = acc + t;
             }
         const f4 gbar = WEIGHTED ? acc : acc * a.inv_n;
@@ -342,15 +351,15 @@ __global__ __launch_bounds__(kBlock) void k_window_layer(const WindowLayerArgs a
         for (unsigned i = threadIdx.x * kVec; i < (unsigned)c.len; i += kStride) {
             const int rem = (int)c.len - (int)i;
             const f4 p = ld_stream(Pc + i);
-            f4 g[kWindowMaxWorkers];
+            typename GradRaw<GT>::type raw[kWindowMaxWorkers];
 #pragma unroll
             for (int j = 0; j < kWindowMaxWorkers; ++j)
                 if (j < N)
-                    g[j] = ld_grad<GT>(Gc + (long long)j * a.worker_stride + i);
+                    raw[j] = ld_grad_raw(Gc + (long long)j * a.worker_stride + i);
 #pragma unroll
             for (int j = 0; j < kWindowMaxWorkers; ++j)
                 if (j < N) {
-                    const f4 ls = g[j] * a.lr;
+                    const f4 ls = widen(raw[j]) * a.lr;
                     const f4 pl = p - ls;
                     float *dst = Wc + (long long)j * a.param_stride + i;
                     if (rem >= kVec) {
