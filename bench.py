@@ -52,7 +52,7 @@ PROFILED_TRAFFIC = {
     ("vgg16", "layer", "k_aggregate_update"):
         (8235800000, "profiles/sync_step_vgg16_layer.txt"),
     ("vgg16", "element", "k_rs_window_element"):
-        (21138700000, "profiles/sync_step_vgg16_element.txt"),
+        (21136400000, "profiles/sync_step_vgg16_element.txt"),
 }
 
 

@@ -339,22 +339,32 @@ osp_status launch_check(osp_ctx *ctx, const char *what)
 
 // How many one-wavefront workgroups of a wide kernel a compute unit should hold.  A wavefront
 // of the aggregate has (N + 2) KB of loads in flight, and a compute unit takes as many
-// wavefronts as their registers allow (20 at N = 16): over 90 MB in flight on the whole GPU,
-// several times what keeps the memory busy, and measurably worse than less (the requests of
-// one moment then spread over more DRAM pages).  The launch therefore asks for dynamic LDS that
-// no kernel touches, sized so that only `target_bytes / bytes_per_wave` workgroups fit into a
-// compute unit's 160 KB.  Measured on VGG-16- (N = 16) and ResNet-shaped (N = 8) steps:
-// 64 KB of loads per compute unit for the aggregate and the element-granular RS window
-// (4 wavefronts at N = 16: 1.31 -> 1.27 ms and 3.92 -> 3.56 ms; 6 at N = 8), 110 KB for
-// k_lgp_keep (6 at N = 16: 0.87 -> 0.85 ms; none at N = 8), 64 KB of stores for the
-// element-granular ICS window (6 at N = 8: 0.74 -> 0.65 ms).  Fewer than 4 is never asked for
-// (3 ran 35 % slower than 4); above `most` (10; 8 for the RS window, whose (N + 4) KB of
-// stores per wavefront count as well: bfloat16 arenas at N = 8, 0.78 -> 0.74 ms) the launch is
-// left alone.  The sweep kernels (one load per lane) and k_update_from_stash lose from any such
-// bound.
-constexpr unsigned kLdsPerCu = 160u * 1024u;
-constexpr size_t kLoadsInFlightPerCu = 64u * 1024u;
-constexpr size_t kKeepLoadsInFlightPerCu = 110u * 1024u;
+// wavefronts as their registers allow (16-20 at N = 16): over 70 MB in flight on the whole
+// GPU, several times what keeps the memory busy, and measurably worse than less (the requests
+// of one moment then spread over more DRAM pages).  The launch therefore asks for dynamic LDS
+// that no kernel touches, sized so that only `target_bytes / bytes_per_wave` workgroups fit
+// into a compute unit.  Measured on VGG-16- (N = 16) and ResNet-shaped (N = 8) steps, best
+// count per compute unit and time against the unbounded launch:
+//   aggregate              N = 16: 4-5 (1.31 -> 1.27 ms)   N = 8: 7 (0.136 -> 0.130 ms)
+//   k_lgp_keep             N = 16: 6-7 (0.87 -> 0.85 ms)   N = 8: unbounded is best
+//   element RS window      N = 16: 4 (3.92 -> 3.56 ms)     N = 8: 5-6 (0.95 -> 0.87 ms)
+//   element ICS window                                     N = 8: 6-8 (0.74 -> 0.65 ms)
+// which the three byte targets below reproduce.  Fewer than 4 is never asked for (3 ran 35 %
+// slower than 4); above `most` (10; 8 for the RS window, whose (N + 4) KB of stores per
+// wavefront count as well: bfloat16 arenas at N = 8, 0.78 -> 0.74 ms) the launch is left
+// alone.  The sweep kernels (one load per lane) and k_update_from_stash lose from any bound.
+constexpr size_t kLoadsInFlightPerCu = 70u * 1024u;
+constexpr size_t kKeepStoresInFlightPerCu = 110u * 1024u;
+constexpr size_t kWindowBytesInFlightPerCu = 62u * 1024u;
+
+// Dynamic LDS per one-wavefront workgroup that leaves room for exactly `waves` of them in a
+// compute unit (measured with a kernel that counts its resident workgroups per compute unit:
+// the 160 KB do not divide evenly, 32 KB fit 4 times and 16 KB 9 times).
+static unsigned lds_for_waves(size_t waves)
+{
+    static const unsigned lds[] = {40960, 30720, 26624, 22528, 20480, 16384, 14336};   // 4 .. 10
+    return lds[waves - 4];
+}
 
 static unsigned occupancy_lds(size_t bytes_per_wave, size_t target_bytes, size_t most = 10,
                               bool always = false)
@@ -367,7 +377,7 @@ static unsigned occupancy_lds(size_t bytes_per_wave, size_t target_bytes, size_t
     }
     if (waves < 4)
         waves = 4;
-    return (unsigned)(kLdsPerCu / waves) & ~1023u;
+    return lds_for_waves(waves);
 }
 
 // Bytes one wavefront moves per pass over a group of chunks: `n_grad` gradient streams of
@@ -447,7 +457,7 @@ static void launch_rs_window_element(const osp_ctx *ctx, const RsElementArgs &a,
     const dim3 block(kBlock);
     const int N = ctx->n_workers;
     const int cap = N <= 4 ? 4 : (N <= 8 ? 8 : 16);
-    const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(GT), 2), kLoadsInFlightPerCu, 8, true);
+    const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(GT), 2), kWindowBytesInFlightPerCu, 8, true);
     if (ctx->weighted) {
         if (cap == 4) k_rs_window_element<4, true, GT><<<grid, block, lds, s>>>(a);
         else if (cap == 8) k_rs_window_element<8, true, GT><<<grid, block, lds, s>>>(a);
@@ -477,7 +487,8 @@ static void launch_lgp_keep(const osp_ctx *ctx, const Span *table, const LgpKeep
 {
     const dim3 grid(n_groups), block(kBlock);
     const int variant = (ctx->weighted ? 2 : 0) | (ctx->element_keys ? 1 : 0);
-    const unsigned lds = occupancy_lds(wave_bytes(ctx->n_workers, sizeof(GT), 1), kKeepLoadsInFlightPerCu);
+    // (counted on the (N + 1) KB a wavefront stores, whatever the gradients' type)
+    const unsigned lds = occupancy_lds(wave_bytes(ctx->n_workers, sizeof(float), 1), kKeepStoresInFlightPerCu);
     switch (variant) {
     case 0: k_lgp_keep<false, false, GT><<<grid, block, lds, s>>>(table, a); break;
     case 1: k_lgp_keep<false, true, GT><<<grid, block, lds, s>>>(table, a); break;
@@ -1512,7 +1523,7 @@ static osp_status ics_window(osp_ctx *ctx, const void *grads, int64_t worker_str
             a.mu = ctx->mu;
             const dim3 grid((unsigned)ctx->spans.size() * kSpanChunks), block(kBlock);
             // (N + 2) KB of stores per wavefront; bounded like the loads of the RS window
-            const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(float), 2), kLoadsInFlightPerCu);
+            const unsigned lds = occupancy_lds(wave_bytes(N, sizeof(float), 2), kWindowBytesInFlightPerCu);
             if (from_stash)
                 k_ics_window_element<true, false><<<grid, block, lds, s>>>(a);
             else if (bf16 && ctx->weighted)
