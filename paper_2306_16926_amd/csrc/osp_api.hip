@@ -1953,8 +1953,11 @@ osp_status osp_stream_pattern(const float *reads, int32_t n_read, int64_t read_s
     const long long groups = (a.n_vec + kBlock - 1) / kBlock;
     if (groups > 0x7FFFFFFFLL)
         return OSP_ERR_INVALID_ARG;
-    if (groups > 0)
-        k_stream_pattern<<<(unsigned)groups, kBlock, 0, (hipStream_t)stream>>>(a);
+    if (groups > 0) {
+        // bounded like the aggregate whose traffic it stands for
+        const unsigned lds = occupancy_lds(wave_bytes(n_read, sizeof(float), n_rw), kLoadsInFlightPerCu);
+        k_stream_pattern<<<(unsigned)groups, kBlock, lds, (hipStream_t)stream>>>(a);
+    }
     return hipGetLastError() == hipSuccess ? OSP_OK : OSP_ERR_HIP;
 }
 
