@@ -428,7 +428,7 @@ def main() -> int:
     wl = W.get(args.workload)
     element = args.granularity == "element"
     N, M = wl.n_workers, wl.n_params
-    arena, stride = wl.arena_elems(), wl.worker_stride()
+    arena, stride, pstride = wl.arena_elems(), wl.worker_stride(), wl.replica_stride()
     K, Wm = args.steps, args.warmup
     bf16 = args.grad_dtype == "bf16"
     keep_on = args.keep_stage2_aggregate == "on"
@@ -444,7 +444,7 @@ def main() -> int:
     # two gradient sets, alternated, so a step never re-reads what the last one left in cache
     host_sets = [wl.make_grads(args.seed, s, stride=stride, threads=args.gen_threads) for s in (0, 1)]
     job = DeviceJob(wl.numel, wl.offsets(), arena, N, wl.lr, wl.momentum, params,
-                    element_keys=element, chunk_elems=args.chunk_elems, param_stride=stride)
+                    element_keys=element, chunk_elems=args.chunk_elems, param_stride=pstride)
     if bf16:                                    # rounded once, on the host; the oracle gets the widened values
         halves = [W.to_bf16(h) for h in host_sets]
         host_sets = [W.from_bf16(h) for h in halves]
@@ -470,7 +470,7 @@ def main() -> int:
         del job
         torch.cuda.empty_cache()
         job = DeviceJob(wl.numel, wl.offsets(), arena, N, wl.lr, wl.momentum, params,
-                        element_keys=True, chunk_elems=args.chunk_elems, param_stride=stride)
+                        element_keys=True, chunk_elems=args.chunk_elems, param_stride=pstride)
         eleg = run_leg(torch, wl, job, gsets, True, "windows", args.element_steps, 3, False, False,
                        True, log)
         log(f"element leg: {eleg['ms_per_step']:.4f} ms per step")
@@ -549,7 +549,7 @@ def cpu_baseline(wl, params, host_sets, job, history, element, stride, log, base
 
     def chain(omp, steps, budget_s=None):
         o = OracleOSP(wl.numel, wl.offsets(), wl.arena_elems(), N, wl.lr, wl.momentum,
-                      param_stride=stride, omp=omp)
+                      param_stride=wl.replica_stride(), omp=omp)
         o.load_params(params)
         o.set_gib(0, all1)
         times = []

@@ -81,11 +81,11 @@ def test_resnet18_shaped_other_seeds(seed, gran):
 def full_size_steps(name, steps, windows=False):
     from paper_2306_16926_amd.device import DeviceJob
     wl = W.get(name)
-    stride = wl.worker_stride()
+    stride, pstride = wl.worker_stride(), wl.replica_stride()     # as bench.py lays them out
     arena = wl.arena_elems()
-    o = make_oracle(wl, omp=True, param_stride=stride)
+    o = make_oracle(wl, omp=True, param_stride=pstride)
     job = DeviceJob(wl.numel, wl.offsets(), arena, wl.n_workers, wl.lr, wl.momentum,
-                    wl.make_params(0), param_stride=stride)
+                    wl.make_params(0), param_stride=pstride)
     all1 = np.ones(wl.n_tensors, np.uint8)
     o.set_gib(GRAN_LAYER, all1); job.ctx.osp_set_gib(GRAN_LAYER, all1)
     sizes = []
@@ -155,10 +155,10 @@ def full_size_element(name):
     that sort."""
     from paper_2306_16926_amd.device import DeviceJob
     wl = W.get(name)
-    stride, arena = wl.worker_stride(), wl.arena_elems()
-    o = make_oracle(wl, omp=True, param_stride=stride)
+    stride, pstride, arena = wl.worker_stride(), wl.replica_stride(), wl.arena_elems()
+    o = make_oracle(wl, omp=True, param_stride=pstride)
     job = DeviceJob(wl.numel, wl.offsets(), arena, wl.n_workers, wl.lr, wl.momentum,
-                    wl.make_params(0), element_keys=True, param_stride=stride)
+                    wl.make_params(0), element_keys=True, param_stride=pstride)
     c = job.ctx
     real = brute.real_mask(wl.numel, wl.offsets(), arena)
     k = wl.budget

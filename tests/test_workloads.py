@@ -14,6 +14,7 @@ def test_counts(name):
     ends = off + np.asarray(wl.numel)
     assert (off[1:] >= ends[:-1]).all() and ends[-1] <= wl.arena_elems()
     assert wl.worker_stride() >= wl.arena_elems() and wl.worker_stride() % 4 == 0
+    assert wl.replica_stride() >= wl.arena_elems() and wl.replica_stride() % 4 == 0
 
 
 def test_seeded_and_distinct():
