@@ -38,7 +38,9 @@
  *   bytes in flight move faster), and it is not available to other kernels on
  *   that compute unit meanwhile.  Gradient arenas that are a multiple of 1 MiB
  *   plus 4 to 32 KiB apart (worker_stride) measure 1-3 % faster in these
- *   kernels than arenas 4 KiB + 768 B apart.
+ *   kernels than arenas 4 KiB + 768 B apart, and replicas a multiple of 1 KiB
+ *   apart (param_stride; say a multiple of 1 MiB plus 1 KiB) 1-3 % faster than
+ *   replicas that are not.
  *
  * Concurrency
  *   The calls of one context update shared buffers and must not overlap in

@@ -195,21 +195,23 @@ class Workload:
         end = int(off[-1] + self.numel[-1])
         return -(-end // a) * a
 
+    def _stride(self, align: int | None, pad: int) -> int:
+        m = self.arena_elems(align)
+        unit = (1 << 18) if m >= (1 << 20) else 1024          # 1 MiB, or 4 KiB for small arenas
+        return -(-m // unit) * unit + pad
+
     def replica_stride(self, align: int | None = None) -> int:
         """Distance in elements between consecutive workers' parameter replicas: the arena
-        rounded up to 4 KiB plus one odd multiple of 256 B (a replica stride that is a multiple
-        of 8 MiB measured 5 % slower on the install)."""
-        m = self.arena_elems(align)
-        return -(-m // 1024) * 1024 + 3 * 64
+        rounded up to 1 MiB, plus 1 KiB.  Measured on MI355X: rows that are not a multiple of
+        1 KiB apart (the earlier 4 KiB + 768 B) cost the kernels that write all N replicas from
+        one wavefront 1.5-3 %; an exact multiple of 8 MiB costs the install 5 %."""
+        return self._stride(align, 256)
 
     def worker_stride(self, align: int | None = None) -> int:
         """Distance in elements between consecutive workers' gradient arenas: the arena rounded
-        up to 1 MiB plus 8 KiB (measured on MI355X against 4 KiB + 768 B: the kernels that read
-        all N arenas at once 1-3 % faster); small arenas as the replicas."""
-        m = self.arena_elems(align)
-        if m < (1 << 20):
-            return self.replica_stride(align)
-        return -(-m // (1 << 18)) * (1 << 18) + 2048
+        up to 1 MiB, plus 8 KiB (measured against 4 KiB + 768 B: the kernels that read all N
+        arenas at once 1-3 % faster; +4 KiB to +32 KiB measure the same)."""
+        return self._stride(align, 2048)
 
     # ---- seeded inputs ---------------------------------------------------
     def _rng(self, seed: int, *path: int) -> np.random.Generator:
