@@ -119,7 +119,9 @@ typedef struct {
     float *ps_momentum;            /* [arena_elems] momentum buffer V on the PS */
     float *worker_param;           /* worker w's replica starts at worker_param + w*stride */
     int64_t worker_param_stride;   /* elements, multiple of 4, >= arena_elems */
-    void *workspace;               /* 256-byte aligned scratch, >= osp_workspace_bytes() */
+    void *workspace;               /* 256-byte aligned scratch, >= osp_workspace_bytes();
+                                      4 KiB alignment lets its arena-sized arrays start on
+                                      4 KiB boundaries like the arenas' tensors */
     size_t workspace_bytes;
     int32_t replicas_in_sync;      /* nonzero: the caller asserts that every replica equals
                                       ps_param on every tensor element right now.  Lets the

@@ -180,6 +180,13 @@ void layout_workspace(osp_ctx *c)
         o = align_up(o + bytes);
         return at;
     };
+    // The arena-sized arrays start on 4 KiB boundaries of the workspace (tensor offsets are
+    // multiples of 4 KiB in the measured layouts): the 1 KiB a wavefront loads or stores is
+    // then one aligned piece of them, as it is of the caller's arenas.
+    auto take_arena = [&](size_t bytes) {
+        o = (o + 4095) / 4096 * 4096;
+        return take(bytes);
+    };
     const size_t nc = (size_t)c->n_chunks, ns = c->spans.size();
     c->off_spans = take(ns * sizeof(Span));
     c->off_slayer = take(ns * sizeof(int));
@@ -189,7 +196,7 @@ void layout_workspace(osp_ctx *c)
     c->off_lsb = take((size_t)(c->n_tensors + 1) * sizeof(int));
     c->off_big = take((size_t)(c->big_layers.size() + 1) * sizeof(int));
     c->off_lists = take(4 * ns * sizeof(Span));
-    c->off_partial = take(2 * nc * sizeof(double));
+    c->off_partial = take_arena(2 * nc * sizeof(double));
     c->off_segsum = take(c->segments.size() * sizeof(double));
     c->off_imp = take((size_t)c->n_tensors * sizeof(double));
     c->off_order = take((size_t)c->n_tensors * sizeof(int));
@@ -199,10 +206,10 @@ void layout_workspace(osp_ctx *c)
     c->off_state = take(sizeof(SplitState));
     c->off_weights = take((size_t)c->n_workers * sizeof(float));
     c->off_pack = take((2 * (nc + 1) + 2 * (size_t)c->n_pack_blocks()) * sizeof(long long));
-    c->off_stash = take((size_t)c->arena * sizeof(float));
+    c->off_stash = take_arena((size_t)c->arena * sizeof(float));
     if (c->element_keys) {
-        c->off_key = take((size_t)c->arena * sizeof(uint32_t));
-        c->off_bitmap = take((size_t)c->n_words * sizeof(uint32_t));
+        c->off_key = take_arena((size_t)c->arena * sizeof(uint32_t));
+        c->off_bitmap = take_arena((size_t)c->n_words * sizeof(uint32_t));
         // three histograms, then the length of the tie-candidate list (zero between splits)
         c->off_hist = take(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long));
         c->off_cand = take((size_t)kTieCandidates * sizeof(TieCandidate));
