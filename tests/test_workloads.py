@@ -15,6 +15,11 @@ def test_counts(name):
     assert (off[1:] >= ends[:-1]).all() and ends[-1] <= wl.arena_elems()
     assert wl.worker_stride() >= wl.arena_elems() and wl.worker_stride() % 4 == 0
     assert wl.replica_stride() >= wl.arena_elems() and wl.replica_stride() % 4 == 0
+    # the measured layout: rows a multiple of 1 KiB apart, gradient rows 8 KiB past a round
+    # number, replica rows 1 KiB past it and never a multiple of 8 MiB
+    assert wl.replica_stride() % 256 == 0 and wl.worker_stride() % 256 == 0
+    assert wl.worker_stride() % 1024 == 0 and wl.replica_stride() % 1024 == 256
+    assert (wl.replica_stride() * 4) % (8 << 20) != 0
 
 
 def test_seeded_and_distinct():
