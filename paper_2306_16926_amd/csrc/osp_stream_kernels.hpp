@@ -476,7 +476,7 @@ __global__ __launch_bounds__(kBlock) void k_update_from_stash(const Span *__rest
 //
 //  * sweep (N > 4): writing all N from one workgroup keeps 16+ DRAM write
 //    streams open at once (measured 5.7 TB/s at N = 16).  Instead the table is
-//    cut into blocks of about 8 MB of parameters and, block after block, the GPU
+//    cut into blocks of about 16 MB of parameters and, block after block, the GPU
 //    writes one replica at a time: the parameter block is read from HBM once and
 //    served from cache to the other N-1 sweeps, and the writes form a single
 //    stream.  Workgroups of 256 lanes: with one wavefront per KiB the launch
