@@ -105,7 +105,10 @@ def moved_bytes(N, M, E2, element, gb, lgp_shared, lgp_kept, fused_rs, fused_ics
         b["lgp"] = ((gb + 4) * N + 4) * M + bm if lgp_shared else (8 + gb) * N * M + bm
         b["agg2"] = 20 * M + bm                          # from the kept aggregate
         b["apply2"] = 4 * (N + 1) * M
-        b["split"] = 3 * 4 * M + bm                      # two histogram passes + the bitmap pass
+        # one histogram pass + the bitmap pass: the first pass also counts the second digit
+        # under the previous split's first digit, and in a run of steps that guess holds (a
+        # step whose threshold leaves that bucket reads the keys a third time)
+        b["split"] = 2 * 4 * M + bm
         b["rs_window"] = ((gb * N + 8) * M + bm + (16 + 4 * N) * M if fused_rs
                           else b["agg1"] + b["apply1"] + b["lgp"])
         b["ics_window"] = (12 * M + bm + (8 + 4 * N) * M if fused_ics

@@ -137,7 +137,7 @@ struct osp_ctx {
     {
         return at<unsigned long long>(off_hist) + (size_t)pass * kRadixBins;
     }
-    unsigned int *d_n_cand() const { return reinterpret_cast<unsigned int *>(d_hist(3)); }
+    unsigned int *d_n_cand() const { return reinterpret_cast<unsigned int *>(d_hist(kSelectHistograms)); }
     TieCandidate *d_cand() const { return at<TieCandidate>(off_cand); }
     unsigned int *d_tile_ties() const { return at<unsigned int>(off_tile_ties); }
 };
@@ -210,8 +210,8 @@ void layout_workspace(osp_ctx *c)
     if (c->element_keys) {
         c->off_key = take_arena((size_t)c->arena * sizeof(uint32_t));
         c->off_bitmap = take_arena((size_t)c->n_words * sizeof(uint32_t));
-        // three histograms, then the length of the tie-candidate list (zero between splits)
-        c->off_hist = take(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long));
+        // four histograms, then the length of the tie-candidate list (zero between splits)
+        c->off_hist = take(((size_t)kSelectHistograms * kRadixBins + 1) * sizeof(unsigned long long));
         c->off_cand = take((size_t)kTieCandidates * sizeof(TieCandidate));
         c->off_tile_ties = take((size_t)c->n_tiles * sizeof(unsigned int));
     }
@@ -510,7 +510,7 @@ static void launch_lgp_keep(const osp_ctx *ctx, const Span *table, const LgpKeep
 
 // The launches of one element-granular selection: `budget` smallest keys in the order
 // (key, index) -> bitmap.  Everything but `key` and `bitmap` is scratch: the split state,
-// hist = (3 * kRadixBins + 1) counters of 8 bytes (three histograms, then the length of the
+// hist = (4 * kRadixBins + 1) counters of 8 bytes (four histograms, then the length of the
 // candidate list; all zero on entry and left zero), the candidate list, the per-tile tie
 // counts.
 struct SelectScratch {
@@ -525,19 +525,20 @@ static void enqueue_element_select(const uint32_t *key, long long n_vec, long lo
                                    uint32_t *bitmap, hipStream_t s)
 {
     unsigned long long *h0 = w.hist, *h1 = w.hist + kRadixBins, *h2 = w.hist + 2 * kRadixBins;
-    unsigned int *n_cand = reinterpret_cast<unsigned int *>(w.hist + 3 * kRadixBins);
+    unsigned long long *hg = w.hist + 3 * kRadixBins;      // the second digit under the guessed first
+    unsigned int *n_cand = reinterpret_cast<unsigned int *>(w.hist + kSelectHistograms * kRadixBins);
     // histogram passes: few, large workgroups (see select_histogram)
     const long long per_wg = (long long)kHistBlock * kHistVecPerThread;
     long long want = (n_vec + per_wg - 1) / per_wg;
     const unsigned hist_grid = (unsigned)(want < kHistMaxGrid ? (want < 1 ? 1 : want) : kHistMaxGrid);
     // the tile passes walk their tiles in rounds of the grid: their prologue is paid per workgroup
     const unsigned tgrid = (unsigned)(n_tiles < 8192 ? (n_tiles < 1 ? 1 : n_tiles) : 8192);
-    k_select_histogram0<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h0);
+    k_select_histogram0<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h0, hg);
     k_select_histogram1<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h0, h1);
     k_select_bitmap<<<tgrid, kSplitBlock, 0, s>>>(key, n_vec, n_words, n_tiles, budget, w.state, h0, h1,
-                                                 w.cand, n_cand, bitmap);
-    k_select_finish<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h1, h2, w.cand, n_cand,
-                                                    bitmap);
+                                                 hg, w.cand, n_cand, bitmap);
+    k_select_finish<<<hist_grid, kHistBlock, 0, s>>>(key, n_vec, budget, w.state, h1, hg, h2, w.cand,
+                                                    n_cand, bitmap);
     // (the last two return at once unless many keys share the threshold's upper 22 bits:
     // small grids, so that returning costs little)
     const unsigned fgrid = tgrid < 1024 ? tgrid : 1024;
@@ -553,12 +554,12 @@ static void enqueue_element_select(const uint32_t *key, long long n_vec, long lo
 // ---------------------------------------------------------------------------
 constexpr long long kStaticMaxElems = 1LL << 28;
 constexpr size_t kStaticOffHist = 256;                                   // SplitState first
-constexpr size_t kStaticOffCand = kStaticOffHist + 49408;                // (3 * 2048 + 1) * 8, rounded up
+constexpr size_t kStaticOffCand = kStaticOffHist + 65792;                // (4 * 2048 + 1) * 8, rounded up
 constexpr size_t kStaticOffTies = kStaticOffCand + (size_t)kTieCandidates * sizeof(TieCandidate);
 constexpr size_t kStaticTiles = (size_t)(kStaticMaxElems / kSelTile);
 constexpr size_t kStaticScratchBytes = kStaticOffTies + kStaticTiles * sizeof(unsigned int);
 static_assert(sizeof(SplitState) <= kStaticOffHist, "state fits in front of the histograms");
-static_assert(((size_t)3 * kRadixBins + 1) * sizeof(unsigned long long) <= kStaticOffCand - kStaticOffHist,
+static_assert(((size_t)kSelectHistograms * kRadixBins + 1) * sizeof(unsigned long long) <= kStaticOffCand - kStaticOffHist,
               "histograms fit");
 static_assert(kStaticOffCand % 256 == 0 && kStaticOffTies % 256 == 0,
               "every part starts on a 256-byte boundary");
@@ -812,7 +813,7 @@ osp_status osp_bind(osp_ctx *ctx, const osp_buffers *buf, void *stream)
         k_fill_u32<<<256, kSplitBlock, 0, s>>>(ctx->d_bitmap(), ctx->n_words, 0xFFFFFFFFu);
         // histograms and the candidate count start at zero; every split leaves them so
         k_fill_u32<<<24, kSplitBlock, 0, s>>>(reinterpret_cast<uint32_t *>(ctx->d_hist(0)),
-                                             (long long)(3 * kRadixBins + 1) * 2, 0u);
+                                             (long long)(kSelectHistograms * kRadixBins + 1) * 2, 0u);
     }
     osp_status st = launch_check(ctx, "bind fill kernels");
     if (st != OSP_OK)

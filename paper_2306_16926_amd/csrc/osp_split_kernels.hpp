@@ -56,6 +56,8 @@ struct SplitState {                    // one per context, in the workspace
     unsigned int all_ties;             // 1: every key equal to T is taken
     unsigned int collect;              // 1: few keys share the threshold's 22-bit prefix; the bitmap
                                        // pass lists them and one workgroup decides among them
+    unsigned int next_guess;           // 1 + the first digit of the last split's threshold (0: none):
+                                       // the bucket the next split's first pass refines on spec
     unsigned int layer_ticket;         // workgroups of k_layer_split_lds that have summed their segments
     long long *log;                    // caller's log of stage-2 sizes, or null (osp_set_stage2_log)
     long long log_cap;
@@ -839,6 +841,7 @@ __global__ __launch_bounds__(kSplitBlock) void k_stage_lists(
 // one that read it.  Integer arithmetic only.
 // ---------------------------------------------------------------------------
 constexpr int kRadixBins = 2048;
+constexpr int kSelectHistograms = 4;   // three digits, and the second digit under a guessed first one
 // pass 0: bits 31..21, pass 1: bits 20..10, pass 2: bits 9..0
 __device__ __forceinline__ constexpr int radix_shift(int pass) { return pass == 0 ? 21 : (pass == 1 ? 10 : 0); }
 __device__ __forceinline__ constexpr int radix_bits(int pass) { return pass == 2 ? 10 : 11; }
@@ -981,14 +984,26 @@ constexpr int kHistBlock = 1024;
 constexpr int kHistVecPerThread = 16;  // 16-byte groups a thread reads (when the grid is not capped)
 constexpr int kHistMaxGrid = 512;
 
-template <int PASS, int BLOCK>
+//
+// SPEC (first pass only): the threshold's first digit rarely moves from one iteration to the
+// next, so the pass also counts the second digit of the keys whose first digit is `guess`, into
+// hist_guess.  If the guess turns out right that is the second pass's histogram, and the second
+// pass over the keys is not made.
+template <int PASS, int BLOCK, bool SPEC = false>
 __device__ __forceinline__ void select_histogram(const uint32_t *__restrict__ key, long long n_vec,
                                                  unsigned prefix,
-                                                 unsigned long long *__restrict__ hist)
+                                                 unsigned long long *__restrict__ hist,
+                                                 unsigned guess = 0,
+                                                 unsigned long long *__restrict__ hist_guess = nullptr)
 {
+    static_assert(!SPEC || PASS == 0, "only the first pass guesses");
     __shared__ unsigned int h[kRadixBins];
-    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK)
+    __shared__ unsigned int hg[SPEC ? kRadixBins : 1];
+    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK) {
         h[b] = 0;
+        if (SPEC)
+            hg[b] = 0;
+    }
     __syncthreads();
     constexpr int shift = radix_shift(PASS);
     constexpr unsigned mask = (1u << radix_bits(PASS)) - 1u;
@@ -1028,19 +1043,32 @@ __device__ __forceinline__ void select_histogram(const uint32_t *__restrict__ ke
                     if (in[j])
                         atomicAdd(&h[bin[j]], 1u);
             }
+            if (SPEC) {
+                constexpr int shift1 = radix_shift(1);
+                constexpr unsigned mask1 = (1u << radix_bits(1)) - 1u;
+#pragma unroll
+                for (int j = 0; j < kVec; ++j)
+                    if (bin[j] == guess)
+                        atomicAdd(&hg[(k[u][j] >> shift1) & mask1], 1u);
+            }
         }
     }
     __syncthreads();
-    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK)
+    for (int b = threadIdx.x; b < kRadixBins; b += BLOCK) {
         if (h[b])
             atomicAdd(&hist[b], (unsigned long long)h[b]);
+        if (SPEC && hg[b])
+            atomicAdd(&hist_guess[b], (unsigned long long)hg[b]);
+    }
 }
 
 // Launch 1: the top 11 bits.
 __global__ __launch_bounds__(kHistBlock) void k_select_histogram0(
     const uint32_t *__restrict__ key, long long n_vec, long long budget,
-    SplitState *__restrict__ st, unsigned long long *__restrict__ hist0)
+    SplitState *__restrict__ st, unsigned long long *__restrict__ hist0,
+    unsigned long long *__restrict__ hist_guess)
 {
+    const unsigned next_guess = st->next_guess;      // (written by the last split's launch 4 only)
     if (blockIdx.x == 0 && threadIdx.x == 0) {
         st->n_stage2 = budget;
         log_stage2(st, budget);
@@ -1052,7 +1080,10 @@ __global__ __launch_bounds__(kHistBlock) void k_select_histogram0(
             st->collect = 0;
         }
     }
-    select_histogram<0, kHistBlock>(key, n_vec, 0u, hist0);
+    if (next_guess != 0 && budget != 0)
+        select_histogram<0, kHistBlock, true>(key, n_vec, 0u, hist0, next_guess - 1u, hist_guess);
+    else
+        select_histogram<0, kHistBlock>(key, n_vec, 0u, hist0);
 }
 
 // Launch 2: the next 11 bits inside the bucket the first histogram points to.
@@ -1067,6 +1098,8 @@ __global__ __launch_bounds__(kHistBlock) void k_select_histogram1(
     record_pick<0>(st, p0);
     if (!p0.ok)
         return;
+    if (st->next_guess == p0.prefix + 1u)
+        return;                        // launch 1 guessed this bucket: its histogram is there already
     select_histogram<1, kHistBlock>(key, n_vec, p0.prefix, hist1);
 }
 
@@ -1100,14 +1133,16 @@ __device__ __forceinline__ void store_bitmap_word(unsigned sel, long long v, lon
 __global__ __launch_bounds__(kSplitBlock) void k_select_bitmap(
     const uint32_t *__restrict__ key, long long n_vec, long long n_words, long long n_tiles,
     long long budget, SplitState *__restrict__ st, unsigned long long *__restrict__ hist0,
-    const unsigned long long *__restrict__ hist1, TieCandidate *__restrict__ cand,
-    unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
+    const unsigned long long *__restrict__ hist1, const unsigned long long *__restrict__ hist_guess,
+    TieCandidate *__restrict__ cand, unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
 {
     bool none = budget == 0;
     bool collect = false;
     unsigned P = 0;
     if (!none) {
-        const Picked p1 = pick_bucket<1>(budget, hist1, st);
+        // (launch 1 guessed the bucket launch 2 found: the second digit's counts are in hist_guess)
+        const bool guessed = st->next_guess == st->prefix[0] + 1u;
+        const Picked p1 = pick_bucket<1>(budget, guessed ? hist_guess : hist1, st);
         record_pick<1>(st, p1);
         none = !p1.ok;                 // (cannot happen)
         collect = p1.count <= kTieCandidates;
@@ -1158,11 +1193,17 @@ constexpr int kIndexDigit = 11;        // arena indices are cut by four digits o
 __global__ __launch_bounds__(kHistBlock) void k_select_finish(
     const uint32_t *__restrict__ key, long long n_vec, long long budget,
     SplitState *__restrict__ st, unsigned long long *__restrict__ hist1,
-    unsigned long long *__restrict__ hist2, const TieCandidate *__restrict__ cand,
-    unsigned int *__restrict__ n_cand, uint32_t *__restrict__ bitmap)
+    unsigned long long *__restrict__ hist_guess, unsigned long long *__restrict__ hist2,
+    const TieCandidate *__restrict__ cand, unsigned int *__restrict__ n_cand,
+    uint32_t *__restrict__ bitmap)
 {
-    if (blockIdx.x == gridDim.x - 1)
-        zero_histogram(hist1);         // (read by launch 3 only)
+    if (blockIdx.x == gridDim.x - 1) {
+        zero_histogram(hist1);         // (both read by launch 3 only)
+        zero_histogram(hist_guess);
+        // the next split's guess; launches 1 to 3 of this one, which read the old one, are done
+        if (threadIdx.x == 0 && budget != 0)
+            st->next_guess = st->prefix[0] + 1u;
+    }
     if (budget == 0)
         return;
     const unsigned P = st->prefix[1];

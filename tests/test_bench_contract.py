@@ -60,7 +60,7 @@ def test_element_windows_move_one_pass_each():
     N, M, E2 = 16, 3200, 1600
     mv = bench.moved_bytes(N, M, E2, True, 4, True, False, True, False)
     assert mv["rs_window"] == (4 * N + 8) * M + M // 8 + (16 + 4 * N) * M
-    assert mv["ics_window"] == (20 * M + M // 8) + 4 * (N + 1) * M + (12 * M + M // 8)
+    assert mv["ics_window"] == (20 * M + M // 8) + 4 * (N + 1) * M + (8 * M + M // 8)
 
 
 def test_more_than_one_gpu_is_refused_with_a_message():

@@ -560,6 +560,34 @@ def test_split_element_adversarial(case):
     _split_from_keys(keys, k, numel)
 
 
+def test_split_element_guess_of_the_first_digit():
+    """The first radix pass also refines the bucket the previous split's threshold fell into.
+    Splits in a row on one context: budgets that keep the threshold in its bucket (the guess
+    is right and the second pass is skipped), budgets and keys that move it (the guess is
+    wrong and the second pass is made), budget 0 in between; every GIB against the oracle."""
+    say("element split: guessed first digit")
+    rng = np.random.default_rng(11)
+    n = 300_000                                  # several histogram workgroups, ragged tail
+    wl = W.custom([n - 7, 3, 4], 1, align=4, config_id=33)
+    arena, off = wl.arena_elems(), wl.offsets()
+    real = brute.real_mask(wl.numel, off, arena)
+    P = np.zeros(arena, F); P[real] = 1.0
+    o = OracleOSP(wl.numel, off, arena, 1, 0.0, 0.0); o.load_params(P)     # lr 0: P stays 1
+    job = device_job(wl, element_keys=True, lr=0.0, mu=0.0, params=P)
+    narrow = (1.0 + rng.random(n)).astype(F)                    # one binade: 4 first digits
+    wide = (10.0 ** rng.uniform(-6, 2, n)).astype(F)            # many binades
+    rounds = [(narrow, n // 2), (narrow, n // 2 + 11), (narrow, n // 2 - 5000), (narrow, 17),
+              (narrow, n // 2), (wide, n // 2), (wide, n // 2 + 1), (wide, 0), (wide, n // 2),
+              (narrow, n - 3), (narrow, n), (narrow, n // 2)]
+    for r, (vals, k) in enumerate(rounds):
+        g = np.zeros((1, arena), F); g[0, real] = vals
+        gd = job.upload_grads(g)
+        o.ps_aggregate_update(0, g); job.ctx.osp_ps_aggregate_update(0, gd, arena)
+        o.split(GRAN_ELEMENT, k); job.ctx.osp_split(GRAN_ELEMENT, k)
+        compare_gib(job, o, f"round {r}, budget {k}")
+        assert np.array_equal(job.ctx.osp_get_keys()[real], o.keys()[real])
+
+
 @pytest.mark.parametrize("ties,take", [(3000, 1234), (5, 2), (70_000, 69_999)])
 def test_split_element_ties_cut_at_large_indices(ties, take):
     """Ties at the threshold spread over 8.4 M keys: the cut by arena index works through its
